@@ -1,0 +1,355 @@
+"""Pins for the CPU oracle: values the paper prints, closed forms, brute force on tiny inputs.
+
+Each check is written independently of oracle/dllava_ref.py (pure-Python loops, a different
+formulation of the same definition, or a printed number), so that a dropped term, a wrong sign or
+index, or a transposed operand in the oracle fails at least one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import dllava_ref as R
+from synth import workloads as W
+from synth import rng
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+# ------------------------------------------------------------------ printed numbers (Table 1, Eq. 11, Eq. 13)
+
+def test_keep_count_matches_printed_token_counts():
+    for n, r, k in _rows("keep_counts.txt"):
+        assert R.keep_count(float(r), int(n)) == int(k)
+
+
+def test_eq13_reproduces_table1_tflops():
+    for model, C, L, method, after, tokens, printed in _rows("table1_image_prefill.txt"):
+        got = R.model_prefill_tflops(576, int(tokens), int(C), int(L), int(after))
+        assert abs(got - float(printed)) <= 0.05 + 1e-9, (model, method, got, printed)
+    # the printed 2.5 / 4.7 need BOTH l = 2 dense layers and k = 115: neighbours miss the rounding window
+    assert round(R.model_prefill_tflops(576, 115, 4096, 32, 2), 1) == 2.5
+    assert round(R.model_prefill_tflops(576, 115, 4096, 32, 0), 1) != 2.5
+    assert round(R.model_prefill_tflops(576, 115, 5120, 40, 2), 1) == 4.7
+    assert round(R.model_prefill_tflops(576, 115, 5120, 40, 4), 1) != 4.7
+
+
+# ------------------------------------------------------------------ predictor
+
+def _score_loops(x, W1, b1, W2, b2):
+    M, d = x.shape
+    dh = W1.shape[0]
+    D = np.zeros((M, 2))
+    for i in range(M):
+        h = []
+        for j in range(dh):
+            a = float(b1[j])
+            for c in range(d):
+                a += float(x[i, c]) * float(W1[j, c])
+            h.append(0.5 * a * (1.0 + math.erf(a / math.sqrt(2.0))))
+        for o in range(2):
+            D[i, o] = float(b2[o]) + sum(h[j] * float(W2[o, j]) for j in range(dh))
+    return D
+
+
+def test_gelu_closed_form_values():
+    # GELU(a) = a * Phi(a); Phi(1) = 0.8413447460685429, Phi(-1) = 1 - Phi(1), Phi(2) = 0.9772498680518208
+    a = np.array([0.0, 1.0, -1.0, 2.0, 40.0, -40.0])
+    g = R.gelu(a)
+    exp = [0.0, 0.8413447460685429, -(1 - 0.8413447460685429), 2 * 0.9772498680518208, 40.0, 0.0]
+    assert np.allclose(g, exp, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_score_vs_triple_loop(dtype):
+    M, d, dh = 5, 12, 7
+    x = W.store(rng.normal(11, "x", (M, d)), dtype)
+    W1 = W.store(rng.normal(11, "W1", (dh, d)) * 0.5, dtype)
+    W2 = W.store(rng.normal(11, "W2", (2, dh)), dtype)
+    b1 = rng.normal(11, "b1", (dh,))
+    b2 = rng.normal(11, "b2", (2,))
+    ref = _score_loops(W.stored_to_f32(x, dtype), W.stored_to_f32(W1, dtype), b1,
+                       W.stored_to_f32(W2, dtype), b2)
+    got = R.score(x, W1, b1, W2, b2, dtype)
+    assert got.dtype == np.float32 and got.shape == (M, 2)
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6)
+    # columns are not interchangeable and W1 is used as [dh, d] (not transposed)
+    assert not np.allclose(got[:, 0], got[:, 1])
+
+
+def test_score_special_cases():
+    M, d, dh = 4, 8, 6
+    x = rng.normal(3, "x", (M, d))
+    W2 = rng.normal(3, "W2", (2, dh))
+    b1 = rng.normal(3, "b1", (dh,))
+    b2 = np.array([0.25, -0.5], np.float32)
+    # zero first layer: D = b2 + GELU(b1) W2^T for every row
+    D = R.score(x, np.zeros((dh, d), np.float32), b1, W2, b2, "f32")
+    g = np.array([0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in b1.astype(np.float64)])
+    exp = b2.astype(np.float64) + W2.astype(np.float64) @ g
+    assert np.allclose(D, np.tile(exp, (M, 1)), atol=1e-6)
+    # W2 = [0; e_j] picks hidden unit j into the keep column, nothing into the drop column
+    W1 = rng.normal(3, "W1", (dh, d))
+    E = np.zeros((2, dh), np.float32)
+    E[1, 2] = 1.0
+    D = R.score(x, W1, None, E, None, "f32")
+    a = x.astype(np.float64) @ W1.astype(np.float64)[2]
+    assert np.allclose(D[:, 0], 0.0)
+    assert np.allclose(D[:, 1], [0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in a], atol=1e-6)
+
+
+# ------------------------------------------------------------------ selection
+
+def _topk_rank_count(s, k):
+    """Definition by counting: token i is kept iff fewer than k tokens beat it."""
+    n = len(s)
+
+    def beats(j, i):           # j ranks strictly ahead of i
+        a, b = float(s[j]), float(s[i])
+        an, bn = a != a, b != b
+        if an or bn:
+            if an and bn:
+                return j < i
+            return bn          # a number beats NaN
+        if a != b:
+            return a > b
+        return j < i
+    return np.array([i for i in range(n) if sum(beats(j, i) for j in range(n) if j != i) < k], np.int32)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_topk_equals_rank_count_with_ties(seed):
+    n = 37
+    s = rng.normal(seed, "s", (n,))
+    s = np.round(s * 2) / 2            # many exact ties
+    s[3] = 0.0
+    s[9] = -0.0
+    if seed % 2:
+        s[5] = np.nan
+        s[20] = np.nan
+        s[7] = np.inf
+        s[8] = -np.inf
+    for k in (0, 1, 5, 17, n - 1, n, n + 3):
+        got = R.select_topk(s, k)
+        exp = _topk_rank_count(s, min(k, n))
+        assert np.array_equal(got, exp), (seed, k)
+        assert len(got) == min(k, n) and np.all(np.diff(got) > 0)
+
+
+def test_topk_tie_goes_to_lower_index():
+    s = np.array([1.0, 2.0, 2.0, 2.0, 0.5], np.float32)
+    assert list(R.select_topk(s, 2)) == [1, 2]
+    assert list(R.select_topk(np.array([0.0, -0.0, 0.0], np.float32), 2)) == [0, 1]
+
+
+def test_threshold_is_strict_argmax_rule():
+    D = np.array([[0.0, 1.0], [1.0, 0.0], [0.5, 0.5], [-1.0, -0.5]], np.float32)
+    assert list(R.select_threshold(D, 0.0)) == [1, 0, 0, 1]          # tie -> drop (Eq. 5: "greater than")
+    assert list(R.select_threshold(D, -np.inf)) == [1, 1, 1, 1]
+    assert list(R.select_threshold(D, np.inf)) == [0, 0, 0, 0]
+    assert list(R.select_threshold(D, 0.5)) == [1, 0, 0, 0]
+
+
+def _ragged():
+    return W.make("ragged", "bf16", 32, 2, 16, 3, [3, 0, 5], [20, 33, 7], [4, 9, 0], 0.3, 6)
+
+
+def test_select_counts_and_order():
+    w = _ragged()
+    D = rng.normal(5, "D", (int(sum(w.n_vis)), 2))
+    mask, idx, off = R.select(D, w.seq_off, w.vis_start, w.vis_len, R.TOPK, w.keep_ratio, 0.0)
+    for b in range(w.B):
+        s0, s1 = w.seq_off[b], w.seq_off[b + 1]
+        k = math.floor(w.keep_ratio * w.n_vis[b])
+        assert off[b + 1] - off[b] == int(mask[s0:s1].sum()) == w.n_sys[b] + k + w.n_prompt[b]
+        ib = idx[off[b]:off[b + 1]]
+        assert np.all(np.diff(ib) > 0) and np.all(mask[s0 + ib] == 1)
+        # text rows all kept
+        assert mask[s0:s0 + w.n_sys[b]].all() and mask[s0 + w.n_sys[b] + w.n_vis[b]:s1].all()
+    # keep everything / nothing
+    m1, i1, o1 = R.select(D, w.seq_off, w.vis_start, w.vis_len, R.TOPK, 1.0, 0.0)
+    assert m1.all() and list(o1) == list(w.seq_off)
+    m0, i0, o0 = R.select(D, w.seq_off, w.vis_start, w.vis_len, R.TOPK, 0.0, 0.0)
+    assert int(m0.sum()) == sum(w.n_sys) + sum(w.n_prompt)
+
+
+# ------------------------------------------------------------------ attention, brute force
+
+def _attn_row_loops(q, keys, vals, scale):
+    """softmax(scale * q.k_j) weighted mean of v_j, pure Python, float64."""
+    s = [scale * sum(float(a) * float(b) for a, b in zip(q, k)) for k in keys]
+    m = max(s)
+    p = [math.exp(v - m) for v in s]
+    z = sum(p)
+    return [sum(p[j] * float(vals[j][c]) for j in range(len(keys))) / z for c in range(len(vals[0]))]
+
+
+def _tiny(dtype="bf16", T=5, ratio=0.4):
+    w = W.make("tiny", dtype, 16, 2, 8, 2, [2, 1], [9, 6], [3, 2], ratio, T)
+    pre = W.prefill_inputs(w)
+    dec = W.decode_inputs(w)
+    return w, pre, dec
+
+
+def _run_oracle(w, pre, dec, ratio, theta, D=None, keep_seq=None):
+    if D is None:
+        D = rng.normal(w.seed, "pins.D", (int(sum(w.n_vis)), 2))
+    mask, idx, off = R.select(D, w.seq_off, w.vis_start, w.vis_len, R.TOPK, ratio, 0.0)
+    bt, n_pages = W.block_table(w, extra_tokens=max(w.seq_len))
+    cache = R.PagedCache(n_pages, bt, w.H, w.Dh, w.dtype)
+    _, Qc = R.compact(idx, off, w.seq_off, hidden=None, Q=pre["Q"], K=pre["K"], V=pre["V"], cache=cache)
+    Kc = np.concatenate([cache.rows(b)[0] for b in range(w.B)])
+    Vc = np.concatenate([cache.rows(b)[1] for b in range(w.B)])
+    scale = 1.0 / math.sqrt(w.Dh)
+    O = R.prefill_attn(Qc, Kc, Vc, off, scale, w.dtype)
+    outs, keeps = [], []
+    Dt = rng.normal(w.seed, "pins.Dt", (w.T, w.B, 2))
+    for t in range(w.T):
+        keep = R.decode_keep(Dt[t], theta) if keep_seq is None else keep_seq[t]
+        o, err = R.decode_attn_append(dec["q"][t], dec["k"][t], dec["v"][t], keep, cache, scale)
+        assert not err.any()
+        outs.append(o)
+        keeps.append(np.array(keep))
+    return mask, idx, off, O, outs, keeps, cache
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_keep_everything_is_dense_causal_attention(dtype):
+    """ratio 1.0 and threshold -inf: prefill and every decode step equal dense attention over all tokens."""
+    w, pre, dec = _tiny(dtype)
+    mask, idx, off, O, outs, keeps, cache = _run_oracle(w, pre, dec, 1.0, -np.inf)
+    assert mask.all() and all(k.all() for k in keeps)
+    f = lambda a: W.stored_to_f32(a, dtype).astype(np.float64)
+    Q, K, V = f(pre["Q"]), f(pre["K"]), f(pre["V"])
+    scale = 1.0 / math.sqrt(w.Dh)
+    for b in range(w.B):
+        s0, s1 = int(w.seq_off[b]), int(w.seq_off[b + 1])
+        for h in range(w.H):
+            for i in range(s0, s1):
+                ref = _attn_row_loops(Q[i, h], K[s0:i + 1, h], V[s0:i + 1, h], scale)
+                assert np.allclose(O[i, h], ref, atol=1e-12)
+            for t in range(w.T):
+                keys = list(K[s0:s1, h]) + [f(dec["k"][u])[b, h] for u in range(t + 1)]
+                vals = list(V[s0:s1, h]) + [f(dec["v"][u])[b, h] for u in range(t + 1)]
+                ref = _attn_row_loops(f(dec["q"][t])[b, h], keys, vals, scale)
+                assert np.allclose(outs[t][b, h], ref, atol=1e-12)
+    assert list(cache.cache_len) == [n + w.T for n in w.seq_len]
+
+
+def _masked_softmax_attention(Q, K, V, M, scale):
+    """Eq. 7 with a causal mask: dense N x N attention, G[i,j] = M[j], diag(G) = 1.  Returns [N,Dh]."""
+    N = len(Q)
+    out = np.zeros((N, V.shape[1]))
+    for i in range(N):
+        x = [scale * float(Q[i] @ K[j]) for j in range(i + 1)]
+        g = [1.0 if (j == i or M[j]) else 0.0 for j in range(i + 1)]
+        mx = max(x)
+        e = [math.exp(x[j] - mx) * g[j] for j in range(i + 1)]
+        z = sum(e)
+        for j in range(i + 1):
+            out[i] += (e[j] / z) * V[j]
+    return out
+
+
+def test_gather_form_equals_masked_softmax_form():
+    """Inference (gather then causal attention) == training form (Eq. 7 mask on the full sequence),
+    for prefill rows that are kept and for every decode step under an arbitrary keep history."""
+    w, pre, dec = _tiny("bf16", T=6, ratio=0.4)
+    keep_seq = [np.array(v, np.uint8) for v in ([1, 0], [0, 0], [1, 1], [0, 1], [1, 0], [0, 1])]
+    mask, idx, off, O, outs, keeps, cache = _run_oracle(w, pre, dec, 0.4, 0.0, keep_seq=keep_seq)
+    f = lambda a: W.stored_to_f32(a, "bf16").astype(np.float64)
+    scale = 1.0 / math.sqrt(w.Dh)
+    for b in range(w.B):
+        s0, s1 = int(w.seq_off[b]), int(w.seq_off[b + 1])
+        Mfull = list(mask[s0:s1]) + [int(keep_seq[t][b]) for t in range(w.T)]
+        for h in range(w.H):
+            Qa = np.concatenate([f(pre["Q"])[s0:s1, h], np.stack([f(dec["q"][t])[b, h] for t in range(w.T)])])
+            Ka = np.concatenate([f(pre["K"])[s0:s1, h], np.stack([f(dec["k"][t])[b, h] for t in range(w.T)])])
+            Va = np.concatenate([f(pre["V"])[s0:s1, h], np.stack([f(dec["v"][t])[b, h] for t in range(w.T)])])
+            dense = _masked_softmax_attention(Qa, Ka, Va, Mfull, scale)
+            kept_rows = idx[off[b]:off[b + 1]]
+            assert np.allclose(O[off[b]:off[b + 1], h], dense[kept_rows], atol=1e-12)
+            for t in range(w.T):
+                assert np.allclose(outs[t][b, h], dense[(s1 - s0) + t], atol=1e-12)
+    exp_len = [int(off[b + 1] - off[b]) + sum(int(k[b]) for k in keep_seq) for b in range(w.B)]
+    assert list(cache.cache_len) == exp_len
+
+
+def test_decode_closed_forms():
+    H, Dh = 2, 8
+    bt = np.array([[1, 0]], np.int32)
+    cache = R.PagedCache(2, bt, H, Dh, "f32", page_size=4)
+    q = rng.normal(1, "q", (1, H, Dh))
+    k = rng.normal(1, "k", (1, H, Dh))
+    v = rng.normal(1, "v", (1, H, Dh))
+    # empty cache: softmax over the single (current) key is 1 -> o == v_new; token not kept -> cache stays empty
+    o, _ = R.decode_attn_append(q, k, v, [0], cache, 0.3)
+    assert np.array_equal(o.astype(np.float32), v) and cache.cache_len[0] == 0
+    # identical keys: uniform weights -> arithmetic mean of the values (cached ones and the new one)
+    vs = [rng.normal(2, f"v{t}", (1, H, Dh)) for t in range(6)]
+    for t in range(5):
+        R.decode_attn_append(q, k, vs[t], [1], cache, 0.3)
+    assert cache.cache_len[0] == 5
+    o, _ = R.decode_attn_append(q, k, vs[5], [0], cache, 0.3)
+    assert np.allclose(o, np.mean([a.astype(np.float64) for a in vs], axis=0), atol=1e-12)
+    # a key aligned with q with a huge logit takes all the weight
+    kbig = (q * 1000).astype(np.float32)
+    vbig = rng.normal(3, "vbig", (1, H, Dh))
+    o, _ = R.decode_attn_append(q, kbig, vbig, [0], cache, 1.0)
+    assert np.allclose(o, vbig, atol=1e-9)
+    # capacity: 8 slots; fill up, then a kept token is flagged and not stored
+    for t in range(3):
+        _, err = R.decode_attn_append(q, k, v, [1], cache, 0.3)
+        assert not err.any()
+    assert cache.cache_len[0] == 8
+    _, err = R.decode_attn_append(q, k, v, [1], cache, 0.3)
+    assert err[0] == 1 and cache.cache_len[0] == 8
+
+
+def test_outputs_are_convex_combinations_and_page_placement_is_irrelevant():
+    w, pre, dec = _tiny("bf16", T=4, ratio=0.5)
+    a = _run_oracle(w, pre, dec, 0.5, 0.0)
+    w2 = W.make("tiny", "bf16", 16, 2, 8, 2, [2, 1], [9, 6], [3, 2], 0.5, 4, seed=w.seed)
+    O, outs, cache = a[3], a[4], a[6]
+    # each output channel lies within the range of the values it averages
+    f = lambda x: W.stored_to_f32(x, "bf16").astype(np.float64)
+    for b in range(w.B):
+        Kc, Vc = cache.rows(b)
+        Vf = f(Vc)
+        for h in range(w.H):
+            lo = np.minimum(Vf[:, h].min(0), f(dec["v"][-1])[b, h])
+            hi = np.maximum(Vf[:, h].max(0), f(dec["v"][-1])[b, h])
+            assert np.all(outs[-1][b, h] >= lo - 1e-12) and np.all(outs[-1][b, h] <= hi + 1e-12)
+    # a different block table (reversed page ids) gives bit-identical outputs
+    mask, idx, off = a[0], a[1], a[2]
+    bt, n_pages = W.block_table(w, extra_tokens=max(w.seq_len))
+    cache2 = R.PagedCache(n_pages, (n_pages - 1 - bt), w.H, w.Dh, w.dtype)
+    R.compact(idx, off, w.seq_off, Q=pre["Q"], K=pre["K"], V=pre["V"], cache=cache2)
+    scale = 1.0 / math.sqrt(w.Dh)
+    for t in range(w.T):
+        o2, _ = R.decode_attn_append(dec["q"][t], dec["k"][t], dec["v"][t], a[5][t], cache2, scale)
+        assert np.array_equal(o2, outs[t])
+
+
+def test_compact_copies_kept_rows_bit_exactly():
+    w, pre, dec = _tiny("bf16")
+    D = rng.normal(9, "D", (int(sum(w.n_vis)), 2))
+    mask, idx, off = R.select(D, w.seq_off, w.vis_start, w.vis_len, R.TOPK, w.keep_ratio, 0.0)
+    bt, n_pages = W.block_table(w)
+    cache = R.PagedCache(n_pages, bt, w.H, w.Dh, w.dtype)
+    h_out, q_out = R.compact(idx, off, w.seq_off, hidden=pre["hidden"], Q=pre["Q"], K=pre["K"], V=pre["V"], cache=cache)
+    j = 0
+    for b in range(w.B):
+        Kc, Vc = cache.rows(b)
+        for t, p in enumerate(idx[off[b]:off[b + 1]]):
+            src = int(w.seq_off[b]) + int(p)
+            assert np.array_equal(h_out[j], pre["hidden"][src]) and np.array_equal(q_out[j], pre["Q"][src])
+            assert np.array_equal(Kc[t], pre["K"][src]) and np.array_equal(Vc[t], pre["V"][src])
+            j += 1
+    assert j == off[-1] == len(h_out)
