@@ -1,0 +1,196 @@
+/*
+ * dllava — token sparsification followed by attention over the reduced context
+ * (Dynamic-LLaVA, arXiv 2412.00876), as a C-ABI library for one AMD MI355X (gfx950).
+ *
+ * The four entry points are the steps of the paper's sparsification inference
+ * (Sec. 3.3.2; batch-parallel form in Appendix A.1):
+ *   dllava_score               predictor logits D = P(S_l)                 (Eq. 5 line 1, Eq. 11 line 1)
+ *   dllava_select_compact      keep decisions + reduced token set / cache  (Eq. 5 lines 2-3, Eq. 11 lines 2-3)
+ *   dllava_prefill_attn        Attention over the reduced prefill set      (Eq. 1 with S^{P*}, Sec. 3.3.2)
+ *   dllava_decode_attn_append  decode step with online KV-cache reduction  (Eq. 6)
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller
+ *     allocates and frees every buffer; the library allocates nothing.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued asynchronously on it; no entry point synchronises with the host, so the
+ *     calls may be recorded into a HIP graph.
+ *   - Floating tensors are stored in `dtype` (DLLAVA_F32 or DLLAVA_BF16), row-major, with
+ *     the last index contiguous.  All accumulation is in float32.  Logits are float32.
+ *   - Token layout of a batch: sequences are concatenated ("ragged"); sequence b owns rows
+ *     [seq_off[b], seq_off[b+1]) and, inside them, one vision span
+ *     [vis_start[b], vis_start[b] + vis_len[b]) in sequence-relative positions.  All other
+ *     rows are text and are always kept in prefill (Fig. 2 of the paper).
+ *   - Return value: DLLAVA_OK (0) or a negative dllava_status.  Argument errors are found on
+ *     the host before anything is launched; dllava_last_error() then holds a message.
+ *     Outputs are fully overwritten; inputs are never modified, except the KV cache
+ *     (pages at newly written slots, cache_len).
+ *   - Workspaces: the *_workspace() queries are pure host functions; the caller passes a
+ *     device buffer of at least that many bytes, 256-byte aligned.  Its contents need not
+ *     be initialised and are undefined afterwards.
+ */
+#ifndef DLLAVA_H
+#define DLLAVA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DLLAVA_F32 = 0, DLLAVA_BF16 = 1 } dllava_dtype;
+
+typedef enum {
+  DLLAVA_OK = 0,
+  DLLAVA_EINVAL = -1,     /* a scalar argument is out of range                     */
+  DLLAVA_ENULL = -2,      /* a required pointer is NULL                            */
+  DLLAVA_ESHAPE = -3,     /* a size is unsupported (see each call)                 */
+  DLLAVA_EDTYPE = -4,     /* unknown dtype, or cache dtype differs from the call's */
+  DLLAVA_ECAPACITY = -5,  /* a host-visible capacity is too small                  */
+  DLLAVA_EWORKSPACE = -6, /* workspace missing, misaligned or too small            */
+  DLLAVA_ELAUNCH = -7     /* the HIP runtime refused a launch                      */
+} dllava_status;
+
+typedef enum { DLLAVA_MODE_TOPK = 0, DLLAVA_MODE_THRESHOLD = 1 } dllava_mode;
+
+/*
+ * Paged KV cache of ONE decoder layer; caller-owned (the per-sample caches {S^K(b), S^V(b)} of
+ * Appendix A.1, stored ragged in pages instead of left-padded to a batch tensor).
+ *   pages        [n_pages][2 (0 = K, 1 = V)][H][page_size][Dh], dtype
+ *   block_table  [B][max_pages_per_seq] page ids; token t of sequence b lives in page
+ *                block_table[b][t / page_size], slot t % page_size.  Every entry must be a
+ *                valid page id in [0, n_pages) (capacity is pre-assigned by the caller).
+ *   cache_len    [B] tokens currently cached per sequence; device-resident, read and
+ *                written by the library.
+ * page_size must be 16; Dh must be 64 or 128.  The struct itself lives in host memory.
+ */
+typedef struct dllava_kv_cache {
+  void* pages;
+  int32_t* block_table;
+  int32_t* cache_len;
+  int32_t n_pages;
+  int32_t max_pages_per_seq;
+  int32_t page_size;
+  int32_t H;
+  int32_t Dh;
+  int32_t dtype; /* dllava_dtype */
+} dllava_kv_cache;
+
+/* Library version (major*10000 + minor*100 + patch).  Host, pure. */
+int dllava_version(void);
+
+/* Message of the last failing call made by this host thread ("" if none).  Host string
+ * owned by the library, valid until the thread's next failing call. */
+const char* dllava_last_error(void);
+
+/*
+ * Predictor scoring, D = P(S_l) (Eq. 5 line 1; Eq. 11 line 1), with the two-layer predictor
+ *     h = GELU(x W1^T + b1)   (exact erf GELU),     D = h W2^T + b2,
+ * one row per token, rows independent.  Column 0 of D is the "drop" logit, column 1 the "keep"
+ * logit (a token is kept when the second value exceeds the first).
+ *
+ *   x        [*, d] dtype, row stride ldx elements (ldx >= d)
+ *   M        number of rows scored = rows of `logits`
+ *   B, seq_off [B+1], vis_start [B], vis_len [B]
+ *            if seq_off is NULL, rows 0..M-1 of x are scored (decode: one row per sequence,
+ *            B/vis_* ignored).  Otherwise the vision spans are scored: logits row
+ *            sum_{b'<b} vis_len[b'] + i  <-  x row seq_off[b] + vis_start[b] + i,  i < vis_len[b];
+ *            M must equal sum_b vis_len[b] (rows beyond that sum are left untouched).
+ *   W1 [dh, d] dtype, W2 [2, dh] dtype;  b1 [dh], b2 [2] float32, either may be NULL (= 0)
+ *   logits   [M, 2] float32, out
+ * Sizes: d % 8 == 0, 1 <= dh, M >= 0 (M == 0 is a no-op).
+ */
+int dllava_score(const void* x, int64_t ldx, int64_t M,
+                 int32_t B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_len,
+                 int64_t d, int64_t dh,
+                 const void* W1, const float* b1, const void* W2, const float* b2,
+                 int dtype, float* logits,
+                 void* workspace, size_t workspace_bytes, void* stream);
+size_t dllava_score_workspace(int64_t M, int64_t d, int64_t dh, int dtype);
+
+/*
+ * Keep decisions and order-preserving stream compaction (Eq. 5 lines 2-3; Eq. 11 lines 2-3).
+ *
+ * Decisions, per sequence b over its vision span (n = vis_len[b]):
+ *   DLLAVA_MODE_TOPK       keep the k = floor(keep_ratio * n) rows (float64 product) with the largest
+ *                          logits[:,1]; ties go to the lower index; NaN ranks below every
+ *                          number; -0 equals +0.
+ *   DLLAVA_MODE_THRESHOLD  keep row i iff logits[i,1] - logits[i,0] > threshold (float32,
+ *                          strict; threshold 0 is the argmax rule of Eq. 5).
+ * Text rows are always kept.  Kept rows keep their original relative order, which is what
+ * makes causal attention over the reduced set equal the masked attention of Eq. 7.
+ *
+ *   logits     [sum_b vis_len[b], 2] float32, vision rows of all sequences back to back
+ *   sumN       total rows = seq_off[B] (host copy of that value)
+ *   hidden     [sumN, d] dtype -> hidden_out [sum N*, d]      (both NULL to skip)
+ *   Q          [sumN, H*Dh] dtype -> Q_out [sum N*, H*Dh]     (both NULL to skip; H, Dh from `cache`,
+ *              which is then required)
+ *   K, V       [sumN, H, Dh] dtype -> written through cache->block_table into cache->pages at
+ *              positions 0..N*(b)-1, and cache->cache_len[b] = N*(b)   (K, V, cache all NULL to skip)
+ *   keep_mask  [sumN] uint8, out
+ *   kept_idx   [sumN] capacity, out: sequence-relative original positions of the kept rows,
+ *              ascending within each sequence, packed by out_off
+ *   out_off    [B+1] out: offsets of each sequence in the compacted row order; out_off[B] = sum N*
+ *   err_flag   device int32, may be NULL: set to 1 if some N*(b) exceeds the cache capacity
+ *              max_pages_per_seq * page_size; the rows beyond capacity are then not written
+ *              and cache_len[b] is clamped to the capacity.  Never cleared by the library.
+ * Output buffers hidden_out / Q_out need capacity for sum N* rows (sumN always suffices).
+ * Errors: keep_ratio outside [0,1] or NaN, NaN threshold, d*sizeof(dtype) % 16 != 0.
+ */
+int dllava_select_compact(const float* logits,
+                          int32_t B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_len,
+                          int64_t sumN, int mode, double keep_ratio, float threshold,
+                          const void* hidden, void* hidden_out, int64_t d,
+                          const void* Q, void* Q_out,
+                          const void* K, const void* V, const dllava_kv_cache* cache,
+                          uint8_t* keep_mask, int32_t* kept_idx, int32_t* out_off,
+                          int32_t* err_flag, int dtype,
+                          void* workspace, size_t workspace_bytes, void* stream);
+size_t dllava_select_compact_workspace(int32_t B, int64_t sumN);
+
+/*
+ * Causal scaled-dot-product attention over the reduced prefill set (Eq. 1 applied to S^{P*}):
+ * for sequence b, head h and compacted row i,  O_i = softmax_{j<=i}(scale * q_i . k_j) V.
+ *
+ *   Q       [rows, H, Dh] dtype, compacted rows (rows >= off[B])
+ *   K, V    [rows, H, Dh] dtype; or both NULL to read keys/values of sequence b from `cache`
+ *           positions 0..n_b-1 (the cache must hold at least n_b = off[b+1]-off[b] tokens)
+ *   off     [B+1] row offsets of the sequences (out_off of dllava_select_compact)
+ *   rows    host upper bound on off[B] (capacity of Q and O); only rows < off[B] are written
+ *   O       [rows, H, Dh] dtype, out
+ * Sizes: Dh in {64, 128}.
+ */
+int dllava_prefill_attn(const void* Q, const void* K, const void* V, const dllava_kv_cache* cache,
+                        int32_t B, const int32_t* off, int64_t rows,
+                        int32_t H, int32_t Dh, float scale, void* O, int dtype, void* stream);
+
+/*
+ * One decode step with online KV-cache reduction (Eq. 6), for B sequences:
+ *   o[b,h]  = softmax(scale * [K_cache(b,h); k_new[b,h]] q[b,h]) [V_cache(b,h); v_new[b,h]]
+ *             -- the current token always takes part, whatever its keep decision;
+ *   keep[b] = keep_override[b] != 0                      if keep_override != NULL
+ *           = logits[b,1] - logits[b,0] > threshold      otherwise (float32, strict);
+ *   if keep[b]: k_new[b], v_new[b] are stored at position cache_len[b] and cache_len[b] += 1.
+ *
+ *   q, k_new, v_new  [B, H, Dh] cache->dtype
+ *   logits           [B, 2] float32 (output of dllava_score for the current tokens); may be NULL
+ *                    only if keep_override is given
+ *   o                [B, H, Dh] cache->dtype, out
+ *   keep_out         [B] uint8 out, may be NULL
+ *   err_flag         device int32, may be NULL: set to 1 when a kept token finds its sequence at
+ *                    capacity (max_pages_per_seq * page_size); that append is skipped, cache_len
+ *                    stays, keep_out still reports the decision.  Never cleared by the library.
+ * Two calls that share a cache must be ordered on one stream (or otherwise serialised).
+ */
+int dllava_decode_attn_append(const void* q, const void* k_new, const void* v_new, int32_t B,
+                              const float* logits, float threshold, const uint8_t* keep_override,
+                              const dllava_kv_cache* cache, float scale,
+                              void* o, uint8_t* keep_out, int32_t* err_flag,
+                              void* workspace, size_t workspace_bytes, void* stream);
+size_t dllava_decode_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pages_per_seq);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLLAVA_H */

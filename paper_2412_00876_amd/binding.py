@@ -1,0 +1,167 @@
+"""Thin ctypes binding of libdllava.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point (include/dllava.h); tensors are
+torch tensors used purely as device buffers (data_ptr), and the stream defaults to torch's current
+stream.  A non-zero status raises DllavaError with the library's message.  Nothing here computes:
+if the shared library is missing the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libdllava.so")
+
+F32, BF16 = 0, 1
+MODE_TOPK, MODE_THRESHOLD = 0, 1
+PAGE_SIZE = 16
+
+
+class DllavaError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"dllava status {status}: {msg}")
+        self.status = status
+
+
+class _KvCache(C.Structure):
+    _fields_ = [("pages", C.c_void_p), ("block_table", C.c_void_p), ("cache_len", C.c_void_p),
+                ("n_pages", C.c_int32), ("max_pages_per_seq", C.c_int32), ("page_size", C.c_int32),
+                ("H", C.c_int32), ("Dh", C.c_int32), ("dtype", C.c_int32)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2412_00876_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+    lib.dllava_version.restype = C.c_int
+    lib.dllava_version.argtypes = []
+    lib.dllava_last_error.restype = C.c_char_p
+    lib.dllava_last_error.argtypes = []
+    lib.dllava_score.restype = C.c_int
+    lib.dllava_score.argtypes = [vp, i64, i64, i32, vp, vp, vp, i64, i64, vp, vp, vp, vp, C.c_int, vp, vp, sz, vp]
+    lib.dllava_score_workspace.restype = sz
+    lib.dllava_score_workspace.argtypes = [i64, i64, i64, C.c_int]
+    lib.dllava_select_compact.restype = C.c_int
+    lib.dllava_select_compact.argtypes = [vp, i32, vp, vp, vp, i64, C.c_int, C.c_double, f32, vp, vp, i64, vp, vp, vp, vp,
+                                          C.POINTER(_KvCache), vp, vp, vp, vp, C.c_int, vp, sz, vp]
+    lib.dllava_select_compact_workspace.restype = sz
+    lib.dllava_select_compact_workspace.argtypes = [i32, i64]
+    lib.dllava_prefill_attn.restype = C.c_int
+    lib.dllava_prefill_attn.argtypes = [vp, vp, vp, C.POINTER(_KvCache), i32, vp, i64, i32, i32, f32, vp, C.c_int, vp]
+    lib.dllava_decode_attn_append.restype = C.c_int
+    lib.dllava_decode_attn_append.argtypes = [vp, vp, vp, i32, vp, f32, vp, C.POINTER(_KvCache), f32, vp, vp, vp,
+                                              vp, sz, vp]
+    lib.dllava_decode_workspace.restype = sz
+    lib.dllava_decode_workspace.argtypes = [i32, i32, i32, i32]
+    return lib
+
+
+_lib = _load()
+EXPORTS = ("dllava_version", "dllava_last_error", "dllava_score", "dllava_score_workspace",
+           "dllava_select_compact", "dllava_select_compact_workspace", "dllava_prefill_attn",
+           "dllava_decode_attn_append", "dllava_decode_workspace")
+
+
+def lib() -> C.CDLL:
+    return _lib
+
+
+def dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t}")
+
+
+def _p(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    return stream or None
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise DllavaError(rc, _lib.dllava_last_error().decode())
+
+
+def _ws(workspace: Optional[torch.Tensor]):
+    if workspace is None:
+        return None, 0
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+class KVCache:
+    """Host-side descriptor (dllava_kv_cache) over caller-owned device tensors."""
+
+    def __init__(self, pages: torch.Tensor, block_table: torch.Tensor, cache_len: torch.Tensor):
+        n_pages, two, H, ps, Dh = pages.shape
+        assert two == 2 and pages.is_contiguous() and block_table.is_contiguous()
+        assert block_table.dtype == torch.int32 and cache_len.dtype == torch.int32
+        self.pages, self.block_table, self.cache_len = pages, block_table, cache_len
+        self.H, self.Dh, self.page_size = H, Dh, ps
+        self.B, self.max_pages_per_seq = block_table.shape
+        self.c = _KvCache(pages.data_ptr(), block_table.data_ptr(), cache_len.data_ptr(), n_pages,
+                          self.max_pages_per_seq, ps, H, Dh, dtype_code(pages.dtype))
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+
+def dllava_version() -> int:
+    return _lib.dllava_version()
+
+
+def dllava_score_workspace(M: int, d: int, dh: int, dtype: int) -> int:
+    return _lib.dllava_score_workspace(M, d, dh, dtype)
+
+
+def dllava_select_compact_workspace(B: int, sumN: int) -> int:
+    return _lib.dllava_select_compact_workspace(B, sumN)
+
+
+def dllava_decode_workspace(B: int, H: int, Dh: int, max_pages_per_seq: int) -> int:
+    return _lib.dllava_decode_workspace(B, H, Dh, max_pages_per_seq)
+
+
+def dllava_score(x, ldx, M, B, seq_off, vis_start, vis_len, d, dh, W1, b1, W2, b2, dtype, logits,
+                 workspace, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(_lib.dllava_score(_p(x), ldx, M, B, _p(seq_off), _p(vis_start), _p(vis_len), d, dh, _p(W1), _p(b1),
+                             _p(W2), _p(b2), dtype, _p(logits), wp, wb, _stream(stream)))
+
+
+def dllava_select_compact(logits, B, seq_off, vis_start, vis_len, sumN, mode, keep_ratio, threshold,
+                          hidden, hidden_out, d, Q, Q_out, K, V, cache: Optional[KVCache],
+                          keep_mask, kept_idx, out_off, err_flag, dtype, workspace, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(_lib.dllava_select_compact(_p(logits), B, _p(seq_off), _p(vis_start), _p(vis_len), sumN, mode,
+                                      keep_ratio, threshold, _p(hidden), _p(hidden_out), d, _p(Q), _p(Q_out),
+                                      _p(K), _p(V), cache.ref if cache is not None else None, _p(keep_mask),
+                                      _p(kept_idx), _p(out_off), _p(err_flag), dtype, wp, wb, _stream(stream)))
+
+
+def dllava_prefill_attn(Q, K, V, cache: Optional[KVCache], B, off, rows, H, Dh, scale, O, dtype,
+                        stream=None) -> None:
+    _check(_lib.dllava_prefill_attn(_p(Q), _p(K), _p(V), cache.ref if cache is not None else None, B, _p(off),
+                                    rows, H, Dh, scale, _p(O), dtype, _stream(stream)))
+
+
+def dllava_decode_attn_append(q, k_new, v_new, B, logits, threshold, keep_override, cache: KVCache, scale,
+                              o, keep_out, err_flag, workspace, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(_lib.dllava_decode_attn_append(_p(q), _p(k_new), _p(v_new), B, _p(logits), threshold,
+                                          _p(keep_override), cache.ref, scale, _p(o), _p(keep_out),
+                                          _p(err_flag), wp, wb, _stream(stream)))

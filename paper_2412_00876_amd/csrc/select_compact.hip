@@ -1,0 +1,328 @@
+// dllava_select_compact: keep decisions (Eq. 5 line 2 / Eq. 11 line 2 of the paper) and order-preserving
+// stream compaction of hidden states, queries and K/V into the reduced token set / paged cache
+// (Eq. 5 line 3 / Eq. 11 line 3).
+//
+// Three launches:
+//   1. select_kernel   one block per sequence.  Top-k: the k-th largest score is found exactly by a
+//                      4-pass most-significant-byte radix select over an order-preserving 32-bit key,
+//                      then one in-order pass keeps keys above it plus the first (k - #above) equal keys,
+//                      which is the "ties go to the lower index" rule.  The same pass ranks the kept
+//                      rows of the sequence (prefix sum), so kept positions come out ascending.
+//   2. offsets_kernel  exclusive scan of the per-sequence counts -> out_off, cache_len, capacity check.
+//   3. gather_kernel   one block per (compacted row, tensor): 16-byte coalesced row copies; K/V rows
+//                      are scattered head by head into their page slot.
+// Selection is integer-exact: it only compares float32 keys.
+#include "common.h"
+
+namespace dllava {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+
+// Order-preserving key: larger score <-> larger key; -0 and +0 share a key; NaN gets the lowest key.
+__device__ __forceinline__ uint32_t score_key(float s) {
+  if (s != s) return 0u;
+  if (s == 0.f) return 0x80000000u;
+  const uint32_t u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Exclusive prefix sum of one int per thread over the block; `total` receives the block sum.
+__device__ __forceinline__ int block_excl_scan(int v, int* sm_tot /*[kWaves]*/, int& total) {
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int incl = wave_incl_scan(v);
+  __syncthreads();  // previous use of sm_tot is over
+  if (lane == kWave - 1) sm_tot[w] = incl;
+  __syncthreads();
+  int off = 0, t = 0;
+#pragma unroll
+  for (int i = 0; i < kWaves; ++i) {
+    const int x = sm_tot[i];
+    if (i < w) off += x;
+    t += x;
+  }
+  total = t;
+  return off + incl - v;
+}
+
+struct SelectArgs {
+  const float* logits;
+  const int32_t* seq_off;
+  const int32_t* vis_start;
+  const int32_t* vis_len;
+  int32_t B;
+  int32_t mode;
+  double keep_ratio;
+  float threshold;
+  uint8_t* keep_mask;
+  int32_t* ws_kept;    // [sumN]: kept positions of sequence b at [seq_off[b] ...)
+  int32_t* ws_counts;  // [B]
+};
+
+__global__ __launch_bounds__(kThreads) void select_kernel(SelectArgs a) {
+  __shared__ int hist[256];
+  __shared__ int sm_tot[kWaves];
+  __shared__ int sm_sel[2];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int s0 = a.seq_off[b];
+  int N = a.seq_off[b + 1] - s0;
+  if (N < 0) N = 0;
+  int v0 = a.vis_start[b];
+  v0 = v0 < 0 ? 0 : (v0 > N ? N : v0);
+  int n = a.vis_len[b];
+  n = n < 0 ? 0 : (n > N - v0 ? N - v0 : n);
+
+  // row of this sequence's first vision token in `logits`
+  int part = 0;
+  for (int i = tid; i < b; i += kThreads) {
+    const int x = a.vis_len[i];
+    part += x > 0 ? x : 0;
+  }
+  int lo;
+  block_excl_scan(part, sm_tot, lo);
+  const float* D = a.logits + 2 * static_cast<size_t>(lo);
+
+  uint32_t kth = 0;     // key of the k-th largest score
+  int need = 0;         // how many rows with key == kth are kept (taken in index order)
+  bool all = false, none = false;
+  if (a.mode == DLLAVA_MODE_TOPK) {
+    int64_t k = static_cast<int64_t>(floor(a.keep_ratio * static_cast<double>(n)));
+    if (k <= 0) none = true;
+    else if (k >= n) all = true;
+    else {
+      uint32_t prefix = 0, mask = 0;
+      int remaining = static_cast<int>(k);
+      for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += kThreads) {
+          const uint32_t key = score_key(D[2 * i + 1]);
+          if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        // suffix sums over the bins: thread t looks at bin 255 - t
+        const int bin = 255 - tid;
+        const int c = hist[bin];
+        int tot;
+        const int above = block_excl_scan(c, sm_tot, tot);  // rows in higher bins
+        if (above < remaining && above + c >= remaining) {
+          sm_sel[0] = bin;
+          sm_sel[1] = remaining - above;
+        }
+        __syncthreads();
+        prefix |= static_cast<uint32_t>(sm_sel[0]) << shift;
+        mask |= 0xffu << shift;
+        remaining = sm_sel[1];
+        __syncthreads();
+      }
+      kth = prefix;
+      need = remaining;
+    }
+  }
+
+  // in-order pass over all rows of the sequence
+  int carry_eq = 0, carry_keep = 0;
+  for (int base = 0; base < N; base += kThreads) {
+    const int p = base + tid;
+    const bool in = p < N;
+    const bool vis = in && p >= v0 && p < v0 + n;
+    bool keep = in && !vis;
+    bool eq = false;
+    if (vis) {
+      const int i = p - v0;
+      if (a.mode == DLLAVA_MODE_TOPK) {
+        if (all) keep = true;
+        else if (!none) {
+          const uint32_t key = score_key(D[2 * i + 1]);
+          keep = key > kth;
+          eq = key == kth;
+        }
+      } else {
+        keep = keep_from_logits(D, i, a.threshold);
+      }
+    }
+    if (a.mode == DLLAVA_MODE_TOPK && !all && !none) {
+      int tot_eq;
+      const int rank_eq = carry_eq + block_excl_scan(eq ? 1 : 0, sm_tot, tot_eq);
+      if (eq && rank_eq < need) keep = true;
+      carry_eq += tot_eq;
+    }
+    int tot_keep;
+    const int pos = carry_keep + block_excl_scan(keep ? 1 : 0, sm_tot, tot_keep);
+    carry_keep += tot_keep;
+    if (in) {
+      a.keep_mask[static_cast<size_t>(s0) + p] = keep ? 1 : 0;
+      if (keep) a.ws_kept[static_cast<size_t>(s0) + pos] = p;
+    }
+  }
+  if (tid == 0) a.ws_counts[b] = carry_keep;
+}
+
+__global__ __launch_bounds__(kThreads) void offsets_kernel(const int32_t* counts, int32_t B, int32_t* out_off,
+                                                           int32_t* cache_len, int32_t cap, int32_t* err_flag) {
+  __shared__ int sm_tot[kWaves];
+  const int tid = threadIdx.x;
+  int carry = 0;
+  for (int base = 0; base < B; base += kThreads) {
+    const int b = base + tid;
+    const int c = b < B ? counts[b] : 0;
+    int tot;
+    const int ex = carry + block_excl_scan(c, sm_tot, tot);
+    carry += tot;
+    if (b < B) {
+      out_off[b] = ex;
+      if (cache_len) {
+        cache_len[b] = c > cap ? cap : c;
+        if (c > cap && err_flag) *err_flag = 1;
+      }
+    }
+  }
+  if (tid == 0) out_off[B] = carry;
+}
+
+struct GatherArgs {
+  const int32_t* seq_off;
+  const int32_t* out_off;
+  const int32_t* ws_kept;
+  int32_t* kept_idx;
+  int32_t B;
+  const uint4* hidden; uint4* hidden_out; int64_t hidden_chunks;  // 16-byte chunks per row
+  const uint4* Q; uint4* Q_out; int64_t q_chunks;
+  const uint4* K; const uint4* V; int64_t kv_chunks;              // per row, all heads
+  uint4* pages; const int32_t* block_table;
+  int32_t max_pages, H, head_chunks;                              // 16-byte chunks per (token, head)
+};
+
+// grid (rows upper bound, 4): y = 0 hidden, 1 Q, 2 K, 3 V
+__global__ __launch_bounds__(kThreads) void gather_kernel(GatherArgs a) {
+  const int j = blockIdx.x, what = blockIdx.y, tid = threadIdx.x;
+  const int total = a.out_off[a.B];
+  if (j >= total) return;
+  int lo = 0, hi = a.B;  // largest b with out_off[b] <= j
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.out_off[mid] <= j) lo = mid; else hi = mid;
+  }
+  const int b = lo;
+  const int pos = j - a.out_off[b];
+  const int s0 = a.seq_off[b];
+  const int rel = a.ws_kept[static_cast<size_t>(s0) + pos];
+  const size_t src = static_cast<size_t>(s0) + rel;
+  if (what == 0) {
+    if (tid == 0) a.kept_idx[j] = rel;
+    if (!a.hidden) return;
+    const uint4* in = a.hidden + src * a.hidden_chunks;
+    uint4* out = a.hidden_out + static_cast<size_t>(j) * a.hidden_chunks;
+    for (int64_t c = tid; c < a.hidden_chunks; c += kThreads) out[c] = in[c];
+  } else if (what == 1) {
+    if (!a.Q) return;
+    const uint4* in = a.Q + src * a.q_chunks;
+    uint4* out = a.Q_out + static_cast<size_t>(j) * a.q_chunks;
+    for (int64_t c = tid; c < a.q_chunks; c += kThreads) out[c] = in[c];
+  } else {
+    if (!a.K || pos >= a.max_pages * kPage) return;
+    const int kv = what - 2;
+    const uint4* in = (kv ? a.V : a.K) + src * a.kv_chunks;
+    const int pg = a.block_table[static_cast<size_t>(b) * a.max_pages + pos / kPage];
+    const int slot = pos % kPage;
+    const size_t tile_chunks = static_cast<size_t>(kPage) * a.head_chunks;
+    uint4* base = a.pages + (static_cast<size_t>(pg) * 2 + kv) * a.H * tile_chunks +
+                  static_cast<size_t>(slot) * a.head_chunks;
+    for (int64_t c = tid; c < a.kv_chunks; c += kThreads) {
+      const int h = static_cast<int>(c / a.head_chunks), cc = static_cast<int>(c % a.head_chunks);
+      base[h * tile_chunks + cc] = in[c];
+    }
+  }
+}
+
+}  // namespace
+}  // namespace dllava
+
+using namespace dllava;
+
+extern "C" size_t dllava_select_compact_workspace(int32_t B, int64_t sumN) {
+  const size_t b = B > 0 ? B : 0, n = sumN > 0 ? sumN : 0;
+  return round_up(n * sizeof(int32_t), 256) + round_up(b * sizeof(int32_t), 256) + 256;
+}
+
+extern "C" int dllava_select_compact(const float* logits, int32_t B, const int32_t* seq_off,
+                                     const int32_t* vis_start, const int32_t* vis_len, int64_t sumN, int mode,
+                                     double keep_ratio, float threshold, const void* hidden, void* hidden_out,
+                                     int64_t d, const void* Q, void* Q_out, const void* K, const void* V,
+                                     const dllava_kv_cache* cache, uint8_t* keep_mask, int32_t* kept_idx,
+                                     int32_t* out_off, int32_t* err_flag, int dtype, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  DLLAVA_REQUIRE(B >= 0 && sumN >= 0, DLLAVA_EINVAL, "select_compact: B = %d, sumN = %lld", B, (long long)sumN);
+  DLLAVA_REQUIRE(sumN <= 0x7fffffffLL, DLLAVA_ESHAPE, "select_compact: sumN must fit in int32");
+  DLLAVA_REQUIRE(dtype == DLLAVA_F32 || dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "select_compact: unknown dtype %d", dtype);
+  DLLAVA_REQUIRE(mode == DLLAVA_MODE_TOPK || mode == DLLAVA_MODE_THRESHOLD, DLLAVA_EINVAL,
+                 "select_compact: unknown mode %d", mode);
+  if (mode == DLLAVA_MODE_TOPK)
+    DLLAVA_REQUIRE(keep_ratio >= 0.0 && keep_ratio <= 1.0, DLLAVA_EINVAL,
+                   "select_compact: keep_ratio must lie in [0,1] (got %g)", keep_ratio);
+  else
+    DLLAVA_REQUIRE(threshold == threshold, DLLAVA_EINVAL, "select_compact: threshold is NaN");
+  DLLAVA_REQUIRE(out_off, DLLAVA_ENULL, "select_compact: out_off is required");
+  DLLAVA_REQUIRE((hidden == nullptr) == (hidden_out == nullptr), DLLAVA_ENULL,
+                 "select_compact: hidden and hidden_out go together");
+  DLLAVA_REQUIRE((Q == nullptr) == (Q_out == nullptr), DLLAVA_ENULL, "select_compact: Q and Q_out go together");
+  DLLAVA_REQUIRE((K == nullptr) == (V == nullptr), DLLAVA_ENULL, "select_compact: K and V go together");
+  DLLAVA_REQUIRE(!K || cache, DLLAVA_ENULL, "select_compact: K/V need a cache to be written to");
+  DLLAVA_REQUIRE(!Q || cache, DLLAVA_ENULL, "select_compact: Q needs cache->H and cache->Dh");
+  const size_t es = dtype_size(dtype);
+  if (cache) {
+    if (int rc = check_cache(cache, "select_compact")) return rc;
+    DLLAVA_REQUIRE(cache->dtype == dtype, DLLAVA_EDTYPE, "select_compact: cache dtype differs from dtype");
+  }
+  if (hidden) {
+    DLLAVA_REQUIRE(d > 0 && (d * es) % 16 == 0, DLLAVA_ESHAPE,
+                   "select_compact: hidden rows must be a multiple of 16 bytes (d = %lld)", (long long)d);
+    DLLAVA_REQUIRE(aligned(hidden, 16) && aligned(hidden_out, 16), DLLAVA_EINVAL,
+                   "select_compact: hidden buffers must be 16-byte aligned");
+  }
+  DLLAVA_REQUIRE((!Q || (aligned(Q, 16) && aligned(Q_out, 16))) && (!K || (aligned(K, 16) && aligned(V, 16))),
+                 DLLAVA_EINVAL, "select_compact: Q/K/V buffers must be 16-byte aligned");
+  if (B == 0) return DLLAVA_OK;  // nothing to read: out_off[0] is left to the caller
+  DLLAVA_REQUIRE(logits && seq_off && vis_start && vis_len && keep_mask && kept_idx, DLLAVA_ENULL,
+                 "select_compact: logits, seq_off, vis_start, vis_len, keep_mask, kept_idx are required");
+  const size_t need = dllava_select_compact_workspace(B, sumN);
+  DLLAVA_REQUIRE(workspace && aligned(workspace, 256) && workspace_bytes >= need, DLLAVA_EWORKSPACE,
+                 "select_compact: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int32_t* ws_kept = static_cast<int32_t*>(workspace);
+  int32_t* ws_counts =
+      reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + round_up(static_cast<size_t>(sumN) * 4, 256));
+
+  SelectArgs sa{logits, seq_off, vis_start, vis_len, B, mode, keep_ratio, threshold, keep_mask, ws_kept, ws_counts};
+  hipLaunchKernelGGL(select_kernel, dim3(B), dim3(kThreads), 0, st, sa);
+  DLLAVA_CHECK_LAUNCH("select_kernel");
+
+  const bool write_cache = K != nullptr;
+  const int32_t cap = cache ? cache->max_pages_per_seq * cache->page_size : 0;
+  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kThreads), 0, st, ws_counts, B, out_off,
+                     write_cache ? cache->cache_len : nullptr, cap, err_flag);
+  DLLAVA_CHECK_LAUNCH("offsets_kernel");
+
+  if (sumN == 0) return DLLAVA_OK;
+  GatherArgs ga{};
+  ga.seq_off = seq_off; ga.out_off = out_off; ga.ws_kept = ws_kept; ga.kept_idx = kept_idx; ga.B = B;
+  ga.hidden = static_cast<const uint4*>(hidden); ga.hidden_out = static_cast<uint4*>(hidden_out);
+  ga.hidden_chunks = hidden ? static_cast<int64_t>(d * es / 16) : 0;
+  if (cache) {
+    ga.H = cache->H;
+    ga.head_chunks = static_cast<int32_t>(cache->Dh * es / 16);
+    ga.kv_chunks = static_cast<int64_t>(ga.H) * ga.head_chunks;
+    ga.q_chunks = ga.kv_chunks;
+    ga.max_pages = cache->max_pages_per_seq;
+    ga.pages = static_cast<uint4*>(cache->pages);
+    ga.block_table = cache->block_table;
+  }
+  ga.Q = static_cast<const uint4*>(Q); ga.Q_out = static_cast<uint4*>(Q_out);
+  ga.K = static_cast<const uint4*>(K); ga.V = static_cast<const uint4*>(V);
+  const int parts = K ? 4 : (Q ? 2 : 1);
+  hipLaunchKernelGGL(gather_kernel, dim3(static_cast<unsigned>(sumN), parts), dim3(kThreads), 0, st, ga);
+  DLLAVA_CHECK_LAUNCH("gather_kernel");
+  return DLLAVA_OK;
+}
