@@ -26,8 +26,11 @@
  *     Outputs are fully overwritten; inputs are never modified, except the KV cache
  *     (pages at newly written slots, cache_len).
  *   - Workspaces: the *_workspace() queries are pure host functions; the caller passes a
- *     device buffer of at least that many bytes, 256-byte aligned.  Its contents need not
- *     be initialised and are undefined afterwards.
+ *     device buffer of at least that many bytes, 256-byte aligned.  A workspace must be
+ *     ZERO-FILLED once before its first use: it starts with device-scope counters that the
+ *     kernels count up and return to zero before the call's work completes.  The same buffer
+ *     may then be reused by later calls of the SAME entry point with the same sizes, ordered
+ *     on one stream; it must not be shared with another entry point or written by the caller.
  */
 #ifndef DLLAVA_H
 #define DLLAVA_H

@@ -6,36 +6,9 @@
 // sums the wave, and lane 0 applies bias + GELU and accumulates the two logit terms.  The four wave
 // partials are added in wave order, so the result is bit-reproducible.  It serves float32 inputs and
 // shapes the matrix-core kernels do not cover.
-#include "common.h"
+#include "score_args.h"
 
 namespace dllava {
-
-struct ScoreArgs {
-  const void* x;
-  int64_t ldx, M, d, dh;
-  int32_t B;
-  const int32_t* seq_off;
-  const int32_t* vis_start;
-  const int32_t* vis_len;
-  const void* W1;
-  const float* b1;
-  const void* W2;
-  const float* b2;
-  float* logits;
-  void* workspace;
-};
-
-// Source row of x for logits row m (vision spans back to back), or -1 if m is beyond the spans.
-__device__ __forceinline__ int64_t score_src_row(const ScoreArgs& a, int64_t m) {
-  if (!a.seq_off) return m;
-  int64_t acc = 0;
-  for (int b = 0; b < a.B; ++b) {
-    const int n = a.vis_len[b] > 0 ? a.vis_len[b] : 0;
-    if (m < acc + n) return static_cast<int64_t>(a.seq_off[b]) + a.vis_start[b] + (m - acc);
-    acc += n;
-  }
-  return -1;
-}
 
 namespace {
 
@@ -49,7 +22,7 @@ __global__ __launch_bounds__(kThreads) void score_generic_kernel(ScoreArgs a) {
   constexpr int E = Elem<T>::kPer16B;
   const int64_t m = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-  const int64_t src = score_src_row(a, m);
+  const int64_t src = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m);
   if (src < 0) return;
   const T* xrow = static_cast<const T*>(a.x) + src * a.ldx;
   const int chunks = static_cast<int>(a.d / E);
@@ -103,10 +76,6 @@ int launch_generic(const ScoreArgs& a, hipStream_t st) {
 }
 
 }  // namespace
-
-// matrix-core paths (score_mfma.hip); return 1 if the shape is not handled
-int score_mfma_launch(const ScoreArgs& a, hipStream_t st);
-size_t score_mfma_workspace(int64_t M, int64_t d, int64_t dh);
 
 }  // namespace dllava
 

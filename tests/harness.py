@@ -55,10 +55,12 @@ class GpuPath:
         if pred:
             self.pred = {"W1": to_dev(pred["W1"], w.dtype), "W2": to_dev(pred["W2"], w.dtype),
                          "b1": to_dev(pred["b1"], "f32"), "b2": to_dev(pred["b2"], "f32")}
-        ws = max(P.dllava_select_compact_workspace(w.B, w.sumN),
-                 P.dllava_decode_workspace(w.B, w.H, w.Dh, self.cache.max_pages_per_seq),
-                 P.dllava_score_workspace(max(w.sumN, w.B), w.d, w.dh, self.code))
-        self.ws = torch.empty(ws, dtype=torch.uint8, device=DEV)
+        # one zero-filled workspace per entry point (their counters must start at zero and stay private)
+        z = lambda n: torch.zeros(n, dtype=torch.uint8, device=DEV)
+        self.ws_select = z(P.dllava_select_compact_workspace(w.B, w.sumN))
+        self.ws_decode = z(P.dllava_decode_workspace(w.B, w.H, w.Dh, self.cache.max_pages_per_seq))
+        self.ws_score = z(P.dllava_score_workspace(max(w.sumN, w.B, 1), w.d, w.dh, self.code))
+        self.ws_score_small = z(P.dllava_score_workspace(64, w.d, w.dh, self.code))
         self.scale = 1.0 / math.sqrt(w.Dh)
 
     # -- steps ------------------------------------------------------------------------------
@@ -68,7 +70,7 @@ class GpuPath:
         logits = torch.full((M, 2), float("nan"), dtype=torch.float32, device=DEV)
         p = self.pred
         P.dllava_score(self.pre["hidden"], w.d, M, w.B, self.seq_off, self.vis_start, self.vis_len, w.d, w.dh,
-                       p["W1"], p["b1"], p["W2"], p["b2"], self.code, logits, self.ws)
+                       p["W1"], p["b1"], p["W2"], p["b2"], self.code, logits, self.ws_score)
         return logits
 
     def score_rows(self, x: torch.Tensor) -> torch.Tensor:
@@ -77,7 +79,7 @@ class GpuPath:
         logits = torch.full((M, 2), float("nan"), dtype=torch.float32, device=DEV)
         p = self.pred
         P.dllava_score(x, x.stride(0), M, 0, None, None, None, w.d, w.dh, p["W1"], p["b1"], p["W2"], p["b2"],
-                       self.code, logits, self.ws)
+                       self.code, logits, self.ws_score_small if M <= 64 else self.ws_score)
         return logits
 
     def select_compact(self, logits: torch.Tensor, mode=P.MODE_TOPK, ratio=None, theta=0.0,
@@ -99,7 +101,7 @@ class GpuPath:
                                 pre["Q"] if with_q else None, out["Q_out"],
                                 pre["K"] if with_kv else None, pre["V"] if with_kv else None,
                                 self.cache if (with_kv or with_q) else None,
-                                out["keep_mask"], out["kept_idx"], out["out_off"], self.err, self.code, self.ws)
+                                out["keep_mask"], out["kept_idx"], out["out_off"], self.err, self.code, self.ws_select)
         return out
 
     def prefill(self, Qc: torch.Tensor, off: torch.Tensor, K=None, V=None) -> torch.Tensor:
@@ -114,7 +116,7 @@ class GpuPath:
         o = torch.zeros_like(q)
         keep = torch.full((w.B,), 255, dtype=torch.uint8, device=DEV)
         P.dllava_decode_attn_append(q, k, v, w.B, logits, theta, keep_override, self.cache, self.scale, o, keep,
-                                    self.err, self.ws)
+                                    self.err, self.ws_decode)
         return o, keep
 
     def cache_rows(self, b: int, L: int):
