@@ -104,6 +104,27 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
   return v;
 }
 
+// ---- cross-block hand-off without cache flushes ----------------------------------------------------
+// Data that one block leaves for another goes through device-scope relaxed atomics: the stores write
+// through to the memory side and the loads miss the per-XCD caches, so no L2 write-back / invalidate
+// (which a device-scope fence would cost on every block) is needed.  Protocol: every thread st_agent()s
+// its values, block_publish() waits until those stores have completed and joins the block, one thread
+// bumps the counter with add_agent(); the block that sees the final count ld_agent()s the data.
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int add_agent(int* p, int v) {
+  return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void zero_agent(int* p) { __hip_atomic_store(p, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void block_publish() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+}
+
 // The keep decision of Eq. 5 for one text token: margin of the float32 logits against a threshold.
 __device__ __forceinline__ bool keep_from_logits(const float* logits, int row, float threshold) {
   const float margin = logits[2 * row + 1] - logits[2 * row];

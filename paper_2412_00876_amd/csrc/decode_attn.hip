@@ -4,27 +4,32 @@
 // cached K/V byte is read by exactly one (sequence, head) query and there is one flop per byte.  The
 // kernel therefore uses fully coalesced 16-byte loads and VALU arithmetic, not matrix cores.
 //
-// ONE launch per step.  Grid (n_split, H, B), 256 threads = 4 waves per block.  Block (s, h, b) owns pages
-// [s*P/S, (s+1)*P/S) of the P = ceil(cache_len[b]/16) pages of sequence b; its waves take those pages
-// round-robin, each wave keeping the next page's 8 KiB of K and V in flight while it works on the current
-// one, and are merged through LDS.  Split 0 also folds in the current token (it always takes part in its
-// own attention) and, when the token is kept, stores its K/V at position cache_len[b], a slot no block
-// reads in this launch.
+// ONE launch per step.  Grid (n_split, H, B), NW waves per block (4 or 8).  The S*NW waves that serve
+// (b, h) take the P = ceil(cache_len[b]/16) pages of sequence b round-robin, 8 KiB of K and V per page,
+// and the waves of a block are merged through LDS.  The kernel is latency-bound at short contexts, so the
+// dependent-load chain is kept short: page ids and, with a single split, the first page itself are
+// requested before cache_len has arrived.  Split 0 also folds in the current token (it always takes part
+// in its own attention) and, when the token is kept, stores its K/V at position cache_len[b], a slot no
+// block reads in this launch.
 //
 // Cross-block steps use device-scope counters kept at the start of the workspace (zero before the first
 // call; each is reset by the block that consumes it):
-//   * the last of the S blocks of (b, h) to finish merges the S partial (max, sum, accumulator) triples in
-//     split order -- a fixed order, so the result is bit-reproducible -- and writes o[b, h];
-//   * the last of the H heads of sequence b to be finalised commits the keep decision: cache_len[b] += 1.
-//     Every block of sequence b has read cache_len[b] long before, so the update cannot race with a read.
+//   * cache_len[b] may only advance once every block of sequence b has read it.  Each block draws a ticket
+//     right after its read; the block holding the last ticket commits the keep decision (cache_len[b] += 1).
+//     Same-address atomics are slow (they serialise at the memory side), but drawn at the start their
+//     latency is hidden behind the page stream.
+//   * with S > 1, the last of the S blocks of (b, h) to finish merges the S partial (max, sum, accumulator)
+//     triples in split order -- a fixed order, so the result is bit-reproducible -- and writes o[b, h].
+#include <limits.h>
+
 #include "attend.h"
 
 namespace dllava {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / kWave;
 constexpr int kMaxSplit = 16;
+constexpr int kCnt = 64;  // int32 slots per counter: each counter owns 256 bytes, because atomics that share a
+                          // memory line serialise at the memory side even when their addresses differ
 
 struct DecodeArgs {
   const void* q;
@@ -41,8 +46,9 @@ struct DecodeArgs {
   int32_t H;
   int32_t B;
   int32_t n_split;
-  int32_t* cnt_bh;  // [B*H] splits finished per (b, h)
-  int32_t* cnt_b;   // [B]   heads finalised per sequence
+  int32_t* cnt_bh;    // [B*H] blocks of (b, h) that have read cache_len[b]   (used when S > 1)
+  int32_t* cnt_done;  // [B*H] blocks of (b, h) whose partial result is published
+  int32_t* cnt_b;     // [B]   heads of sequence b all of whose blocks have read cache_len[b]
   float* part_acc;  // [B*H*S][DH]
   float* part_ml;   // [B*H*S][2]
   void* o;
@@ -167,19 +173,13 @@ __device__ __forceinline__ void consume_page(const PageRegs<T, DH>& pr, int nval
   st.m = mx;
 }
 
-template <typename T, int DH>
-__global__ __launch_bounds__(kThreads) void decode_attn_kernel(DecodeArgs a) {
+template <typename T, int DH, int NW>
+__global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
   using C = AttendCfg<T, DH>;
   const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
   const int S = a.n_split, H = a.H;
   const int cap = a.max_pages * kPage;
-  int L = a.cache_len[b];
-  L = L < 0 ? 0 : (L > cap ? cap : L);
-  const int P = (L + kPage - 1) / kPage;
-  const int p0 = static_cast<int>(static_cast<int64_t>(s) * P / S);
-  const int p1 = static_cast<int>(static_cast<int64_t>(s + 1) * P / S);
-
   const size_t bh = static_cast<size_t>(b) * H + h;
   const T* qrow = static_cast<const T*>(a.q) + bh * DH;
   const T* knew = static_cast<const T*>(a.k_new) + bh * DH;
@@ -189,19 +189,36 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(DecodeArgs a) {
   const size_t tile = static_cast<size_t>(kPage) * DH;  // elements of one (page, K|V, head) tile
   const size_t vofs = static_cast<size_t>(H) * tile;    // from a K tile to the V tile of the same page/head
 
+  // Pages are dealt round-robin to the S*NW waves that serve (b, h): wave g takes pages g, g+S*NW, ...
+  // Its first page index does not depend on cache_len, so the page-id load and (with one split) the
+  // first K/V loads are issued without waiting for the length: every block-table entry names an
+  // allocated page, so the loads are in bounds even if the page turns out to lie beyond the end.
+  const int stride = S * NW;
+  int p = s * NW + w;
+  int pg = bt[p < a.max_pages ? p : a.max_pages - 1];
+  int L = a.cache_len[b];
+  PageRegs<T, DH> cur;
+  const bool spec = (S == 1);
+  if (spec) {
+    const T* kt = pages + (static_cast<size_t>(pg) * 2 * H + h) * tile;
+    load_page<T, DH>(cur, kt, kt + vofs);
+  }
+  // Thread 0 announces that this block has read cache_len[b].  The increment depends on the loaded value, so
+  // it cannot be issued before the load has returned; its own latency hides behind the page stream.
+  int ticket = 0;
+  if (tid == 0) ticket = add_agent(S == 1 ? &a.cnt_b[b * kCnt] : &a.cnt_bh[(static_cast<size_t>(b) * H + h) * kCnt], 1 + (L == INT32_MIN));
+  L = L < 0 ? 0 : (L > cap ? cap : L);
+  const int P = (L + kPage - 1) / kPage;
+  if (!spec && p < P) {
+    const T* kt = pages + (static_cast<size_t>(pg) * 2 * H + h) * tile;
+    load_page<T, DH>(cur, kt, kt + vofs);
+  }
+  int pg_next = (p + stride < P) ? bt[p + stride] : 0;
+
   LaneDot<T> qd;
   qd.init(qrow, lane % C::G, a.scale_log2);
   AttnState<C::E> st;
   st.clear();
-
-  // pipeline: the next page's loads are issued before the current page is consumed
-  int p = p0 + w;
-  PageRegs<T, DH> cur;
-  if (p < p1) {
-    const T* kt = pages + (static_cast<size_t>(bt[p]) * 2 * H + h) * tile;
-    load_page<T, DH>(cur, kt, kt + vofs);
-  }
-  int pg_next = (p + kWaves < p1) ? bt[p + kWaves] : 0;
 
   if (s == 0 && w == 0) {  // the current token, folded into lane group 0
     const uint4 kr = *reinterpret_cast<const uint4*>(knew + (lane % C::G) * C::E);
@@ -214,26 +231,24 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(DecodeArgs a) {
     }
   }
 
-  while (p < p1) {
-    const int pn = p + kWaves;
-    PageRegs<T, DH> nxt;
-    if (pn < p1) {
-      const T* kt = pages + (static_cast<size_t>(pg_next) * 2 * H + h) * tile;
-      load_page<T, DH>(nxt, kt, kt + vofs);
-      if (pn + kWaves < p1) pg_next = bt[pn + kWaves];
-    }
+  while (p < P) {
+    const int pn = p + stride;
     const int nvalid = L - p * kPage;
     if (nvalid >= kPage)
       consume_page<T, DH, false>(cur, kPage, qd, st);
     else
       consume_page<T, DH, true>(cur, nvalid, qd, st);
-    if (pn < p1) cur = nxt;
+    if (pn < P) {
+      const T* kt = pages + (static_cast<size_t>(pg_next) * 2 * H + h) * tile;
+      load_page<T, DH>(cur, kt, kt + vofs);
+      if (pn + stride < P) pg_next = bt[pn + stride];
+    }
     p = pn;
   }
   merge_groups<T, DH>(st);
 
-  __shared__ float sm_acc[kWaves][DH];
-  __shared__ float sm_m[kWaves], sm_l[kWaves];
+  __shared__ float sm_acc[NW][DH];
+  __shared__ float sm_m[NW], sm_l[NW];
   __shared__ int sm_flag;
   if (lane < C::G) {
 #pragma unroll
@@ -249,8 +264,8 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(DecodeArgs a) {
     constexpr int kChunks = DH * sizeof(T) / 16;
     if (tid < 2 * kChunks) {
       const int kv = tid / kChunks, cc = tid % kChunks;
-      const int pg = bt[L / kPage];
-      T* dst = pages + ((static_cast<size_t>(pg) * 2 + kv) * H + h) * tile + static_cast<size_t>(L % kPage) * DH;
+      const int pga = bt[L / kPage];
+      T* dst = pages + ((static_cast<size_t>(pga) * 2 + kv) * H + h) * tile + static_cast<size_t>(L % kPage) * DH;
       const T* src = kv ? vnew : knew;
       reinterpret_cast<uint4*>(dst)[cc] = reinterpret_cast<const uint4*>(src)[cc];
     }
@@ -261,82 +276,128 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(DecodeArgs a) {
   if (tid < DH) {
     M = sm_m[0];
 #pragma unroll
-    for (int i = 1; i < kWaves; ++i) M = fmaxf(M, sm_m[i]);
+    for (int i = 1; i < NW; ++i) M = fmaxf(M, sm_m[i]);
 #pragma unroll
-    for (int i = 0; i < kWaves; ++i) {
+    for (int i = 0; i < NW; ++i) {
       const float wgt = (sm_m[i] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sm_m[i] - M);
       l += wgt * sm_l[i];
       acc += wgt * sm_acc[i][tid];
     }
   }
+  bool committer = (S == 1) && (ticket == H - 1);
+  bool finalize = true;  // this block writes o[b, h]
   if (S > 1) {
+    // every block of (b, h) has read the length once the last reader's ticket is out; that block tells the
+    // sequence counter (second level), again long before the results are due
+    if (tid == 0 && ticket == S - 1) {
+      zero_agent(&a.cnt_bh[bh * kCnt]);
+      sm_flag = (add_agent(&a.cnt_b[b * kCnt], 1) == H - 1);
+    } else if (tid == 0) {
+      sm_flag = 0;
+    }
     if (tid < DH) {
       const size_t ps = bh * S + s;
-      a.part_acc[ps * DH + tid] = acc;
+      st_agent(a.part_acc + ps * DH + tid, acc);
       if (tid == 0) {
-        a.part_ml[2 * ps] = M;
-        a.part_ml[2 * ps + 1] = l;
+        st_agent(a.part_ml + 2 * ps, M);
+        st_agent(a.part_ml + 2 * ps + 1, l);
       }
     }
-    __threadfence();  // partials visible device-wide before the counter moves
+    block_publish();  // partials have reached the memory side before the counter moves
+    committer = (tid == 0) && sm_flag;
     __syncthreads();
-    if (tid == 0) sm_flag = (atomicAdd(&a.cnt_bh[bh], 1) == S - 1);
+    if (tid == 0) sm_flag = (add_agent(&a.cnt_done[bh * kCnt], 1) == S - 1);
     __syncthreads();
-    if (!sm_flag) return;
-    __threadfence();
-    if (tid < DH) {
-      const float* ml = a.part_ml + 2 * bh * S;
-      M = ml[0];
-      for (int i = 1; i < S; ++i) M = fmaxf(M, ml[2 * i]);
-      l = 0.f;
-      acc = 0.f;
-      for (int i = 0; i < S; ++i) {
-        const float m = ml[2 * i];
-        const float wgt = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - M);
-        l += wgt * ml[2 * i + 1];
-        acc += wgt * a.part_acc[(bh * S + i) * DH + tid];
+    finalize = sm_flag != 0;
+    if (finalize) {
+      if (tid < DH) {
+        // all S partials are requested before any is used (S <= kMaxSplit): a dependent chain of
+        // device-scope loads would cost one memory round trip per split
+        const float* ml = a.part_ml + 2 * bh * S;
+        float pm[kMaxSplit], pl[kMaxSplit], pa[kMaxSplit];
+#pragma unroll
+        for (int i = 0; i < kMaxSplit; ++i) {
+          const bool ok = i < S;
+          pm[i] = ok ? ld_agent(ml + 2 * i) : -INFINITY;
+          pl[i] = ok ? ld_agent(ml + 2 * i + 1) : 0.f;
+          pa[i] = ok ? ld_agent(a.part_acc + (bh * S + i) * DH + tid) : 0.f;
+        }
+        M = pm[0];
+#pragma unroll
+        for (int i = 1; i < kMaxSplit; ++i) M = fmaxf(M, pm[i]);
+        l = 0.f;
+        acc = 0.f;
+#pragma unroll
+        for (int i = 0; i < kMaxSplit; ++i) {
+          const float wgt = (pm[i] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(pm[i] - M);
+          l += wgt * pl[i];
+          acc += wgt * pa[i];
+        }
       }
+      if (tid == 0) zero_agent(&a.cnt_done[bh * kCnt]);
     }
-    if (tid == 0) a.cnt_bh[bh] = 0;
   }
   // split 0 always holds the current token, so l > 0
-  if (tid < DH) Elem<T>::store(static_cast<T*>(a.o) + bh * DH + tid, acc / l);
+  if (finalize && tid < DH) Elem<T>::store(static_cast<T*>(a.o) + bh * DH + tid, acc / l);
 
-  if (tid == 0 && atomicAdd(&a.cnt_b[b], 1) == H - 1) {  // last head of sequence b: commit the decision
-    a.cnt_b[b] = 0;
+  // The block that drew the last ticket of sequence b knows every block of b has read cache_len[b]:
+  // it alone advances it, so the update cannot race with a read.
+  if (tid == 0 && committer) {
+    zero_agent(&a.cnt_b[b * kCnt]);
     const bool keep = decode_keep(a.logits, a.keep_override, a.threshold, b);
     if (a.keep_out) a.keep_out[b] = keep ? 1 : 0;
     if (keep) {
-      const int Lr = a.cache_len[b];
-      if (Lr >= 0 && Lr < cap)
-        a.cache_len[b] = Lr + 1;
+      if (L < cap)
+        a.cache_len[b] = L + 1;
       else if (a.err_flag)
         *a.err_flag = 1;
     }
   }
 }
 
-int pick_splits(int64_t n_bh, int max_pages) {
-  static const int forced = [] {
-    const char* e = getenv("DLLAVA_DECODE_SPLITS");
-    return e ? atoi(e) : 0;
-  }();
-  int64_t S = forced > 0 ? forced : ceil_div(1536, n_bh);
-  if (S > kMaxSplit) S = kMaxSplit;
-  if (S > max_pages) S = max_pages;
-  if (S < 1) S = 1;
-  return static_cast<int>(S);
+struct DecodeShape {
+  int nw;       // waves per block: 4 or 8
+  int n_split;  // blocks per (sequence, head)
+};
+
+int env_int(const char* name) {
+  const char* e = getenv(name);
+  return e ? atoi(e) : 0;
 }
 
-template <typename T, int DH>
-int launch(const DecodeArgs& a, hipStream_t st) {
+// Launch shape from host-known sizes only (cache lengths live on the device).  Measured on MI355X: about
+// 16 waves per CU (4096 in all) already saturate the memory pipeline, and a single split per (b, h) wins
+// whenever that many waves are available, because every further split adds a round trip through memory
+// for the partial results and speculative first-page loads are only used with one split.
+DecodeShape pick_shape(int64_t n_bh, int max_pages) {
+  DecodeShape sh;
+  const int64_t target_waves = 4096;
+  sh.nw = n_bh * 8 <= 2 * target_waves ? 8 : 4;
+  int64_t S = target_waves / (n_bh * sh.nw);
+  if (S > kMaxSplit) S = kMaxSplit;
+  const int64_t max_useful = ceil_div(max_pages, sh.nw);
+  if (S > max_useful) S = max_useful;
+  if (S < 1) S = 1;
+  sh.n_split = static_cast<int>(S);
+  // tuning overrides
+  if (int v = env_int("DLLAVA_DECODE_WAVES")) sh.nw = (v == 4 || v == 8) ? v : sh.nw;
+  if (int v = env_int("DLLAVA_DECODE_SPLITS")) sh.n_split = v > kMaxSplit ? kMaxSplit : (v < 1 ? 1 : v);
+  return sh;
+}
+
+template <typename T, int DH, int NW>
+int launch2(const DecodeArgs& a, hipStream_t st) {
   dim3 grid(a.n_split, a.H, a.B);
-  hipLaunchKernelGGL((decode_attn_kernel<T, DH>), grid, dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL((decode_attn_kernel<T, DH, NW>), grid, dim3(NW * kWave), 0, st, a);
   DLLAVA_CHECK_LAUNCH("decode_attn_kernel");
   return DLLAVA_OK;
 }
+template <typename T, int DH>
+int launch(const DecodeArgs& a, const DecodeShape& sh, hipStream_t st) {
+  return sh.nw == 8 ? launch2<T, DH, 8>(a, st) : launch2<T, DH, 4>(a, st);
+}
 
-size_t counter_bytes(int64_t B, int64_t H) { return round_up(static_cast<size_t>(B * H + B) * sizeof(int32_t), 256); }
+size_t counter_bytes(int64_t B, int64_t H) { return static_cast<size_t>(2 * B * H + B) * kCnt * sizeof(int32_t); }
 
 }  // namespace
 }  // namespace dllava
@@ -376,11 +437,13 @@ extern "C" int dllava_decode_attn_append(const void* q, const void* k_new, const
   a.scale_log2 = scale * 1.44269504088896340736f;
   a.pages = cache->pages; a.block_table = cache->block_table; a.cache_len = cache->cache_len;
   a.max_pages = cache->max_pages_per_seq; a.H = cache->H; a.B = B;
-  a.n_split = pick_splits(static_cast<int64_t>(B) * cache->H, cache->max_pages_per_seq);
+  const DecodeShape sh = pick_shape(static_cast<int64_t>(B) * cache->H, cache->max_pages_per_seq);
+  a.n_split = sh.n_split;
   const size_t n = static_cast<size_t>(B) * cache->H * kMaxSplit;
   char* ws = static_cast<char*>(workspace);
   a.cnt_bh = reinterpret_cast<int32_t*>(ws);
-  a.cnt_b = a.cnt_bh + static_cast<size_t>(B) * cache->H;
+  a.cnt_done = a.cnt_bh + static_cast<size_t>(B) * cache->H * kCnt;
+  a.cnt_b = a.cnt_done + static_cast<size_t>(B) * cache->H * kCnt;
   ws += counter_bytes(B, cache->H);
   a.part_acc = reinterpret_cast<float*>(ws);
   a.part_ml = reinterpret_cast<float*>(ws + round_up(n * cache->Dh * sizeof(float), 256));
@@ -388,6 +451,6 @@ extern "C" int dllava_decode_attn_append(const void* q, const void* k_new, const
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bool bf = cache->dtype == DLLAVA_BF16;
-  if (cache->Dh == 128) return bf ? launch<bf16_t, 128>(a, st) : launch<float, 128>(a, st);
-  return bf ? launch<bf16_t, 64>(a, st) : launch<float, 64>(a, st);
+  if (cache->Dh == 128) return bf ? launch<bf16_t, 128>(a, sh, st) : launch<float, 128>(a, sh, st);
+  return bf ? launch<bf16_t, 64>(a, sh, st) : launch<float, 64>(a, sh, st);
 }

@@ -42,6 +42,7 @@ constexpr int kMaxCounters = 1024;
 constexpr int kSkWaves = 8;
 constexpr int kSkThreads = kSkWaves * kWave;
 constexpr int kSkUnits = 16;
+constexpr int kSkBatch = 16;  // k-steps whose loads are issued together
 
 template <int NT>
 __global__ __launch_bounds__(kSkThreads) void score_skinny_kernel(ScoreArgs a, int32_t* counter, float* partial) {
@@ -69,17 +70,30 @@ __global__ __launch_bounds__(kSkThreads) void score_skinny_kernel(ScoreArgs a, i
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // wave w takes k-steps w, w+8, ... (32 elements each)
+  // wave w takes k-steps w, w+8, ... (32 elements each), kSkBatch of them in flight at a time: the kernel
+  // is a stream over W1, so what matters is the number of outstanding 16-byte loads, not the MFMA rate
   const int ksteps = static_cast<int>(d / 32);
   const int n_it = (ksteps - w + kSkWaves - 1) / kSkWaves;
-  for (int it = 0; it < n_it; ++it) {
-    const int ks = w + it * kSkWaves;
-    const bf16x8 fa = as_frag(*reinterpret_cast<const uint4*>(wrow + static_cast<int64_t>(ks) * 32));
+  const int rot = ksteps / nblk > 0 ? ksteps / nblk : 1;
+  for (int it0 = 0; it0 < n_it; it0 += kSkBatch) {
+    uint4 ra[kSkBatch], rb[NT][kSkBatch];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const bf16x8 fb = as_frag(*reinterpret_cast<const uint4*>(xrow[t] + static_cast<int64_t>(ks) * 32));
-      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, acc[t], 0, 0, 0);
+    for (int u = 0; u < kSkBatch; ++u) {
+      const bool ok = it0 + u < n_it;
+      // blocks start at different columns, or all of them would sweep W1 in lockstep through the same few
+      // memory channels (rows are 2*d bytes apart); the order of a block's sum is fixed by its index
+      const int ks = (w + (ok ? it0 + u : 0) * kSkWaves + blk * rot) % ksteps;
+      const int64_t ko = static_cast<int64_t>(ks) * 32;
+      ra[u] = *reinterpret_cast<const uint4*>(wrow + ko);
+      if (!ok) ra[u] = make_uint4(0, 0, 0, 0);  // a zero W1 fragment contributes nothing
+#pragma unroll
+      for (int t = 0; t < NT; ++t) rb[t][u] = *reinterpret_cast<const uint4*>(xrow[t] + ko);
     }
+#pragma unroll
+    for (int u = 0; u < kSkBatch; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(ra[u]), as_frag(rb[t][u]), acc[t], 0, 0, 0);
   }
 #pragma unroll
   for (int t = 0; t < NT; ++t)
@@ -111,23 +125,35 @@ __global__ __launch_bounds__(kSkThreads) void score_skinny_kernel(ScoreArgs a, i
       p1 += __shfl_xor(p1, 32, kWave);
       const int tok = t * 16 + lane;
       if (lane < 16 && tok < M) {
-        partial[(static_cast<size_t>(blk) * (NT * 16) + tok) * 2] = p0;
-        partial[(static_cast<size_t>(blk) * (NT * 16) + tok) * 2 + 1] = p1;
+        st_agent(partial + static_cast<size_t>(2 * tok) * nblk + blk, p0);      // [token][logit][block]
+        st_agent(partial + static_cast<size_t>(2 * tok + 1) * nblk + blk, p1);
       }
     }
-    __threadfence();
-    if (lane == 0) sm_last = (atomicAdd(counter, 1) == nblk - 1);
   }
+  block_publish();
+  if (tid == 0) sm_last = (add_agent(counter, 1) == nblk - 1);
   __syncthreads();
   if (!sm_last) return;
-  __threadfence();
-  for (int i = tid; i < 2 * M; i += kSkThreads) {
-    const int tok = i >> 1, c = i & 1;
-    float s = a.b2 ? a.b2[c] : 0.f;
-    for (int b = 0; b < nblk; ++b) s += partial[(static_cast<size_t>(b) * (NT * 16) + tok) * 2 + c];
-    a.logits[i] = s;
+  // Last block: logit (tok, c) = b2[c] + sum over blocks.  A dependent chain of device-scope loads costs a
+  // memory round trip per term, so each (tok, c) pair is summed by a whole wave: lanes load the block
+  // partials side by side (all pairs of the wave in flight together) and a butterfly adds them.
+  constexpr int kPairsPerWave = NT * 16 * 2 / kSkWaves;
+  float v[kPairsPerWave];
+#pragma unroll
+  for (int j = 0; j < kPairsPerWave; ++j) {
+    const int pair = w + j * kSkWaves;  // = 2*tok + c
+    float t = 0.f;
+    if (pair < 2 * M)
+      for (int b = lane; b < nblk; b += kWave) t += ld_agent(partial + static_cast<size_t>(pair) * nblk + b);
+    v[j] = t;
   }
-  if (tid == 0) *counter = 0;
+#pragma unroll
+  for (int j = 0; j < kPairsPerWave; ++j) {
+    const int pair = w + j * kSkWaves;
+    const float t = wave_sum(v[j]);
+    if (lane == 0 && pair < 2 * M) a.logits[pair] = t + (a.b2 ? a.b2[pair & 1] : 0.f);
+  }
+  if (tid == 0) zero_agent(counter);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -264,24 +290,29 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(2, 2)
   {
     const int tok = tid >> 1, c = tid & 1;  // 256 threads = 128 tokens x 2 logits
     const int64_t m = static_cast<int64_t>(mt) * kTM + tok;
-    if (m < M) partial[(static_cast<size_t>(ut) * M + m) * 2 + c] = sm_p[0][tok][c] + sm_p[1][tok][c];
+    if (m < M) st_agent(partial + (static_cast<size_t>(ut) * M + m) * 2 + c, sm_p[0][tok][c] + sm_p[1][tok][c]);
   }
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) sm_last = (atomicAdd(&counters[mt % kMaxCounters], 1) == n_ut - 1);
+  block_publish();
+  if (tid == 0) sm_last = (add_agent(&counters[mt % kMaxCounters], 1) == n_ut - 1);
   __syncthreads();
   if (!sm_last) return;
-  __threadfence();
   {
     const int tok = tid >> 1, c = tid & 1;
     const int64_t m = static_cast<int64_t>(mt) * kTM + tok;
     if (m < M && score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m) >= 0) {
       float s = a.b2 ? a.b2[c] : 0.f;
-      for (int t = 0; t < n_ut; ++t) s += partial[(static_cast<size_t>(t) * M + m) * 2 + c];
+      for (int t0 = 0; t0 < n_ut; t0 += 16) {  // 16 independent loads in flight, then a fixed-order sum
+        float v[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t)
+          v[t] = (t0 + t < n_ut) ? ld_agent(partial + (static_cast<size_t>(t0 + t) * M + m) * 2 + c) : 0.f;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) s += v[t];
+      }
       a.logits[2 * m + c] = s;
     }
   }
-  if (tid == 0) counters[mt % kMaxCounters] = 0;
+  if (tid == 0) zero_agent(&counters[mt % kMaxCounters]);
 }
 
 }  // namespace
