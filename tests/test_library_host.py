@@ -1,0 +1,103 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares, its pure host
+queries behave, and argument errors are reported on the host before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2412_00876_amd", "lib", "libdllava.so")
+HDR = os.path.join(ROOT, "include", "dllava.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2412_00876_amd import build
+        build.build(verbose=False)
+    import paper_2412_00876_amd.binding as b
+    return b
+
+
+def _declared_functions():
+    src = open(HDR).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(dllava_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"dllava_score", "dllava_select_compact", "dllava_prefill_attn", "dllava_decode_attn_append"} <= set(names)
+    raw = C.CDLL(LIB)
+    for n in names:
+        assert hasattr(raw, n), n
+    assert set(lib.EXPORTS) == set(names)
+
+
+def test_version_and_workspace_queries(lib):
+    assert lib.dllava_version() >= 100
+    for q in (lib.dllava_score_workspace(16, 4096, 1024, lib.BF16), lib.dllava_score_workspace(9216, 4096, 1024, lib.BF16),
+              lib.dllava_select_compact_workspace(16, 10800), lib.dllava_decode_workspace(16, 32, 128, 78)):
+        assert q > 0 and q % 256 == 0
+    # monotone in the problem size
+    assert lib.dllava_select_compact_workspace(16, 20000) > lib.dllava_select_compact_workspace(16, 10000)
+    assert lib.dllava_decode_workspace(32, 40, 128, 50) > lib.dllava_decode_workspace(16, 32, 128, 50)
+    assert lib.dllava_score_workspace(0, 4096, 1024, lib.BF16) >= 256
+
+
+def _expect(lib, status, fn, *args):
+    rc = fn(*args)
+    assert rc == status, (rc, lib.lib().dllava_last_error().decode())
+    assert lib.lib().dllava_last_error().decode() != ""
+
+
+def test_argument_errors_are_reported_on_the_host(lib):
+    L = lib.lib()
+    EINVAL, ENULL, ESHAPE, EDTYPE, EWORKSPACE = -1, -2, -3, -4, -6
+    fake = C.c_void_p(0x1000)       # never dereferenced: every call below must fail validation first
+    # score
+    _expect(lib, EDTYPE, L.dllava_score, fake, 64, 4, 0, None, None, None, 64, 16, fake, None, fake, None, 7, fake, fake, 1 << 20, None)
+    _expect(lib, ESHAPE, L.dllava_score, fake, 63, 4, 0, None, None, None, 63, 16, fake, None, fake, None, 1, fake, fake, 1 << 20, None)
+    _expect(lib, ENULL, L.dllava_score, None, 64, 4, 0, None, None, None, 64, 16, fake, None, fake, None, 1, fake, fake, 1 << 20, None)
+    _expect(lib, EWORKSPACE, L.dllava_score, fake, 64, 4, 0, None, None, None, 64, 16, fake, None, fake, None, 1, fake, None, 0, None)
+    # select_compact
+    cache = lib._KvCache(0x1000, 0x1000, 0x1000, 4, 2, 16, 2, 64, 1)
+    args = lambda mode, ratio, thr, d, dtype, ws, wsb: (fake, 2, fake, fake, fake, 40, mode, ratio, thr, fake, fake, d, None, None,
+                                                         None, None, None, fake, fake, fake, None, dtype, ws, wsb, None)
+    _expect(lib, EINVAL, L.dllava_select_compact, *args(0, 1.5, 0.0, 64, 1, fake, 1 << 20))
+    _expect(lib, EINVAL, L.dllava_select_compact, *args(0, float("nan"), 0.0, 64, 1, fake, 1 << 20))
+    _expect(lib, EINVAL, L.dllava_select_compact, *args(1, 0.5, float("nan"), 64, 1, fake, 1 << 20))
+    _expect(lib, EINVAL, L.dllava_select_compact, *args(3, 0.5, 0.0, 64, 1, fake, 1 << 20))
+    _expect(lib, ESHAPE, L.dllava_select_compact, *args(0, 0.5, 0.0, 36, 1, fake, 1 << 20))
+    _expect(lib, EWORKSPACE, L.dllava_select_compact, *args(0, 0.5, 0.0, 64, 1, fake, 16))
+    _expect(lib, EDTYPE, L.dllava_select_compact, *args(0, 0.5, 0.0, 64, 9, fake, 1 << 20))
+    # prefill
+    _expect(lib, ESHAPE, L.dllava_prefill_attn, fake, fake, fake, None, 1, fake, 8, 2, 96, 0.1, fake, 1, None)
+    _expect(lib, EINVAL, L.dllava_prefill_attn, fake, fake, fake, None, 1, fake, 8, 2, 64, -1.0, fake, 1, None)
+    _expect(lib, ENULL, L.dllava_prefill_attn, fake, None, None, None, 1, fake, 8, 2, 64, 0.1, fake, 1, None)
+    bad = lib._KvCache(0x1000, 0x1000, 0x1000, 4, 2, 32, 2, 64, 1)          # page_size 32
+    _expect(lib, ESHAPE, L.dllava_prefill_attn, fake, None, None, C.byref(bad), 1, fake, 8, 2, 64, 0.1, fake, 1, None)
+    # decode
+    _expect(lib, ENULL, L.dllava_decode_attn_append, fake, fake, fake, 2, None, 0.0, None, C.byref(cache), 0.1, fake, None, None, fake, 1 << 24, None)
+    _expect(lib, EWORKSPACE, L.dllava_decode_attn_append, fake, fake, fake, 2, fake, 0.0, None, C.byref(cache), 0.1, fake, None, None, fake, 64, None)
+    _expect(lib, ENULL, L.dllava_decode_attn_append, fake, fake, fake, 2, fake, 0.0, None, None, 0.1, fake, None, None, fake, 1 << 24, None)
+    _expect(lib, EINVAL, L.dllava_decode_attn_append, fake, fake, fake, 2, fake, float("nan"), None, C.byref(cache), 0.1, fake, None, None, fake, 1 << 24, None)
+
+
+def test_noop_sizes_return_ok_without_a_gpu(lib):
+    L = lib.lib()
+    fake = C.c_void_p(0x1000)
+    assert L.dllava_score(fake, 64, 0, 0, None, None, None, 64, 16, fake, None, fake, None, 1, fake, None, 0, None) == 0
+    cache = lib._KvCache(0x1000, 0x1000, 0x1000, 4, 2, 16, 2, 64, 1)
+    assert L.dllava_decode_attn_append(fake, fake, fake, 0, fake, 0.0, None, C.byref(cache), 0.1, fake, None, None, None, 0, None) == 0
+    assert L.dllava_prefill_attn(fake, fake, fake, None, 0, fake, 0, 2, 64, 0.1, fake, 1, None) == 0
+
+
+def test_product_path_has_no_cpu_fallback():
+    """The package must not import the oracle (or anything else that could stand in for the kernels)."""
+    pkg = os.path.join(ROOT, "paper_2412_00876_amd")
+    for fn in os.listdir(pkg):
+        if fn.endswith(".py"):
+            src = open(os.path.join(pkg, fn)).read()
+            assert "oracle" not in src, fn
