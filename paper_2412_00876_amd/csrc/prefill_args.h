@@ -1,0 +1,25 @@
+// Arguments of the prefill-attention kernels.
+#pragma once
+
+#include "common.h"
+
+namespace dllava {
+
+struct PrefillArgs {
+  const void* Q;
+  const void* K;
+  const void* V;
+  void* O;
+  const int32_t* off;
+  int32_t B, H;
+  float scale_log2;
+  // keys/values come from the paged cache when K == nullptr
+  const void* pages;
+  const int32_t* block_table;
+  int32_t max_pages;
+};
+
+// matrix-core path (prefill_mfma.hip); returns 1 if it does not handle the shape
+int prefill_mfma_launch(const PrefillArgs& a, int64_t rows, int Dh, hipStream_t st);
+
+}  // namespace dllava

@@ -4,22 +4,9 @@
 // 16-token chunks with the VALU routine of attend.h.  It serves float32 inputs and head sizes the
 // matrix-core kernel does not cover.
 #include "attend.h"
+#include "prefill_args.h"
 
 namespace dllava {
-
-struct PrefillArgs {
-  const void* Q;
-  const void* K;
-  const void* V;
-  void* O;
-  const int32_t* off;
-  int32_t B, H;
-  float scale_log2;
-  // keys/values from the paged cache when K == nullptr
-  const void* pages;
-  const int32_t* block_table;
-  int32_t max_pages;
-};
 
 namespace {
 
@@ -86,9 +73,6 @@ int launch_generic(const PrefillArgs& a, int64_t rows, hipStream_t st) {
 }
 
 }  // namespace
-
-// matrix-core path (prefill_mfma.hip); returns 1 if it does not handle the shape
-int prefill_mfma_launch(const PrefillArgs& a, int64_t rows, int Dh, hipStream_t st);
 
 }  // namespace dllava
 
