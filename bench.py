@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--pmc-probe", type=int, default=0, metavar="L",
+                    help="counter probe for rocprofv3 --pmc: one 256 MiB device copy (calibration), then 3 decode "
+                         "launches at cache length L with appends disabled; prints the algorithmic bytes and exits")
     return ap.parse_args()
 
 
@@ -192,6 +195,34 @@ def cpu_baseline(path, seconds):
                       f"({wall:.1f} s wall), extrapolated per sequence / per token to the whole step"}
 
 
+def pmc_probe(path, torch, L):
+    """Dispatches whose HBM counters are read with `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`:
+    a plain device-to-device copy of known size (the scale of the counters), then the decode kernel."""
+    w = path.w
+    cap = path.cache.max_pages_per_seq * 16
+    if L > cap:
+        raise SystemExit(f"--pmc-probe {L} exceeds the cache capacity {cap} of this workload (raise --decode-steps)")
+    n = 256 << 20
+    src = torch.full((n,), 7, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)                                   # calibration dispatch: reads n bytes, writes n bytes
+    torch.cuda.synchronize()
+    path.score_vision(); path.select_compact()      # fills the first kept_len tokens of every sequence
+    path.pages.normal_()                             # slots beyond that: arbitrary finite data
+    path.cache_len.fill_(L)
+    keep0 = torch.zeros(w.B, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    for _ in range(3):
+        path.P.dllava_decode_attn_append(path.dec["q"][0], path.dec["k"][0], path.dec["v"][0], w.B, None, 0.0, keep0,
+                                         path.cache, path.scale, path.o_dec[0], path.keep_dec[0], path.err,
+                                         path.ws_decode)
+    torch.cuda.synchronize()
+    es = 2 if w.dtype == "bf16" else 4
+    print(json.dumps({"pmc_probe": True, "copy_bytes_read": n, "copy_bytes_written": n, "cache_len": L,
+                      "decode_algorithmic_bytes_per_launch": w.B * L * 2 * w.H * w.Dh * es}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -216,6 +247,9 @@ def main():
 
     stream = torch.cuda.Stream()
     graph = None
+    if args.pmc_probe:
+        pmc_probe(path, torch, args.pmc_probe)
+        return
     path.calibrate_theta()
     with torch.cuda.stream(stream):
         path.step()                                     # eager once: validates arguments, warms caches
