@@ -28,6 +28,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+# HBM bytes moved per algorithmic byte by the decode kernel, from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE, each
+# scaled by its reading for a 256 MiB copy): profiles/decode_attn_c3_hbm_counters.txt
+DECODE_TRAFFIC_PER_ALGORITHMIC_BYTE = 1.027
 
 
 def parse():
@@ -327,7 +330,8 @@ def main():
                    "B": B, "H": H, "Dh": Dh, "d": w.d, "decode_steps": T, "hip_graph": graph is not None,
                    "text_keep_fraction": float(keep.mean()), "theta": w.theta},
         "roofline": {"kernel": "decode_attn (dllava_decode_attn_append)", "bound": "hbm", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": DECODE_TRAFFIC_PER_ALGORITHMIC_BYTE * avg_bytes if ci == 2 else None,
                      "avg_launch_us": avg_ms * 1e3, "avg_bytes_per_launch": avg_bytes},
         "stages": {
             "score_vision": {"ms": ms_score, "tflops": flops_score / (ms_score * 1e-3) / 1e12,
