@@ -165,3 +165,4 @@ def dllava_decode_attn_append(q, k_new, v_new, B, logits, threshold, keep_overri
     _check(_lib.dllava_decode_attn_append(_p(q), _p(k_new), _p(v_new), B, _p(logits), threshold,
                                           _p(keep_override), cache.ref, scale, _p(o), _p(keep_out),
                                           _p(err_flag), wp, wb, _stream(stream)))
+

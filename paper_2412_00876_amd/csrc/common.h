@@ -108,7 +108,7 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
 // Data that one block leaves for another goes through device-scope relaxed atomics: the stores write
 // through to the memory side and the loads miss the per-XCD caches, so no L2 write-back / invalidate
 // (which a device-scope fence would cost on every block) is needed.  Protocol: every thread st_agent()s
-// its values, block_publish() waits until those stores have completed and joins the block, one thread
+// its values, block_publish() waits until those stores have been acknowledged and joins the block, one thread
 // bumps the counter with add_agent(); the block that sees the final count ld_agent()s the data.
 __device__ __forceinline__ void st_agent(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -120,8 +120,12 @@ __device__ __forceinline__ int add_agent(int* p, int v) {
   return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void zero_agent(int* p) { __hip_atomic_store(p, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+// All vector-memory operations this wave has issued, write-through stores included, have been acknowledged.
+// (A workgroup-scope release fence is not enough: on this target it emits no wait at all, and the counter
+// bump of another wave could then overtake the data.)
+__device__ __forceinline__ void wave_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void block_publish() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  wave_stores_done();
   __syncthreads();
 }
 

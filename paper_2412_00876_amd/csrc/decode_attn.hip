@@ -9,15 +9,16 @@
 // and the waves of a block are merged through LDS.  The kernel is latency-bound at short contexts, so the
 // dependent-load chain is kept short: page ids and, with a single split, the first page itself are
 // requested before cache_len has arrived.  Split 0 also folds in the current token (it always takes part
-// in its own attention) and, when the token is kept, stores its K/V at position cache_len[b], a slot no
-// block reads in this launch.
+// in its own attention).
+
 //
 // Cross-block steps use device-scope counters kept at the start of the workspace (zero before the first
 // call; each is reset by the block that consumes it):
 //   * cache_len[b] may only advance once every block of sequence b has read it.  Each block draws a ticket
-//     right after its read; the block holding the last ticket commits the keep decision (cache_len[b] += 1).
-//     Same-address atomics are slow (they serialise at the memory side), but drawn at the start their
-//     latency is hidden behind the page stream.
+//     right after its read; the block holding the last ticket commits the keep decision: it stores the new
+//     token's K/V for all heads at position cache_len[b] (a slot no block reads in this launch) and advances
+//     the length.  Same-address atomics are slow (they serialise at the memory side), but drawn at the start
+//     their latency is hidden behind the page stream.
 //   * with S > 1, the last of the S blocks of (b, h) to finish merges the S partial (max, sum, accumulator)
 //     triples in split order -- a fixed order, so the result is bit-reproducible -- and writes o[b, h].
 #include <limits.h>
@@ -55,11 +56,6 @@ struct DecodeArgs {
   uint8_t* keep_out;
   int32_t* err_flag;
 };
-
-__device__ __forceinline__ bool decode_keep(const float* logits, const uint8_t* keep_override, float threshold, int b) {
-  if (keep_override) return keep_override[b] != 0;
-  return keep_from_logits(logits, b, threshold);
-}
 
 // ---- one 16-token page held in registers -------------------------------------------------------
 template <typename T, int DH>
@@ -173,10 +169,39 @@ __device__ __forceinline__ void consume_page(const PageRegs<T, DH>& pr, int nval
   st.m = mx;
 }
 
+// Commits the decision of sequence b: keep flag, the new token's K/V for all heads at position cache_len[b],
+// the length.  Called by all threads of exactly one block per sequence and launch, after every block of the
+// sequence has read cache_len[b].
+template <typename T, int DH>
+__device__ __forceinline__ void commit_sequence(const DecodeArgs& a, int b) {
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int H = a.H, cap = a.max_pages * kPage;
+  const bool keep = a.keep_override ? a.keep_override[b] != 0 : keep_from_logits(a.logits, b, a.threshold);
+  const int L = a.cache_len[b];
+  if (tid == 0 && a.keep_out) a.keep_out[b] = keep ? 1 : 0;
+  if (!keep) return;  // block-uniform
+  if (L < 0 || L >= cap) {
+    if (tid == 0 && a.err_flag) *a.err_flag = 1;
+    return;
+  }
+  constexpr int kChunks = DH * sizeof(T) / 16;  // 16-byte chunks per (token, head)
+  const size_t tile = static_cast<size_t>(kPage) * DH;
+  const int pg = a.block_table[static_cast<size_t>(b) * a.max_pages + L / kPage];
+  T* pages = static_cast<T*>(a.pages);
+  for (int i = tid; i < 2 * H * kChunks; i += nthr) {
+    const int kv = i / (H * kChunks), hh = (i / kChunks) % H, cc = i % kChunks;
+    T* dst = pages + ((static_cast<size_t>(pg) * 2 + kv) * H + hh) * tile + static_cast<size_t>(L % kPage) * DH;
+    const T* src = static_cast<const T*>(kv ? a.v_new : a.k_new) + (static_cast<size_t>(b) * H + hh) * DH;
+    reinterpret_cast<uint4*>(dst)[cc] = reinterpret_cast<const uint4*>(src)[cc];
+  }
+  __syncthreads();  // every thread has read L before it moves
+  if (tid == 0) a.cache_len[b] = L + 1;
+}
+
+// The work of block (s, h, b).
 template <typename T, int DH, int NW>
-__global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
+__device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, int b) {
   using C = AttendCfg<T, DH>;
-  const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
   const int S = a.n_split, H = a.H;
   const int cap = a.max_pages * kPage;
@@ -184,7 +209,7 @@ __global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
   const T* qrow = static_cast<const T*>(a.q) + bh * DH;
   const T* knew = static_cast<const T*>(a.k_new) + bh * DH;
   const T* vnew = static_cast<const T*>(a.v_new) + bh * DH;
-  T* pages = static_cast<T*>(a.pages);
+  const T* pages = static_cast<const T*>(a.pages);
   const int32_t* bt = a.block_table + static_cast<size_t>(b) * a.max_pages;
   const size_t tile = static_cast<size_t>(kPage) * DH;  // elements of one (page, K|V, head) tile
   const size_t vofs = static_cast<size_t>(H) * tile;    // from a K tile to the V tile of the same page/head
@@ -206,7 +231,7 @@ __global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
   // Thread 0 announces that this block has read cache_len[b].  The increment depends on the loaded value, so
   // it cannot be issued before the load has returned; its own latency hides behind the page stream.
   int ticket = 0;
-  if (tid == 0) ticket = add_agent(S == 1 ? &a.cnt_b[b * kCnt] : &a.cnt_bh[(static_cast<size_t>(b) * H + h) * kCnt], 1 + (L == INT32_MIN));
+  if (tid == 0) ticket = add_agent(S == 1 ? &a.cnt_b[b * kCnt] : &a.cnt_bh[bh * kCnt], 1 + (L == INT32_MIN));
   L = L < 0 ? 0 : (L > cap ? cap : L);
   const int P = (L + kPage - 1) / kPage;
   if (!spec && p < P) {
@@ -249,7 +274,7 @@ __global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
 
   __shared__ float sm_acc[NW][DH];
   __shared__ float sm_m[NW], sm_l[NW];
-  __shared__ int sm_flag;
+  __shared__ int sm_flag, sm_commit;
   if (lane < C::G) {
 #pragma unroll
     for (int e = 0; e < C::E; ++e) sm_acc[w][lane * C::E + e] = st.acc[e];
@@ -258,17 +283,19 @@ __global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
       sm_l[w] = st.l;
     }
   }
-
-  // conditional append: position L is read by nobody in this launch
-  if (s == 0 && L < cap && decode_keep(a.logits, a.keep_override, a.threshold, b)) {
-    constexpr int kChunks = DH * sizeof(T) / 16;
-    if (tid < 2 * kChunks) {
-      const int kv = tid / kChunks, cc = tid % kChunks;
-      const int pga = bt[L / kPage];
-      T* dst = pages + ((static_cast<size_t>(pga) * 2 + kv) * H + h) * tile + static_cast<size_t>(L % kPage) * DH;
-      const T* src = kv ? vnew : knew;
-      reinterpret_cast<uint4*>(dst)[cc] = reinterpret_cast<const uint4*>(src)[cc];
+  const int target = H;  // tickets on cnt_b[b] before the sequence may be committed
+  if (tid == 0) {
+    int commit = 0;
+    if (S == 1) {
+      commit = (ticket == target - 1);
+    } else if (ticket == S - 1) {
+      // every block of (b, h) has read the length once the last reader's ticket is out; that block reports
+      // the head to the sequence counter
+      zero_agent(&a.cnt_bh[bh * kCnt]);
+      commit = (add_agent(&a.cnt_b[b * kCnt], 1) == target - 1);
     }
+    if (commit) zero_agent(&a.cnt_b[b * kCnt]);
+    sm_commit = commit;
   }
   __syncthreads();
 
@@ -284,17 +311,8 @@ __global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
       acc += wgt * sm_acc[i][tid];
     }
   }
-  bool committer = (S == 1) && (ticket == H - 1);
   bool finalize = true;  // this block writes o[b, h]
   if (S > 1) {
-    // every block of (b, h) has read the length once the last reader's ticket is out; that block tells the
-    // sequence counter (second level), again long before the results are due
-    if (tid == 0 && ticket == S - 1) {
-      zero_agent(&a.cnt_bh[bh * kCnt]);
-      sm_flag = (add_agent(&a.cnt_b[b * kCnt], 1) == H - 1);
-    } else if (tid == 0) {
-      sm_flag = 0;
-    }
     if (tid < DH) {
       const size_t ps = bh * S + s;
       st_agent(a.part_acc + ps * DH + tid, acc);
@@ -304,8 +322,6 @@ __global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
       }
     }
     block_publish();  // partials have reached the memory side before the counter moves
-    committer = (tid == 0) && sm_flag;
-    __syncthreads();
     if (tid == 0) sm_flag = (add_agent(&a.cnt_done[bh * kCnt], 1) == S - 1);
     __syncthreads();
     finalize = sm_flag != 0;
@@ -340,19 +356,14 @@ __global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
   // split 0 always holds the current token, so l > 0
   if (finalize && tid < DH) Elem<T>::store(static_cast<T*>(a.o) + bh * DH + tid, acc / l);
 
-  // The block that drew the last ticket of sequence b knows every block of b has read cache_len[b]:
-  // it alone advances it, so the update cannot race with a read.
-  if (tid == 0 && committer) {
-    zero_agent(&a.cnt_b[b * kCnt]);
-    const bool keep = decode_keep(a.logits, a.keep_override, a.threshold, b);
-    if (a.keep_out) a.keep_out[b] = keep ? 1 : 0;
-    if (keep) {
-      if (L < cap)
-        a.cache_len[b] = L + 1;
-      else if (a.err_flag)
-        *a.err_flag = 1;
-    }
-  }
+  // The block that drew the last ticket of sequence b knows every block of b has read cache_len[b]: it alone
+  // appends and advances the length.
+  if (sm_commit) commit_sequence<T, DH>(a, b);
+}
+
+template <typename T, int DH, int NW>
+__global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
+  attn_block<T, DH, NW>(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 struct DecodeShape {
@@ -399,45 +410,31 @@ int launch(const DecodeArgs& a, const DecodeShape& sh, hipStream_t st) {
 
 size_t counter_bytes(int64_t B, int64_t H) { return static_cast<size_t>(2 * B * H + B) * kCnt * sizeof(int32_t); }
 
-}  // namespace
-}  // namespace dllava
-
-using namespace dllava;
-
-extern "C" size_t dllava_decode_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pages_per_seq) {
-  if (B <= 0 || H <= 0 || Dh <= 0) return 256;
-  (void)max_pages_per_seq;
+size_t partial_bytes(int64_t B, int64_t H, int64_t Dh) {
   const size_t n = static_cast<size_t>(B) * H * kMaxSplit;
-  return counter_bytes(B, H) + round_up(n * Dh * sizeof(float), 256) + round_up(n * 2 * sizeof(float), 256);
+  return round_up(n * Dh * sizeof(float), 256) + round_up(n * 2 * sizeof(float), 256);
 }
 
-extern "C" int dllava_decode_attn_append(const void* q, const void* k_new, const void* v_new, int32_t B,
-                                         const float* logits, float threshold, const uint8_t* keep_override,
-                                         const dllava_kv_cache* cache, float scale, void* o, uint8_t* keep_out,
-                                         int32_t* err_flag, void* workspace, size_t workspace_bytes,
-                                         void* stream) {
-  DLLAVA_REQUIRE(B >= 0, DLLAVA_EINVAL, "decode: B = %d < 0", B);
-  if (int rc = check_cache(cache, "decode")) return rc;
-  if (B == 0) return DLLAVA_OK;
-  DLLAVA_REQUIRE(q && k_new && v_new && o, DLLAVA_ENULL, "decode: q, k_new, v_new and o are required");
-  DLLAVA_REQUIRE(logits || keep_override, DLLAVA_ENULL, "decode: need logits or keep_override");
-  DLLAVA_REQUIRE(threshold == threshold, DLLAVA_EINVAL, "decode: threshold is NaN");
-  DLLAVA_REQUIRE(scale == scale && scale > 0.f && scale < INFINITY, DLLAVA_EINVAL, "decode: bad scale");
+// host validation shared by the two entry points; fills `a` and the launch shape
+int prepare(const char* who, const void* q, const void* k_new, const void* v_new, int32_t B, const float* logits,
+            float threshold, const uint8_t* keep_override, const dllava_kv_cache* cache, float scale, void* o,
+            uint8_t* keep_out, int32_t* err_flag, void* workspace, size_t workspace_bytes, size_t need,
+            DecodeArgs& a, DecodeShape& sh) {
+  DLLAVA_REQUIRE(q && k_new && v_new && o, DLLAVA_ENULL, "%s: q, k_new, v_new and o are required", who);
+  DLLAVA_REQUIRE(threshold == threshold, DLLAVA_EINVAL, "%s: threshold is NaN", who);
+  DLLAVA_REQUIRE(scale == scale && scale > 0.f && scale < INFINITY, DLLAVA_EINVAL, "%s: bad scale", who);
   DLLAVA_REQUIRE(aligned(q, 16) && aligned(k_new, 16) && aligned(v_new, 16) && aligned(o, 16), DLLAVA_EINVAL,
-                 "decode: q, k_new, v_new, o must be 16-byte aligned");
-  DLLAVA_REQUIRE(B <= 65535 && cache->H <= 65535, DLLAVA_ESHAPE, "decode: B and H must be <= 65535");
-  const size_t need = dllava_decode_workspace(B, cache->H, cache->Dh, cache->max_pages_per_seq);
+                 "%s: q, k_new, v_new, o must be 16-byte aligned", who);
+  DLLAVA_REQUIRE(B <= 65535 && cache->H <= 65535, DLLAVA_ESHAPE, "%s: B and H must be <= 65535", who);
   DLLAVA_REQUIRE(workspace && aligned(workspace, 256) && workspace_bytes >= need, DLLAVA_EWORKSPACE,
-                 "decode: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
-
-  DecodeArgs a;
+                 "%s: workspace needs %zu bytes, 256-byte aligned (got %zu)", who, need, workspace_bytes);
   a.q = q; a.k_new = k_new; a.v_new = v_new;
   a.logits = logits; a.keep_override = keep_override;
   a.threshold = threshold;
   a.scale_log2 = scale * 1.44269504088896340736f;
   a.pages = cache->pages; a.block_table = cache->block_table; a.cache_len = cache->cache_len;
   a.max_pages = cache->max_pages_per_seq; a.H = cache->H; a.B = B;
-  const DecodeShape sh = pick_shape(static_cast<int64_t>(B) * cache->H, cache->max_pages_per_seq);
+  sh = pick_shape(static_cast<int64_t>(B) * cache->H, cache->max_pages_per_seq);
   a.n_split = sh.n_split;
   const size_t n = static_cast<size_t>(B) * cache->H * kMaxSplit;
   char* ws = static_cast<char*>(workspace);
@@ -448,7 +445,35 @@ extern "C" int dllava_decode_attn_append(const void* q, const void* k_new, const
   a.part_acc = reinterpret_cast<float*>(ws);
   a.part_ml = reinterpret_cast<float*>(ws + round_up(n * cache->Dh * sizeof(float), 256));
   a.o = o; a.keep_out = keep_out; a.err_flag = err_flag;
+  return DLLAVA_OK;
+}
 
+}  // namespace
+}  // namespace dllava
+
+using namespace dllava;
+
+extern "C" size_t dllava_decode_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pages_per_seq) {
+  if (B <= 0 || H <= 0 || Dh <= 0) return 256;
+  (void)max_pages_per_seq;
+  return counter_bytes(B, H) + partial_bytes(B, H, Dh);
+}
+
+extern "C" int dllava_decode_attn_append(const void* q, const void* k_new, const void* v_new, int32_t B,
+                                         const float* logits, float threshold, const uint8_t* keep_override,
+                                         const dllava_kv_cache* cache, float scale, void* o, uint8_t* keep_out,
+                                         int32_t* err_flag, void* workspace, size_t workspace_bytes,
+                                         void* stream) {
+  DLLAVA_REQUIRE(B >= 0, DLLAVA_EINVAL, "decode: B = %d < 0", B);
+  if (int rc = check_cache(cache, "decode")) return rc;
+  if (B == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(logits || keep_override, DLLAVA_ENULL, "decode: need logits or keep_override");
+  DecodeArgs a;
+  DecodeShape sh;
+  const size_t need = dllava_decode_workspace(B, cache->H, cache->Dh, cache->max_pages_per_seq);
+  if (int rc = prepare("decode", q, k_new, v_new, B, logits, threshold, keep_override, cache, scale, o, keep_out,
+                       err_flag, workspace, workspace_bytes, need, a, sh))
+    return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bool bf = cache->dtype == DLLAVA_BF16;
   if (cache->Dh == 128) return bf ? launch<bf16_t, 128>(a, sh, st) : launch<float, 128>(a, sh, st);

@@ -11,13 +11,10 @@
 //    v_mfma_f32_32x32x16_bf16, K staged through double-buffered padded LDS tiles.  Each block leaves a
 //    partial logit pair per token; the last block of a token tile (device-scope counter) adds the dh/128
 //    partials in tile order and the bias.
-//  * score_skinny_kernel (M <= 64, decode: one row per sequence): bandwidth-bound on W1.  One block per
-//    16 hidden units, 8 waves each taking an eighth of d with v_mfma_f32_16x16x32_bf16 on fragments loaded
-//    straight from global memory (W1 is read exactly once per call); LDS reduction over the waves, GELU,
-//    then the same last-block reduction over all blocks.
+//  * score_skinny_kernel (M <= 64, decode: one row per sequence): bandwidth-bound on W1; see score_skinny.h.
 // All reductions run in a fixed order: results are bit-reproducible.  Counters live at the start of the
 // workspace, start at zero and are returned to zero by the block that consumes them.
-#include "score_args.h"
+#include "score_skinny.h"
 
 namespace dllava {
 
@@ -37,123 +34,14 @@ constexpr size_t kCounterBytes = 4096;  // up to 1024 int32 counters at the star
 constexpr int kMaxCounters = 1024;
 
 // ------------------------------------------------------------------------------------------------
-// skinny: M <= 16*NT tokens
+// skinny: M <= 16*NT tokens (score_skinny.h)
 // ------------------------------------------------------------------------------------------------
 constexpr int kSkWaves = 8;
 constexpr int kSkThreads = kSkWaves * kWave;
-constexpr int kSkUnits = 16;
-constexpr int kSkBatch = 16;  // k-steps whose loads are issued together
 
 template <int NT>
 __global__ __launch_bounds__(kSkThreads) void score_skinny_kernel(ScoreArgs a, int32_t* counter, float* partial) {
-  __shared__ float red[kSkWaves][NT][kWave][4];
-  __shared__ int sm_last;
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-  const int blk = blockIdx.x, nblk = gridDim.x;
-  const int M = static_cast<int>(a.M);
-  const int64_t d = a.d;
-  const bf16_t* W1 = static_cast<const bf16_t*>(a.W1);
-  const bf16_t* X = static_cast<const bf16_t*>(a.x);
-
-  // fragment addressing: lane -> (row = lane%16, 8 consecutive k at 8*(lane/16))
-  int64_t unit = static_cast<int64_t>(blk) * kSkUnits + (lane & 15);
-  if (unit >= a.dh) unit = a.dh - 1;  // clamped rows are masked out below
-  const bf16_t* wrow = W1 + unit * d + 8 * (lane >> 4);
-  const bf16_t* xrow[NT];
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    int tok = t * 16 + (lane & 15);
-    if (tok >= M) tok = M - 1;
-    xrow[t] = X + static_cast<int64_t>(tok) * a.ldx + 8 * (lane >> 4);
-  }
-  f32x4 acc[NT];
-#pragma unroll
-  for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  // wave w takes k-steps w, w+8, ... (32 elements each), kSkBatch of them in flight at a time: the kernel
-  // is a stream over W1, so what matters is the number of outstanding 16-byte loads, not the MFMA rate
-  const int ksteps = static_cast<int>(d / 32);
-  const int n_it = (ksteps - w + kSkWaves - 1) / kSkWaves;
-  const int rot = ksteps / nblk > 0 ? ksteps / nblk : 1;
-  for (int it0 = 0; it0 < n_it; it0 += kSkBatch) {
-    uint4 ra[kSkBatch], rb[NT][kSkBatch];
-#pragma unroll
-    for (int u = 0; u < kSkBatch; ++u) {
-      const bool ok = it0 + u < n_it;
-      // blocks start at different columns, or all of them would sweep W1 in lockstep through the same few
-      // memory channels (rows are 2*d bytes apart); the order of a block's sum is fixed by its index
-      const int ks = (w + (ok ? it0 + u : 0) * kSkWaves + blk * rot) % ksteps;
-      const int64_t ko = static_cast<int64_t>(ks) * 32;
-      ra[u] = *reinterpret_cast<const uint4*>(wrow + ko);
-      if (!ok) ra[u] = make_uint4(0, 0, 0, 0);  // a zero W1 fragment contributes nothing
-#pragma unroll
-      for (int t = 0; t < NT; ++t) rb[t][u] = *reinterpret_cast<const uint4*>(xrow[t] + ko);
-    }
-#pragma unroll
-    for (int u = 0; u < kSkBatch; ++u)
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_frag(ra[u]), as_frag(rb[t][u]), acc[t], 0, 0, 0);
-  }
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) red[w][t][lane][r] = acc[t][r];
-  __syncthreads();
-
-  // wave 0 finishes: sum over waves (fixed order), bias, GELU, contraction with W2 over this block's units
-  if (w == 0) {
-    const bf16_t* W2 = static_cast<const bf16_t*>(a.W2);
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      float p0 = 0.f, p1 = 0.f;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        float s = 0.f;
-#pragma unroll
-        for (int i = 0; i < kSkWaves; ++i) s += red[i][t][lane][r];
-        const int64_t u = static_cast<int64_t>(blk) * kSkUnits + 4 * (lane >> 4) + r;
-        if (u < a.dh) {
-          const float g = gelu_erf_fast(s + (a.b1 ? a.b1[u] : 0.f));
-          p0 = fmaf(g, bf16_to_f32(W2[u]), p0);
-          p1 = fmaf(g, bf16_to_f32(W2[a.dh + u]), p1);
-        }
-      }
-      p0 += __shfl_xor(p0, 16, kWave);
-      p1 += __shfl_xor(p1, 16, kWave);
-      p0 += __shfl_xor(p0, 32, kWave);
-      p1 += __shfl_xor(p1, 32, kWave);
-      const int tok = t * 16 + lane;
-      if (lane < 16 && tok < M) {
-        st_agent(partial + static_cast<size_t>(2 * tok) * nblk + blk, p0);      // [token][logit][block]
-        st_agent(partial + static_cast<size_t>(2 * tok + 1) * nblk + blk, p1);
-      }
-    }
-  }
-  block_publish();
-  if (tid == 0) sm_last = (add_agent(counter, 1) == nblk - 1);
-  __syncthreads();
-  if (!sm_last) return;
-  // Last block: logit (tok, c) = b2[c] + sum over blocks.  A dependent chain of device-scope loads costs a
-  // memory round trip per term, so each (tok, c) pair is summed by a whole wave: lanes load the block
-  // partials side by side (all pairs of the wave in flight together) and a butterfly adds them.
-  constexpr int kPairsPerWave = NT * 16 * 2 / kSkWaves;
-  float v[kPairsPerWave];
-#pragma unroll
-  for (int j = 0; j < kPairsPerWave; ++j) {
-    const int pair = w + j * kSkWaves;  // = 2*tok + c
-    float t = 0.f;
-    if (pair < 2 * M)
-      for (int b = lane; b < nblk; b += kWave) t += ld_agent(partial + static_cast<size_t>(pair) * nblk + b);
-    v[j] = t;
-  }
-#pragma unroll
-  for (int j = 0; j < kPairsPerWave; ++j) {
-    const int pair = w + j * kSkWaves;
-    const float t = wave_sum(v[j]);
-    if (lane == 0 && pair < 2 * M) a.logits[pair] = t + (a.b2 ? a.b2[pair & 1] : 0.f);
-  }
-  if (tid == 0) zero_agent(counter);
+  score_skinny_block<NT, kSkWaves, 16>(a, blockIdx.x, gridDim.x, counter, partial);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -1,0 +1,175 @@
+// Predictor scoring for a handful of rows (decode: one row per sequence), bfloat16, as block-level routines.
+//
+// Bandwidth-bound on W1 (it is read exactly once per call).  Block `blk` of `nblk` owns 16 hidden units; its
+// WAVES waves each take a slice of d with v_mfma_f32_16x16x32_bf16 in the transposed orientation (hidden units
+// down the rows, tokens across the columns) on fragments loaded straight from global memory, many loads in
+// flight together; LDS reduction over the slices in slice order, bias + GELU + contraction with W2 in
+// registers, one partial logit pair per token and block.  The block that finds itself last (device-scope
+// counter) adds the partials: lanes load them side by side and a butterfly sums them, so the order is fixed and
+// the result bit-reproducible.
+#pragma once
+
+#include "score_args.h"
+
+namespace dllava {
+
+typedef __bf16 sk_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float sk_f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kSkUnits = 16;
+constexpr int kSkSlices = 8;  // independent slices of d, summed in slice order
+
+__device__ __forceinline__ sk_bf16x8 sk_frag(const uint4& v) {
+  union { uint4 u; sk_bf16x8 f; } c;
+  c.u = v;
+  return c.f;
+}
+
+// Logit `pair` (= 2*token + column) without its bias: the sum of the nblk block partials.  A dependent chain of
+// device-scope loads would cost a memory round trip per term, so a whole wave sums one pair: lanes load the
+// partials side by side and a butterfly adds them.  Called by all 64 lanes; every lane gets the sum.
+__device__ __forceinline__ float score_pair_load(const float* partial, int pair, int nblk) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const float* row = partial + static_cast<size_t>(pair) * nblk;
+  float t = 0.f;
+  for (int b0 = 0; b0 < nblk; b0 += 8 * kWave) {  // eight loads per lane in flight, then added in index order
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int b = b0 + j * kWave + lane;
+      v[j] = b < nblk ? ld_agent(row + b) : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t += v[j];
+  }
+  return t;
+}
+
+// Part 1: this block's partial logits, written through to memory and complete when the routine returns.
+// BATCH = k-steps whose loads are issued together (more in flight = shorter, but more registers).
+template <int NT, int WAVES, int BATCH>
+__device__ __forceinline__ void score_skinny_partials(const ScoreArgs& a, int blk, int nblk, float* partial) {
+  static_assert(kSkSlices % WAVES == 0, "waves must divide the slices");
+  __shared__ float red[kSkSlices][NT][kWave][4];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+  const int M = static_cast<int>(a.M);
+  const int64_t d = a.d;
+  const bf16_t* W1 = static_cast<const bf16_t*>(a.W1);
+  const bf16_t* W2 = static_cast<const bf16_t*>(a.W2);
+  const bf16_t* X = static_cast<const bf16_t*>(a.x);
+
+  // fragment addressing: lane -> (row = lane%16, 8 consecutive k at 8*(lane/16))
+  int64_t unit = static_cast<int64_t>(blk) * kSkUnits + (lane & 15);
+  if (unit >= a.dh) unit = a.dh - 1;  // clamped rows are masked out below
+  const bf16_t* wrow = W1 + unit * d + 8 * (lane >> 4);
+  const bf16_t* xrow[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    int tok = t * 16 + (lane & 15);
+    if (tok >= M) tok = M - 1;
+    xrow[t] = X + static_cast<int64_t>(tok) * a.ldx + 8 * (lane >> 4);
+  }
+  // epilogue operands of wave 0, requested now so that they are there when the products are
+  float eb[4], ew0[4], ew1[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int64_t u = static_cast<int64_t>(blk) * kSkUnits + 4 * (lane >> 4) + r;
+    const bool ok = (w == 0) && u < a.dh;
+    eb[r] = (ok && a.b1) ? a.b1[u] : 0.f;
+    ew0[r] = ok ? bf16_to_f32(W2[u]) : 0.f;
+    ew1[r] = ok ? bf16_to_f32(W2[a.dh + u]) : 0.f;
+  }
+  // d is split among kSkSlices slices: slice v takes k-steps v, v+8, ... (32 elements each) and is accumulated on
+  // its own, so the arithmetic does not depend on how many waves the block has (wave w takes slices w, w+WAVES, ..).
+  // BATCH k-steps are in flight at a time: the routine is a stream over W1, so what matters is the number of
+  // outstanding 16-byte loads, not the MFMA rate.
+  const int ksteps = static_cast<int>(d / 32);
+  const int rot = ksteps / nblk > 0 ? ksteps / nblk : 1;
+  for (int v = w; v < kSkSlices; v += WAVES) {
+    sk_f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = sk_f32x4{0.f, 0.f, 0.f, 0.f};
+    const int n_it = (ksteps - v + kSkSlices - 1) / kSkSlices;
+    for (int it0 = 0; it0 < n_it; it0 += BATCH) {
+      uint4 ra[BATCH], rb[NT][BATCH];
+#pragma unroll
+      for (int u = 0; u < BATCH; ++u) {
+        const bool ok = it0 + u < n_it;
+        // blocks start at different columns, so that they do not sweep W1 in lockstep through the same few
+        // memory channels (rows are 2*d bytes apart); the order of a block's sum is fixed by its index
+        const int ks = (v + (ok ? it0 + u : 0) * kSkSlices + blk * rot) % ksteps;
+        const int64_t ko = static_cast<int64_t>(ks) * 32;
+        ra[u] = *reinterpret_cast<const uint4*>(wrow + ko);
+        if (!ok) ra[u] = make_uint4(0, 0, 0, 0);  // a zero W1 fragment contributes nothing
+#pragma unroll
+        for (int t = 0; t < NT; ++t) rb[t][u] = *reinterpret_cast<const uint4*>(xrow[t] + ko);
+      }
+#pragma unroll
+      for (int u = 0; u < BATCH; ++u)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sk_frag(ra[u]), sk_frag(rb[t][u]), acc[t], 0, 0, 0);
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) red[v][t][lane][r] = acc[t][r];
+  }
+  __syncthreads();
+
+  // wave 0 finishes: sum over waves (fixed order), bias, GELU, contraction with W2 over this block's units
+  if (w == 0) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      float p0 = 0.f, p1 = 0.f;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < kSkSlices; ++i) s += red[i][t][lane][r];
+        const float g = gelu_erf_fast(s + eb[r]);  // units past dh carry zero weights
+        p0 = fmaf(g, ew0[r], p0);
+        p1 = fmaf(g, ew1[r], p1);
+      }
+      p0 += __shfl_xor(p0, 16, kWave);
+      p1 += __shfl_xor(p1, 16, kWave);
+      p0 += __shfl_xor(p0, 32, kWave);
+      p1 += __shfl_xor(p1, 32, kWave);
+      const int tok = t * 16 + lane;
+      if (lane < 16 && tok < M) {
+        st_agent(partial + static_cast<size_t>(2 * tok) * nblk + blk, p0);  // [token][logit][block]
+        st_agent(partial + static_cast<size_t>(2 * tok + 1) * nblk + blk, p1);
+      }
+    }
+  }
+  block_publish();
+}
+
+// Parts 1 + 2: the block that finds itself last adds the partials and writes a.logits.
+template <int NT, int WAVES, int BATCH>
+__device__ __forceinline__ void score_skinny_block(const ScoreArgs& a, int blk, int nblk, int32_t* counter,
+                                                   float* partial) {
+  __shared__ int sm_last;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+  const int M = static_cast<int>(a.M);
+  score_skinny_partials<NT, WAVES, BATCH>(a, blk, nblk, partial);
+  if (tid == 0) sm_last = (add_agent(counter, 1) == nblk - 1);
+  __syncthreads();
+  if (!sm_last) return;
+  constexpr int kPairsPerWave = NT * 16 * 2 / WAVES;
+  float v[kPairsPerWave];
+#pragma unroll
+  for (int j = 0; j < kPairsPerWave; ++j) {  // all pairs of the wave in flight together
+    const int pair = w + j * WAVES;
+    v[j] = pair < 2 * M ? score_pair_load(partial, pair, nblk) : 0.f;
+  }
+#pragma unroll
+  for (int j = 0; j < kPairsPerWave; ++j) {
+    const int pair = w + j * WAVES;
+    const float t = wave_sum(v[j]);
+    if (lane == 0 && pair < 2 * M) a.logits[pair] = t + (a.b2 ? a.b2[pair & 1] : 0.f);
+  }
+  if (tid == 0) zero_agent(counter);
+}
+
+}  // namespace dllava

@@ -313,3 +313,4 @@ def test_whole_path_with_gpu_scores(name):
         _assert_out_close(h.as_f64(o), o_ref, w.dtype, f"decode step {t}")
     assert forced <= max(1, w.T // 50)
     assert np.array_equal(h.bits(g.pages), cache.pages)
+
