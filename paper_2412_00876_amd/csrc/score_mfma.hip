@@ -8,7 +8,8 @@
 // leave the chip, and only one cross-lane step (lanes l and l+32, or l+16/l+32/l+48) is left.
 //
 //  * score_gemm_kernel   (M > 64, prefill): 128 units x 128 tokens per block, 4 waves of 64x64 built from
-//    v_mfma_f32_32x32x16_bf16, K staged through double-buffered padded LDS tiles.  Each block leaves a
+//    v_mfma_f32_32x32x16_bf16, the hidden dimension streamed through double-buffered padded LDS tiles with the
+//    global loads two stages ahead in registers, LDS-only barriers, XCD-aware tile order.  Each block leaves a
 //    partial logit pair per token; the last block of a token tile (device-scope counter) adds the dh/128
 //    partials in tile order and the bias.
 //  * score_skinny_kernel (M <= 64, decode: one row per sequence): bandwidth-bound on W1; see score_skinny.h.
@@ -23,6 +24,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8 as_frag(const uint4& v) {
   union { uint4 u; bf16x8 f; } c;
@@ -48,62 +50,77 @@ __global__ __launch_bounds__(kSkThreads) void score_skinny_kernel(ScoreArgs a, i
 // GEMM: 128 units x 128 tokens per block
 // ------------------------------------------------------------------------------------------------
 constexpr int kGThreads = 256;
-constexpr int kTU = 128, kTM = 128, kBK = 64;
-constexpr int kLd = kBK + 8;  // padded LDS row (elements): 144 bytes, conflict-free 16-byte fragment reads
+constexpr int kTU = 128, kTM = 128;
+constexpr int kBK = 32;             // hidden-dimension elements per pipeline stage (64 bytes per row)
+constexpr int kLd = kBK + 8;        // padded LDS row (elements): 80 bytes, conflict-free 16-byte fragment reads
 constexpr int kTileElems = 128 * kLd;
+constexpr int kXcds = 8;            // accelerator complex dies of the chip
 
-__global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_gemm_kernel(ScoreArgs a, int32_t* counters, float* partial) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);  // [2][128][kLd]  W1 tile (units)
-  bf16_t* sB = sA + 2 * kTileElems;                  // [2][128][kLd]  x tile (tokens)
+// LDS-only block barrier: waits for this wave's LDS traffic, not for its outstanding global loads.  The generic
+// __syncthreads() drains the vector-memory counter as well, which would stall every stage of the pipeline on
+// the prefetches that were just issued.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+__global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4))) void score_gemm_kernel(
+    ScoreArgs a, int32_t* counters, float* partial, int n_unit_tiles) {
+  __shared__ __align__(16) bf16_t sA[2 * kTileElems];  // [2][128][kLd]  W1 tile (units)
+  __shared__ __align__(16) bf16_t sB[2 * kTileElems];  // [2][128][kLd]  x tile (tokens)
   __shared__ float sm_p[2][kTM][2];
   __shared__ int sm_last;
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-  const int ut = blockIdx.x, mt = blockIdx.y, n_ut = gridDim.x;
+  // XCD-aware tile order.  Consecutive block ids go round-robin to the 8 XCDs, each with its own 4 MiB L2.
+  // XCD x takes the token tiles x, x+8, ... and, for each, all unit tiles: its blocks are resident together and
+  // walk the hidden dimension roughly in step, so each XCD pulls W1 and its share of x through its L2 about once
+  // (the plain (unit tile, token tile) order made every XCD stream all of x: 4x the traffic beyond L2).
+  const int n_ut = n_unit_tiles;
+  const int xcd = blockIdx.x % kXcds, jb = blockIdx.x / kXcds;
+  const int ut = jb % n_ut, mt = (jb / n_ut) * kXcds + xcd;
   const int64_t M = a.M, d = a.d, dh = a.dh;
+  if (static_cast<int64_t>(mt) * kTM >= M) return;  // padding of the last round of token tiles
   const bf16_t* W1 = static_cast<const bf16_t*>(a.W1);
   const bf16_t* X = static_cast<const bf16_t*>(a.x);
 
-  // global -> LDS staging: thread handles chunk c = tid%8 (16 bytes) of rows tid/8 + 32*i, i < 4
-  const int lc = tid & 7, lr = tid >> 3;
-  const bf16_t* gA[4];
-  const bf16_t* gB[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int64_t u = static_cast<int64_t>(ut) * kTU + lr + 32 * i;
-    if (u >= dh) u = dh - 1;
-    gA[i] = W1 + u * d + lc * 8;
-    int64_t m = static_cast<int64_t>(mt) * kTM + lr + 32 * i;
-    if (m >= M) m = M - 1;
-    int64_t src = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m);
-    if (src < 0) src = 0;
-    gB[i] = X + src * a.ldx + lc * 8;
+  // global -> registers -> LDS staging: thread handles the 16-byte chunk lc of rows lr and lr + 64 of each tile
+  const int lc = tid & 3, lr = tid >> 2;
+  const bf16_t *gA0, *gA1, *gB0, *gB1;
+  {
+    int64_t u0 = static_cast<int64_t>(ut) * kTU + lr, u1 = u0 + 64;
+    if (u0 >= dh) u0 = dh - 1;  // clamped rows carry zero W2 weights in the epilogue
+    if (u1 >= dh) u1 = dh - 1;
+    gA0 = W1 + u0 * d + lc * 8;
+    gA1 = W1 + u1 * d + lc * 8;
+    int64_t m0 = static_cast<int64_t>(mt) * kTM + lr, m1 = m0 + 64;
+    if (m0 >= M) m0 = M - 1;
+    if (m1 >= M) m1 = M - 1;
+    int64_t s0 = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m0);
+    int64_t s1 = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m1);
+    if (s0 < 0) s0 = 0;
+    if (s1 < 0) s1 = 0;
+    gB0 = X + s0 * a.ldx + lc * 8;
+    gB1 = X + s1 * a.ldx + lc * 8;
   }
-  uint4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;  // staging registers (scalars, so they stay in VGPRs)
-#define DLLAVA_GLOAD(kt)                                                              \
-  {                                                                                    \
-    const int64_t ko = static_cast<int64_t>(kt) * kBK;                                 \
-    ra0 = *reinterpret_cast<const uint4*>(gA[0] + ko);                                 \
-    ra1 = *reinterpret_cast<const uint4*>(gA[1] + ko);                                 \
-    ra2 = *reinterpret_cast<const uint4*>(gA[2] + ko);                                 \
-    ra3 = *reinterpret_cast<const uint4*>(gA[3] + ko);                                 \
-    rb0 = *reinterpret_cast<const uint4*>(gB[0] + ko);                                 \
-    rb1 = *reinterpret_cast<const uint4*>(gB[1] + ko);                                 \
-    rb2 = *reinterpret_cast<const uint4*>(gB[2] + ko);                                 \
-    rb3 = *reinterpret_cast<const uint4*>(gB[3] + ko);                                 \
+  // two register sets: the loads of stage kt+2 are in flight while stage kt is multiplied
+  u32x4 pa0, pa1, pb0, pb1, qa0, qa1, qb0, qb1;
+#define DLLAVA_GLOAD(S, kt)                                          \
+  {                                                                  \
+    const int64_t ko = static_cast<int64_t>(kt) * kBK;               \
+    S##a0 = *reinterpret_cast<const u32x4*>(gA0 + ko);               \
+    S##a1 = *reinterpret_cast<const u32x4*>(gA1 + ko);               \
+    S##b0 = *reinterpret_cast<const u32x4*>(gB0 + ko);               \
+    S##b1 = *reinterpret_cast<const u32x4*>(gB1 + ko);               \
   }
-#define DLLAVA_SSTORE(buf)                                                            \
-  {                                                                                    \
-    const int o = (buf) * kTileElems + lr * kLd + lc * 8;                              \
-    *reinterpret_cast<uint4*>(sA + o) = ra0;                                           \
-    *reinterpret_cast<uint4*>(sA + o + 32 * kLd) = ra1;                                \
-    *reinterpret_cast<uint4*>(sA + o + 64 * kLd) = ra2;                                \
-    *reinterpret_cast<uint4*>(sA + o + 96 * kLd) = ra3;                                \
-    *reinterpret_cast<uint4*>(sB + o) = rb0;                                           \
-    *reinterpret_cast<uint4*>(sB + o + 32 * kLd) = rb1;                                \
-    *reinterpret_cast<uint4*>(sB + o + 64 * kLd) = rb2;                                \
-    *reinterpret_cast<uint4*>(sB + o + 96 * kLd) = rb3;                                \
+#define DLLAVA_SSTORE(S, buf)                                        \
+  {                                                                  \
+    const int o = (buf) * kTileElems + lr * kLd + lc * 8;            \
+    *reinterpret_cast<u32x4*>(sA + o) = S##a0;                       \
+    *reinterpret_cast<u32x4*>(sA + o + 64 * kLd) = S##a1;            \
+    *reinterpret_cast<u32x4*>(sB + o) = S##b0;                       \
+    *reinterpret_cast<u32x4*>(sB + o + 64 * kLd) = S##b1;            \
   }
 
   const int wu = (w >> 1) * 64, wm = (w & 1) * 64;  // this wave's 64 units x 64 tokens
@@ -115,35 +132,44 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(2, 2)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = static_cast<int>(d / kBK);
-  DLLAVA_GLOAD(0)
-  DLLAVA_SSTORE(0)
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) { DLLAVA_GLOAD(kt + 1) }
-    const bf16_t* tA = sA + buf * kTileElems + (wu + (lane & 31)) * kLd + 8 * (lane >> 5);
-    const bf16_t* tB = sB + buf * kTileElems + (wm + (lane & 31)) * kLd + 8 * (lane >> 5);
-#pragma unroll
-    for (int ks = 0; ks < kBK / 16; ++ks) {
-      bf16x8 fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fa[i] = as_frag(*reinterpret_cast<const uint4*>(tA + i * 32 * kLd + ks * 16));
-        fb[i] = as_frag(*reinterpret_cast<const uint4*>(tB + i * 32 * kLd + ks * 16));
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) { DLLAVA_SSTORE(buf ^ 1) }
-    __syncthreads();
+#define DLLAVA_COMPUTE(buf)                                                                              \
+  {                                                                                                      \
+    const bf16_t* tA = sA + (buf) * kTileElems + (wu + (lane & 31)) * kLd + 8 * (lane >> 5);             \
+    const bf16_t* tB = sB + (buf) * kTileElems + (wm + (lane & 31)) * kLd + 8 * (lane >> 5);             \
+    _Pragma("unroll") for (int ks = 0; ks < kBK / 16; ++ks) {                                            \
+      bf16x8 fa[2], fb[2];                                                                               \
+      _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                    \
+        fa[i] = as_frag(*reinterpret_cast<const uint4*>(tA + i * 32 * kLd + ks * 16));                   \
+        fb[i] = as_frag(*reinterpret_cast<const uint4*>(tB + i * 32 * kLd + ks * 16));                   \
+      }                                                                                                  \
+      _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                      \
+        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                    \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);         \
+    }                                                                                                    \
   }
 
+  // stage kt lives in LDS buffer kt % 2; its registers were loaded two iterations before it is multiplied
+  const int nk = static_cast<int>(d / kBK);  // even: d is a multiple of 64
+  DLLAVA_GLOAD(p, 0)
+  DLLAVA_GLOAD(q, 1)
+  DLLAVA_SSTORE(p, 0)
+  lds_barrier();
+  // Loads are issued unconditionally (past the end they re-read the last stage and are never used): a
+  // conditional load would make the number of outstanding loads path-dependent, and the compiler would then
+  // wait for all of them before every LDS store instead of only for the older register set.
+  for (int kt = 0; kt < nk; kt += 2) {
+    DLLAVA_GLOAD(p, (kt + 2 < nk ? kt + 2 : nk - 1))
+    DLLAVA_COMPUTE(0)
+    DLLAVA_SSTORE(q, 1)  // stage kt+1: waits only for the q loads, the p loads stay in flight
+    lds_barrier();
+    DLLAVA_GLOAD(q, (kt + 3 < nk ? kt + 3 : nk - 1))
+    DLLAVA_COMPUTE(1)
+    DLLAVA_SSTORE(p, 0)  // stage kt+2
+    lds_barrier();
+  }
 #undef DLLAVA_GLOAD
 #undef DLLAVA_SSTORE
+#undef DLLAVA_COMPUTE
 
   // epilogue: lane holds, for token column (lane%32) of token tile j, units 8*(r/4) + 4*(lane/32) + r%4 of unit tile i
   const bf16_t* W2 = static_cast<const bf16_t*>(a.W2);
@@ -217,7 +243,7 @@ size_t score_mfma_workspace(int64_t M, int64_t d, int64_t dh) {
 
 // returns 1 if the shape is not handled here
 int score_mfma_launch(const ScoreArgs& a, hipStream_t st) {
-  if (a.d % kBK != 0 || a.ldx % 8 != 0) return 1;
+  if (a.d % 64 != 0 || a.ldx % 8 != 0) return 1;
   int32_t* counters = static_cast<int32_t*>(a.workspace);
   float* partial = reinterpret_cast<float*>(static_cast<char*>(a.workspace) + kCounterBytes);
   if (a.M <= 64) {
@@ -237,15 +263,11 @@ int score_mfma_launch(const ScoreArgs& a, hipStream_t st) {
   // a token tile's counter may be shared with tile mt + 1024*k: those tiles are far apart in launch order,
   // but to stay exact we only take the path when every tile has its own counter
   if (n_mt > kMaxCounters) return 1;
-  static bool attr_set = false;
-  const size_t smem = static_cast<size_t>(4) * kTileElems * sizeof(bf16_t);
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                        static_cast<int>(smem));
-    attr_set = true;
-  }
-  dim3 grid(static_cast<unsigned>(ceil_div(a.dh, kTU)), static_cast<unsigned>(n_mt));
-  hipLaunchKernelGGL(score_gemm_kernel, grid, dim3(kGThreads), smem, st, a, counters, partial);
+  const int n_ut = static_cast<int>(ceil_div(a.dh, kTU));
+  const int64_t blocks = ceil_div(n_mt, kXcds) * kXcds * n_ut;
+  if (blocks > 0x7fffffffLL) return 1;
+  hipLaunchKernelGGL(score_gemm_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kGThreads), 0, st, a, counters,
+                     partial, n_ut);
   DLLAVA_CHECK_LAUNCH("score_gemm_kernel");
   return DLLAVA_OK;
 }
