@@ -42,8 +42,8 @@ constexpr int kSkWaves = 8;
 constexpr int kSkThreads = kSkWaves * kWave;
 
 template <int NT>
-__global__ __launch_bounds__(kSkThreads) void score_skinny_kernel(ScoreArgs a, int32_t* counter, float* partial) {
-  score_skinny_block<NT, kSkWaves, 16>(a, blockIdx.x, gridDim.x, counter, partial);
+__global__ __launch_bounds__(kSkThreads) void score_skinny_kernel(ScoreArgs a, unsigned long long* acc) {
+  score_skinny_block<NT, kSkWaves, 16>(a, blockIdx.x, gridDim.x, acc);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -235,7 +235,7 @@ size_t score_mfma_workspace(int64_t M, int64_t d, int64_t dh) {
   (void)d;
   size_t part;
   if (M <= 64)
-    part = static_cast<size_t>(ceil_div(dh, kSkUnits)) * 64 * 2 * sizeof(float);
+    part = static_cast<size_t>(2 * 64) * kSkAccStride * sizeof(unsigned long long);
   else
     part = static_cast<size_t>(ceil_div(dh, kTU)) * M * 2 * sizeof(float);
   return kCounterBytes + round_up(part, 256);
@@ -249,12 +249,14 @@ int score_mfma_launch(const ScoreArgs& a, hipStream_t st) {
   if (a.M <= 64) {
     if (a.seq_off) return 1;  // span gathering is only wired into the GEMM path
     const unsigned grid = static_cast<unsigned>(ceil_div(a.dh, kSkUnits));
+    if (grid > 255) return 1;  // the arrival count shares a word with the sum (8 bits)
+    unsigned long long* acc = static_cast<unsigned long long*>(a.workspace);
     if (a.M <= 16)
-      hipLaunchKernelGGL(score_skinny_kernel<1>, dim3(grid), dim3(kSkThreads), 0, st, a, counters, partial);
+      hipLaunchKernelGGL(score_skinny_kernel<1>, dim3(grid), dim3(kSkThreads), 0, st, a, acc);
     else if (a.M <= 32)
-      hipLaunchKernelGGL(score_skinny_kernel<2>, dim3(grid), dim3(kSkThreads), 0, st, a, counters, partial);
+      hipLaunchKernelGGL(score_skinny_kernel<2>, dim3(grid), dim3(kSkThreads), 0, st, a, acc);
     else
-      hipLaunchKernelGGL(score_skinny_kernel<4>, dim3(grid), dim3(kSkThreads), 0, st, a, counters, partial);
+      hipLaunchKernelGGL(score_skinny_kernel<4>, dim3(grid), dim3(kSkThreads), 0, st, a, acc);
     DLLAVA_CHECK_LAUNCH("score_skinny_kernel");
     return DLLAVA_OK;
   }

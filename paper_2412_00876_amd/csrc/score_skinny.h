@@ -4,9 +4,8 @@
 // WAVES waves each take a slice of d with v_mfma_f32_16x16x32_bf16 in the transposed orientation (hidden units
 // down the rows, tokens across the columns) on fragments loaded straight from global memory, many loads in
 // flight together; LDS reduction over the slices in slice order, bias + GELU + contraction with W2 in
-// registers, one partial logit pair per token and block.  The block that finds itself last (device-scope
-// counter) adds the partials: lanes load them side by side and a butterfly sums them, so the order is fixed and
-// the result bit-reproducible.
+// registers, one partial logit pair per token and block, summed across blocks in integer arithmetic by
+// device-scope atomics (order-independent, hence bit-reproducible; see the end of the routine).
 #pragma once
 
 #include "score_args.h"
@@ -25,30 +24,13 @@ __device__ __forceinline__ sk_bf16x8 sk_frag(const uint4& v) {
   return c.f;
 }
 
-// Logit `pair` (= 2*token + column) without its bias: the sum of the nblk block partials.  A dependent chain of
-// device-scope loads would cost a memory round trip per term, so a whole wave sums one pair: lanes load the
-// partials side by side and a butterfly adds them.  Called by all 64 lanes; every lane gets the sum.
-__device__ __forceinline__ float score_pair_load(const float* partial, int pair, int nblk) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const float* row = partial + static_cast<size_t>(pair) * nblk;
-  float t = 0.f;
-  for (int b0 = 0; b0 < nblk; b0 += 8 * kWave) {  // eight loads per lane in flight, then added in index order
-    float v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int b = b0 + j * kWave + lane;
-      v[j] = b < nblk ? ld_agent(row + b) : 0.f;
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) t += v[j];
-  }
-  return t;
-}
+// One accumulator per logit, 256 bytes apart (atomics that share a memory line serialise at the memory side).
+constexpr int kSkAccStride = 32;  // in 8-byte words
 
-// Part 1: this block's partial logits, written through to memory and complete when the routine returns.
 // BATCH = k-steps whose loads are issued together (more in flight = shorter, but more registers).
+// acc = zero-filled accumulators [2*M][kSkAccStride] (left zero-filled again); nblk <= 255.
 template <int NT, int WAVES, int BATCH>
-__device__ __forceinline__ void score_skinny_partials(const ScoreArgs& a, int blk, int nblk, float* partial) {
+__device__ __forceinline__ void score_skinny_block(const ScoreArgs& a, int blk, int nblk, unsigned long long* acc) {
   static_assert(kSkSlices % WAVES == 0, "waves must divide the slices");
   __shared__ float red[kSkSlices][NT][kWave][4];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
@@ -135,41 +117,32 @@ __device__ __forceinline__ void score_skinny_partials(const ScoreArgs& a, int bl
       p1 += __shfl_xor(p1, 16, kWave);
       p0 += __shfl_xor(p0, 32, kWave);
       p1 += __shfl_xor(p1, 32, kWave);
+      // Cross-block sum without a second pass.  Each partial is added, as a 64-bit fixed-point number (resolution
+      // 2^-32, magnitudes below 2^23), to the logit's accumulator with one
+      // returning device-scope atomic; the low 8 bits of the same word count the arrivals.  Integer addition is
+      // associative, so the sum does not depend on the order of arrival, and
+      // the block whose atomic returns the last count holds the total: it converts, adds the bias, writes the
+      // logit and clears the accumulator.  One memory round trip instead of store + counter + reload.
       const int tok = t * 16 + lane;
       if (lane < 16 && tok < M) {
-        st_agent(partial + static_cast<size_t>(2 * tok) * nblk + blk, p0);  // [token][logit][block]
-        st_agent(partial + static_cast<size_t>(2 * tok + 1) * nblk + blk, p1);
+        const float pc[2] = {p0, p1};
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          unsigned long long* slot = acc + static_cast<size_t>(2 * tok + c) * kSkAccStride;
+          const long long fx = __float2ll_rn(pc[c] * 4294967296.0f);
+          const unsigned long long mine = (static_cast<unsigned long long>(fx) << 8) + 1ull;
+          const unsigned long long old =
+              __hip_atomic_fetch_add(slot, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (static_cast<int>(old & 0xffull) == nblk - 1) {
+            const long long total = static_cast<long long>(old + mine) >> 8;  // arithmetic shift drops the count
+            a.logits[2 * tok + c] = static_cast<float>(static_cast<double>(total) * (1.0 / 4294967296.0)) +
+                                    (a.b2 ? a.b2[c] : 0.f);
+            __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
       }
     }
   }
-  block_publish();
-}
-
-// Parts 1 + 2: the block that finds itself last adds the partials and writes a.logits.
-template <int NT, int WAVES, int BATCH>
-__device__ __forceinline__ void score_skinny_block(const ScoreArgs& a, int blk, int nblk, int32_t* counter,
-                                                   float* partial) {
-  __shared__ int sm_last;
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-  const int M = static_cast<int>(a.M);
-  score_skinny_partials<NT, WAVES, BATCH>(a, blk, nblk, partial);
-  if (tid == 0) sm_last = (add_agent(counter, 1) == nblk - 1);
-  __syncthreads();
-  if (!sm_last) return;
-  constexpr int kPairsPerWave = NT * 16 * 2 / WAVES;
-  float v[kPairsPerWave];
-#pragma unroll
-  for (int j = 0; j < kPairsPerWave; ++j) {  // all pairs of the wave in flight together
-    const int pair = w + j * WAVES;
-    v[j] = pair < 2 * M ? score_pair_load(partial, pair, nblk) : 0.f;
-  }
-#pragma unroll
-  for (int j = 0; j < kPairsPerWave; ++j) {
-    const int pair = w + j * WAVES;
-    const float t = wave_sum(v[j]);
-    if (lane == 0 && pair < 2 * M) a.logits[pair] = t + (a.b2 ? a.b2[pair & 1] : 0.f);
-  }
-  if (tid == 0) zero_agent(counter);
 }
 
 }  // namespace dllava
