@@ -1,0 +1,215 @@
+"""GPU edge cases, determinism, buffer overruns and HIP-graph replay for the four entry points."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2412_00876_amd as P
+from oracle import dllava_ref as R
+from synth import rng
+from synth import workloads as W
+from tests.test_gpu_parity import TOL, _assert_out_close
+
+
+def _H():
+    from tests import harness
+    return harness
+
+
+def test_degenerate_sequences_in_a_batch():
+    """Empty sequence, sequence without vision tokens, vision-only sequence, single-token sequence, k = 0."""
+    h = _H()
+    w = W.make("degenerate", "bf16", 256, 2, 128, 6, [0, 5, 0, 1, 0, 3], [0, 0, 17, 0, 1, 2], [0, 4, 0, 0, 0, 6], 0.4, 5,
+               project_qkv=True)
+    pre, pred = W.prefill_inputs(w), W.predictor(w)
+    g = h.GpuPath(w, pre, pred, extra_tokens=8)
+    D = g.score_vision()
+    rows = np.concatenate([np.arange(w.seq_off[b] + w.n_sys[b], w.seq_off[b] + w.n_sys[b] + w.n_vis[b])
+                           for b in range(w.B)]).astype(np.int64)
+    D_ref = R.score(pre["hidden"][rows], pred["W1"], pred["b1"], pred["W2"], pred["b2"], w.dtype)
+    assert np.abs(D.cpu().numpy() - D_ref).max() <= TOL
+    out = g.select_compact(torch.from_numpy(D_ref).to(h.DEV))
+    mask, idx, off = R.select(D_ref, w.seq_off, w.vis_start, w.vis_len, R.TOPK, w.keep_ratio, 0.0)
+    total = int(off[-1])
+    assert list(np.diff(off)) == [0, 9, 6, 1, 0, 9]
+    assert np.array_equal(out["out_off"].cpu().numpy(), off)
+    assert np.array_equal(out["keep_mask"].cpu().numpy(), mask)
+    assert np.array_equal(out["kept_idx"].cpu().numpy()[:total], idx)
+    cache = R.PagedCache(g.pages.shape[0], g.bt_np, w.H, w.Dh, w.dtype)
+    _, Qc = R.compact(idx, off, w.seq_off, Q=pre["Q"], K=pre["K"], V=pre["V"], cache=cache)
+    assert np.array_equal(h.bits(g.pages), cache.pages)
+    src = np.concatenate([w.seq_off[b] + idx[off[b]:off[b + 1]] for b in range(w.B)]).astype(np.int64)
+    O = g.prefill(out["Q_out"][:total].contiguous(), out["out_off"])
+    O_ref = R.prefill_attn(Qc, pre["K"][src], pre["V"][src], off, g.scale, w.dtype)
+    _assert_out_close(h.as_f64(O), O_ref, w.dtype, "prefill")
+    # decode from ragged lengths that include two empty caches
+    dec = W.decode_inputs(w)
+    pattern = W.keep_pattern(w, w.T)
+    for t in range(w.T):
+        q, k, v = (h.to_dev(dec[n][t], w.dtype) for n in ("q", "k", "v"))
+        o, keep = g.decode(q, k, v, keep_override=torch.from_numpy(pattern[t]).to(h.DEV))
+        o_ref, err = R.decode_attn_append(dec["q"][t], dec["k"][t], dec["v"][t], pattern[t], cache, g.scale)
+        assert not err.any()
+        assert np.array_equal(g.cache_len.cpu().numpy(), cache.cache_len)
+        _assert_out_close(h.as_f64(o), o_ref, w.dtype, f"decode {t}")
+    assert np.array_equal(h.bits(g.pages), cache.pages)
+
+
+@pytest.mark.parametrize("B,H,Dh", [(1, 1, 64), (3, 5, 128), (64, 2, 64), (2, 40, 128)])
+def test_decode_shapes_and_ragged_lengths(B, H, Dh):
+    """Odd head counts, the largest batch the scoring fast path takes, several splits (small B*H) and none."""
+    h = _H()
+    T = 3
+    w = W.make("shapes", "bf16", 256, H, Dh, B, 0, 0, 0, 1.0, T)
+    rs = np.random.RandomState(B * 100 + H)
+    lens = rs.randint(0, 150, size=B).astype(np.int32)
+    lens[0] = 0
+    mp = (int(lens.max()) + T) // 16 + 2
+    bt = rng.permutation(7, "bt", B * mp).reshape(B, mp).astype(np.int32)
+    g = h.GpuPath(w, None, None, n_pages=B * mp, bt=bt)
+    pages_np = W.store(rng.normal(7, f"pages{B}{H}", (B * mp, 2, H, 16, Dh)), "bf16")
+    g.pages.copy_(h.to_dev(pages_np, "bf16"))
+    g.cache_len.copy_(torch.from_numpy(lens))
+    cache = R.PagedCache(B * mp, bt, H, Dh, "bf16")
+    cache.pages[...] = pages_np
+    cache.cache_len[...] = lens
+    dec = W.decode_inputs(w, T)
+    for t in range(T):
+        keep = rng.bernoulli(7, f"keep{t}", (B,), 0.5)
+        q, k, v = (h.to_dev(dec[n][t], "bf16") for n in ("q", "k", "v"))
+        o, ko = g.decode(q, k, v, keep_override=torch.from_numpy(keep).to(h.DEV))
+        o_ref, err = R.decode_attn_append(dec["q"][t], dec["k"][t], dec["v"][t], keep, cache, g.scale)
+        assert not err.any() and np.array_equal(ko.cpu().numpy(), keep)
+        assert np.array_equal(g.cache_len.cpu().numpy(), cache.cache_len)
+        _assert_out_close(h.as_f64(o), o_ref, "bf16", f"step {t}")
+    assert np.array_equal(h.bits(g.pages), cache.pages)
+
+
+@pytest.mark.parametrize("M", [1, 15, 16, 17, 33, 64, 65, 129])
+def test_score_row_counts_around_the_kernel_switches(M):
+    h = _H()
+    w = W.make("rows", "bf16", 512, 4, 128, 1, 0, M, 0, 1.0, 0)
+    pre, pred = W.prefill_inputs(w), W.predictor(w, random_bias=True)
+    g = h.GpuPath(w, pre, pred)
+    ref = R.score(pre["hidden"], pred["W1"], pred["b1"], pred["W2"], pred["b2"], "bf16")
+    assert np.abs(g.score_rows(g.pre["hidden"]).cpu().numpy() - ref).max() <= TOL
+    assert np.abs(g.score_vision().cpu().numpy() - ref).max() <= TOL
+
+
+def test_results_are_bit_reproducible():
+    """Every reduction runs in a fixed order (or in integer arithmetic): repeating a call must not change a bit."""
+    h = _H()
+    w = W.config(1)
+    w.T = 6
+    pre, dec, pred = W.prefill_inputs(w), W.decode_inputs(w), W.predictor(w)
+    runs = []
+    for _ in range(3):
+        g = h.GpuPath(w, pre, pred)
+        D = g.score_vision()
+        out = g.select_compact(D)
+        total = int(out["out_off"][-1].item())
+        O = g.prefill(out["Q_out"][:total].contiguous(), out["out_off"])
+        outs = [D.clone(), O.view(torch.int16).clone()]
+        for t in range(w.T):
+            x = h.to_dev(dec["x"][t], w.dtype)
+            q, k, v = (h.to_dev(dec[n][t], w.dtype) for n in ("q", "k", "v"))
+            Dt = g.score_rows(x)
+            o, keep = g.decode(q, k, v, logits=Dt, theta=0.0)
+            outs += [Dt.clone(), o.view(torch.int16).clone(), keep.clone()]
+        outs.append(g.pages.view(torch.int16).clone())
+        runs.append(outs)
+    for other in runs[1:]:
+        for a, b in zip(runs[0], other):
+            assert torch.equal(a, b)
+
+
+def test_outputs_stay_inside_their_buffers():
+    """Guard regions around every output keep their sentinel."""
+    h = _H()
+    w = W.make("guard", "bf16", 256, 3, 128, 2, [2, 1], [30, 21], [5, 0], 0.5, 2, project_qkv=True)
+    pre, dec, pred = W.prefill_inputs(w), W.decode_inputs(w), W.predictor(w)
+    g = h.GpuPath(w, pre, pred)
+    G = 64
+
+    def guarded(n, dtype, fill):
+        buf = torch.full((n + 2 * G,), fill, dtype=dtype, device=h.DEV)
+        return buf, buf[G:G + n]
+
+    M = int(sum(w.n_vis))
+    lbuf, logits = guarded(2 * M, torch.float32, 777.0)
+    p = g.pred
+    P.dllava_score(g.pre["hidden"], w.d, M, w.B, g.seq_off, g.vis_start, g.vis_len, w.d, w.dh, p["W1"], p["b1"], p["W2"],
+                   p["b2"], g.code, logits, g.ws_score)
+    kept = int(sum(w.kept_len))
+    mbuf, mask = guarded(w.sumN, torch.uint8, 99)
+    ibuf, kidx = guarded(w.sumN, torch.int32, -5)
+    obuf, off = guarded(w.B + 1, torch.int32, -5)
+    hbuf, hout = guarded(kept * w.d, torch.bfloat16, 3.0)
+    qbuf, qout = guarded(kept * w.H * w.Dh, torch.bfloat16, 3.0)
+    P.dllava_select_compact(logits, w.B, g.seq_off, g.vis_start, g.vis_len, w.sumN, P.MODE_TOPK, w.keep_ratio, 0.0,
+                            g.pre["hidden"], hout, w.d, g.pre["Q"], qout, g.pre["K"], g.pre["V"], g.cache, mask, kidx, off,
+                            g.err, g.code, g.ws_select)
+    Obuf, O = guarded(kept * w.H * w.Dh, torch.bfloat16, 3.0)
+    P.dllava_prefill_attn(qout, None, None, g.cache, w.B, off, kept, w.H, w.Dh, g.scale, O, g.code)
+    dbuf, o = guarded(w.B * w.H * w.Dh, torch.bfloat16, 3.0)
+    kbuf, keep = guarded(w.B, torch.uint8, 99)
+    q, k, v = (h.to_dev(dec[n][0], w.dtype) for n in ("q", "k", "v"))
+    ov = torch.ones(w.B, dtype=torch.uint8, device=h.DEV)
+    P.dllava_decode_attn_append(q, k, v, w.B, None, 0.0, ov, g.cache, g.scale, o, keep, g.err, g.ws_decode)
+    torch.cuda.synchronize()
+    for buf, fill in ((lbuf, 777.0), (mbuf, 99), (ibuf, -5), (obuf, -5), (hbuf, 3.0), (qbuf, 3.0), (Obuf, 3.0), (dbuf, 3.0),
+                      (kbuf, 99)):
+        assert bool((buf[:G] == fill).all()) and bool((buf[-G:] == fill).all())
+    assert int(kidx[kept - 1].item()) >= 0 and bool((kidx[kept:] == -5).all())     # only sum N* entries are written
+
+
+def test_decode_loop_replays_from_a_hip_graph():
+    """The path never synchronises with the host, so a decode loop can be captured once and replayed.  Every replay,
+    with eager work and synchronisations in between, must reproduce the eager result bit for bit."""
+    h = _H()
+    w = W.make("graph", "bf16", 512, 4, 128, 3, [2, 0, 1], [40, 25, 31], [6, 3, 9], 0.4, 12, project_qkv=True)
+    pre, dec, pred = W.prefill_inputs(w), W.decode_inputs(w), W.predictor(w)
+    g = h.GpuPath(w, pre, pred)
+    D = g.score_vision()
+    x = h.to_dev(dec["x"], w.dtype)
+    q, k, v = (h.to_dev(dec[n], w.dtype) for n in ("q", "k", "v"))
+    T = w.T
+    td = torch.bfloat16
+    o = torch.zeros((T, w.B, w.H, w.Dh), dtype=td, device=h.DEV)
+    lg = torch.zeros((T, w.B, 2), dtype=torch.float32, device=h.DEV)
+    kp = torch.zeros((T, w.B), dtype=torch.uint8, device=h.DEV)
+    mask = torch.zeros(w.sumN, dtype=torch.uint8, device=h.DEV)
+    kidx = torch.zeros(w.sumN, dtype=torch.int32, device=h.DEV)
+    off = torch.zeros(w.B + 1, dtype=torch.int32, device=h.DEV)
+    p = g.pred
+
+    def loop():
+        P.dllava_select_compact(D, w.B, g.seq_off, g.vis_start, g.vis_len, w.sumN, P.MODE_TOPK, w.keep_ratio, 0.0, None, None,
+                                w.d, None, None, g.pre["K"], g.pre["V"], g.cache, mask, kidx, off, g.err, g.code, g.ws_select)
+        for t in range(T):
+            P.dllava_score(x[t], w.d, w.B, 0, None, None, None, w.d, w.dh, p["W1"], p["b1"], p["W2"], p["b2"], g.code, lg[t],
+                           g.ws_score_small)
+            P.dllava_decode_attn_append(q[t], k[t], v[t], w.B, lg[t], 0.0, None, g.cache, g.scale, o[t], kp[t], g.err,
+                                        g.ws_decode)
+
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        loop()
+        st.synchronize()
+        ref = [o.view(torch.int16).clone(), lg.clone(), kp.clone(), g.pages.view(torch.int16).clone(), g.cache_len.clone()]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            loop()
+        for rep in range(4):
+            o.zero_(); lg.zero_(); kp.zero_()                # eager work between replays
+            g.cache_len.fill_(12345)
+            st.synchronize()
+            graph.replay()
+            st.synchronize()
+            got = [o.view(torch.int16), lg, kp, g.pages.view(torch.int16), g.cache_len]
+            for a, b in zip(ref, got):
+                assert torch.equal(a, b), rep
+    assert int(g.err.item()) == 0
