@@ -8,8 +8,9 @@
 // leave the chip, and only one cross-lane step (lanes l and l+32, or l+16/l+32/l+48) is left.
 //
 //  * score_gemm_kernel   (M > 64, prefill): 128 units x 128 tokens per block, 4 waves of 64x64 built from
-//    v_mfma_f32_32x32x16_bf16, the hidden dimension streamed through double-buffered padded LDS tiles with the
-//    global loads two stages ahead in registers, LDS-only barriers, XCD-aware tile order.  Each block leaves a
+//    v_mfma_f32_32x32x16_bf16, the hidden dimension streamed in 64-element stages (whole 128-byte memory lines
+//    per row) through one swizzled LDS tile pair, the global loads two stages ahead in registers, LDS-only
+//    barriers, three blocks per compute unit, XCD-aware tile order.  Each block leaves a
 //    partial logit pair per token; the last block of a token tile (device-scope counter) adds the dh/128
 //    partials in tile order and the bias.
 //  * score_skinny_kernel (M <= 64, decode: one row per sequence): bandwidth-bound on W1; see score_skinny.h.
@@ -51,9 +52,8 @@ __global__ __launch_bounds__(kSkThreads) void score_skinny_kernel(ScoreArgs a, u
 // ------------------------------------------------------------------------------------------------
 constexpr int kGThreads = 256;
 constexpr int kTU = 128, kTM = 128;
-constexpr int kBK = 32;             // hidden-dimension elements per pipeline stage (64 bytes per row)
-constexpr int kLd = kBK + 8;        // padded LDS row (elements): 80 bytes, conflict-free 16-byte fragment reads
-constexpr int kTileElems = 128 * kLd;
+constexpr int kBK = 64;             // hidden-dimension elements per pipeline stage: 128 bytes per row, one memory line
+constexpr int kTileElems = 128 * kBK;
 constexpr int kXcds = 8;            // accelerator complex dies of the chip
 
 // LDS-only block barrier: waits for this wave's LDS traffic, not for its outstanding global loads.  The generic
@@ -67,8 +67,8 @@ __device__ __forceinline__ void lds_barrier() {
 
 __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4))) void score_gemm_kernel(
     ScoreArgs a, int32_t* counters, float* partial, int n_unit_tiles) {
-  __shared__ __align__(16) bf16_t sA[2 * kTileElems];  // [2][128][kLd]  W1 tile (units)
-  __shared__ __align__(16) bf16_t sB[2 * kTileElems];  // [2][128][kLd]  x tile (tokens)
+  __shared__ __align__(16) bf16_t sA[kTileElems];  // [128][64]  W1 tile (units), chunks swizzled
+  __shared__ __align__(16) bf16_t sB[kTileElems];  // [128][64]  x tile (tokens)
   __shared__ float sm_p[2][kTM][2];
   __shared__ int sm_last;
 
@@ -85,45 +85,67 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
   const bf16_t* W1 = static_cast<const bf16_t*>(a.W1);
   const bf16_t* X = static_cast<const bf16_t*>(a.x);
 
-  // global -> registers -> LDS staging: thread handles the 16-byte chunk lc of rows lr and lr + 64 of each tile
-  const int lc = tid & 3, lr = tid >> 2;
-  const bf16_t *gA0, *gA1, *gB0, *gB1;
+  // Global -> registers -> LDS staging.  A stage is 128 bytes of each row, and 8 consecutive lanes fetch one
+  // row's piece as one whole memory line: a half-line piece (32 elements) moves the full line through the
+  // caches anyway and was measured at half the load throughput.  Thread: 16-byte chunk lc of rows lr + 32*j.
+  // LDS swizzle: chunk c of row r sits at chunk position c ^ ((r / 2) % 8).  The LDS serves a 16-byte access 16
+  // lanes at a time over 64 banks (16 bank groups of 16 bytes); with this placement the staging stores (2 rows
+  // x 8 chunks per 16 lanes) and the fragment loads (16 rows x 1 chunk) each touch 16 different bank groups.
+  const int lc = tid & 7, lr = tid >> 3;
+  const int st_off = lr * kBK + (lc ^ ((lr >> 1) & 7)) * 8;
+  const bf16_t *gA0, *gA1, *gA2, *gA3, *gB0, *gB1, *gB2, *gB3;
   {
-    int64_t u0 = static_cast<int64_t>(ut) * kTU + lr, u1 = u0 + 64;
-    if (u0 >= dh) u0 = dh - 1;  // clamped rows carry zero W2 weights in the epilogue
-    if (u1 >= dh) u1 = dh - 1;
-    gA0 = W1 + u0 * d + lc * 8;
-    gA1 = W1 + u1 * d + lc * 8;
-    int64_t m0 = static_cast<int64_t>(mt) * kTM + lr, m1 = m0 + 64;
-    if (m0 >= M) m0 = M - 1;
-    if (m1 >= M) m1 = M - 1;
-    int64_t s0 = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m0);
-    int64_t s1 = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m1);
-    if (s0 < 0) s0 = 0;
-    if (s1 < 0) s1 = 0;
-    gB0 = X + s0 * a.ldx + lc * 8;
-    gB1 = X + s1 * a.ldx + lc * 8;
+    const bf16_t* ga[4];
+    const bf16_t* gb[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int64_t u = static_cast<int64_t>(ut) * kTU + lr + 32 * j;
+      if (u >= dh) u = dh - 1;  // clamped rows carry zero W2 weights in the epilogue
+      ga[j] = W1 + u * d + lc * 8;
+      int64_t m = static_cast<int64_t>(mt) * kTM + lr + 32 * j;
+      if (m >= M) m = M - 1;
+      int64_t sr = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m);
+      if (sr < 0) sr = 0;
+      gb[j] = X + sr * a.ldx + lc * 8;
+    }
+    gA0 = ga[0]; gA1 = ga[1]; gA2 = ga[2]; gA3 = ga[3];
+    gB0 = gb[0]; gB1 = gb[1]; gB2 = gb[2]; gB3 = gb[3];
   }
-  // two register sets: the loads of stage kt+2 are in flight while stage kt is multiplied
-  u32x4 pa0, pa1, pb0, pb1, qa0, qa1, qb0, qb1;
-#define DLLAVA_GLOAD(S, kt)                                          \
-  {                                                                  \
-    const int64_t ko = static_cast<int64_t>(kt) * kBK;               \
-    S##a0 = *reinterpret_cast<const u32x4*>(gA0 + ko);               \
-    S##a1 = *reinterpret_cast<const u32x4*>(gA1 + ko);               \
-    S##b0 = *reinterpret_cast<const u32x4*>(gB0 + ko);               \
-    S##b1 = *reinterpret_cast<const u32x4*>(gB1 + ko);               \
+  const int nk = static_cast<int>(d / kBK);
+  // two register sets: the loads of stages kt+1 and kt+2 are in flight while stage kt is multiplied
+  u32x4 pa0, pa1, pa2, pa3, pb0, pb1, pb2, pb3, qa0, qa1, qa2, qa3, qb0, qb1, qb2, qb3;
+  // Loads are issued unconditionally (past the end they re-read the last stage): a conditional load would make
+  // the number of outstanding loads path-dependent, and the compiler would then wait for all of them before
+  // every LDS store instead of only for the older register set.
+#define DLLAVA_GLOAD(S, kt)                                                      \
+  {                                                                              \
+    const int64_t ko = static_cast<int64_t>((kt) < nk ? (kt) : nk - 1) * kBK;    \
+    S##a0 = *reinterpret_cast<const u32x4*>(gA0 + ko);                           \
+    S##a1 = *reinterpret_cast<const u32x4*>(gA1 + ko);                           \
+    S##a2 = *reinterpret_cast<const u32x4*>(gA2 + ko);                           \
+    S##a3 = *reinterpret_cast<const u32x4*>(gA3 + ko);                           \
+    S##b0 = *reinterpret_cast<const u32x4*>(gB0 + ko);                           \
+    S##b1 = *reinterpret_cast<const u32x4*>(gB1 + ko);                           \
+    S##b2 = *reinterpret_cast<const u32x4*>(gB2 + ko);                           \
+    S##b3 = *reinterpret_cast<const u32x4*>(gB3 + ko);                           \
   }
-#define DLLAVA_SSTORE(S, buf)                                        \
-  {                                                                  \
-    const int o = (buf) * kTileElems + lr * kLd + lc * 8;            \
-    *reinterpret_cast<u32x4*>(sA + o) = S##a0;                       \
-    *reinterpret_cast<u32x4*>(sA + o + 64 * kLd) = S##a1;            \
-    *reinterpret_cast<u32x4*>(sB + o) = S##b0;                       \
-    *reinterpret_cast<u32x4*>(sB + o + 64 * kLd) = S##b1;            \
+  // a stage past the end (odd stage count) is stored with a zero W1 tile, so it adds nothing
+#define DLLAVA_SSTORE(S, kt)                                                     \
+  {                                                                              \
+    if ((kt) >= nk) S##a0 = S##a1 = S##a2 = S##a3 = u32x4{0u, 0u, 0u, 0u};       \
+    *reinterpret_cast<u32x4*>(sA + st_off) = S##a0;                              \
+    *reinterpret_cast<u32x4*>(sA + st_off + 32 * kBK) = S##a1;                   \
+    *reinterpret_cast<u32x4*>(sA + st_off + 64 * kBK) = S##a2;                   \
+    *reinterpret_cast<u32x4*>(sA + st_off + 96 * kBK) = S##a3;                   \
+    *reinterpret_cast<u32x4*>(sB + st_off) = S##b0;                              \
+    *reinterpret_cast<u32x4*>(sB + st_off + 32 * kBK) = S##b1;                   \
+    *reinterpret_cast<u32x4*>(sB + st_off + 64 * kBK) = S##b2;                   \
+    *reinterpret_cast<u32x4*>(sB + st_off + 96 * kBK) = S##b3;                   \
   }
 
   const int wu = (w >> 1) * 64, wm = (w & 1) * 64;  // this wave's 64 units x 64 tokens
+  // fragment of k-step ks: chunk 2*ks + lane/32 of row lane%32 (+ multiples of 32), at its swizzled position
+  const int ld_off = (lane & 31) * kBK + ((lane >> 5) ^ ((lane >> 1) & 7)) * 8;
   f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -132,15 +154,15 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-#define DLLAVA_COMPUTE(buf)                                                                              \
+#define DLLAVA_COMPUTE()                                                                                 \
   {                                                                                                      \
-    const bf16_t* tA = sA + (buf) * kTileElems + (wu + (lane & 31)) * kLd + 8 * (lane >> 5);             \
-    const bf16_t* tB = sB + (buf) * kTileElems + (wm + (lane & 31)) * kLd + 8 * (lane >> 5);             \
+    const bf16_t* tA = sA + wu * kBK;                                                                    \
+    const bf16_t* tB = sB + wm * kBK;                                                                    \
     _Pragma("unroll") for (int ks = 0; ks < kBK / 16; ++ks) {                                            \
       bf16x8 fa[2], fb[2];                                                                               \
       _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                    \
-        fa[i] = as_frag(*reinterpret_cast<const uint4*>(tA + i * 32 * kLd + ks * 16));                   \
-        fb[i] = as_frag(*reinterpret_cast<const uint4*>(tB + i * 32 * kLd + ks * 16));                   \
+        fa[i] = as_frag(*reinterpret_cast<const uint4*>(tA + i * 32 * kBK + (ld_off ^ (ks * 16))));      \
+        fb[i] = as_frag(*reinterpret_cast<const uint4*>(tB + i * 32 * kBK + (ld_off ^ (ks * 16))));      \
       }                                                                                                  \
       _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                      \
         _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                    \
@@ -148,23 +170,22 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
     }                                                                                                    \
   }
 
-  // stage kt lives in LDS buffer kt % 2; its registers were loaded two iterations before it is multiplied
-  const int nk = static_cast<int>(d / kBK);  // even: d is a multiple of 64
+  // One LDS buffer (32 KiB, so three blocks share a compute unit): multiply stage kt, barrier, overwrite it with
+  // stage kt+1 from the older register set, barrier.  Other resident blocks fill the barrier gaps.
   DLLAVA_GLOAD(p, 0)
   DLLAVA_GLOAD(q, 1)
   DLLAVA_SSTORE(p, 0)
   lds_barrier();
-  // Loads are issued unconditionally (past the end they re-read the last stage and are never used): a
-  // conditional load would make the number of outstanding loads path-dependent, and the compiler would then
-  // wait for all of them before every LDS store instead of only for the older register set.
   for (int kt = 0; kt < nk; kt += 2) {
-    DLLAVA_GLOAD(p, (kt + 2 < nk ? kt + 2 : nk - 1))
-    DLLAVA_COMPUTE(0)
-    DLLAVA_SSTORE(q, 1)  // stage kt+1: waits only for the q loads, the p loads stay in flight
+    DLLAVA_GLOAD(p, kt + 2)
+    DLLAVA_COMPUTE()
     lds_barrier();
-    DLLAVA_GLOAD(q, (kt + 3 < nk ? kt + 3 : nk - 1))
-    DLLAVA_COMPUTE(1)
-    DLLAVA_SSTORE(p, 0)  // stage kt+2
+    DLLAVA_SSTORE(q, kt + 1)
+    lds_barrier();
+    DLLAVA_GLOAD(q, kt + 3)
+    DLLAVA_COMPUTE()
+    lds_barrier();
+    DLLAVA_SSTORE(p, kt + 2)
     lds_barrier();
   }
 #undef DLLAVA_GLOAD

@@ -99,6 +99,19 @@ def test_score_row_counts_around_the_kernel_switches(M):
     assert np.abs(g.score_vision().cpu().numpy() - ref).max() <= TOL
 
 
+@pytest.mark.parametrize("d", [64, 192, 320])
+def test_score_odd_number_of_pipeline_stages(d):
+    """The tiled scoring kernel pairs its 64-element stages; d = 64, 192, 320 leave an unpaired last stage."""
+    h = _H()
+    w = W.make("stages", "bf16", d, d // 64, 64, 1, 3, 200, 2, 1.0, 0)
+    pre, pred = W.prefill_inputs(w), W.predictor(w, random_bias=True)
+    g = h.GpuPath(w, pre, pred)
+    ref = R.score(pre["hidden"], pred["W1"], pred["b1"], pred["W2"], pred["b2"], "bf16")
+    assert np.abs(g.score_rows(g.pre["hidden"]).cpu().numpy() - ref).max() <= TOL
+    vis = slice(3, 203)
+    assert np.abs(g.score_vision().cpu().numpy() - ref[vis]).max() <= TOL
+
+
 def test_results_are_bit_reproducible():
     """Every reduction runs in a fixed order (or in integer arithmetic): repeating a call must not change a bit."""
     h = _H()
