@@ -194,16 +194,18 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
 
   // epilogue: lane holds, for token column (lane%32) of token tile j, units 8*(r/4) + 4*(lane/32) + r%4 of unit tile i
   const bf16_t* W2 = static_cast<const bf16_t*>(a.W2);
+  const bool has_b1 = a.b1 != nullptr;
+  const bf16_t* zero16 = reinterpret_cast<const bf16_t*>(kZeroWords);
   float p[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int64_t u = static_cast<int64_t>(ut) * kTU + wu + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-      const bool ok = u < dh;
-      const float bias = (ok && a.b1) ? a.b1[u] : 0.f;
-      const float w20 = ok ? bf16_to_f32(W2[u]) : 0.f;
-      const float w21 = ok ? bf16_to_f32(W2[dh + u]) : 0.f;
+      const bool ok = u < dh;  // operands that must be zero come from kZeroWords: no load under a condition
+      const float bias = *((ok & has_b1) ? a.b1 + u : kZeroWords);
+      const float w20 = bf16_to_f32(*(ok ? W2 + u : zero16));
+      const float w21 = bf16_to_f32(*(ok ? W2 + dh + u : zero16));
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const float g = gelu_erf_fast(acc[i][j][r] + bias);

@@ -32,6 +32,7 @@ constexpr int kSkAccStride = 32;  // in 8-byte words
 template <int NT, int WAVES, int BATCH>
 __device__ __forceinline__ void score_skinny_block(const ScoreArgs& a, int blk, int nblk, unsigned long long* acc) {
   static_assert(kSkSlices % WAVES == 0, "waves must divide the slices");
+  static_assert(BATCH % 2 == 0, "k-steps are issued in pairs");
   __shared__ float red[kSkSlices][NT][kWave][4];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
   const int M = static_cast<int>(a.M);
@@ -51,35 +52,48 @@ __device__ __forceinline__ void score_skinny_block(const ScoreArgs& a, int blk, 
     if (tok >= M) tok = M - 1;
     xrow[t] = X + static_cast<int64_t>(tok) * a.ldx + 8 * (lane >> 4);
   }
-  // epilogue operands of wave 0, requested now so that they are there when the products are
-  float eb[4], ew0[4], ew1[4];
+  // Epilogue operands, requested now so that they are there when the products are; operands that must be zero
+  // (no bias, unit past dh) come from kZeroWords through the address, so that no load sits under a condition.
+  float eb[4], ew0[4], ew1[4], eb2[2];
+  {
+    const bool has_b1 = a.b1 != nullptr;
+    const bf16_t* zero16 = reinterpret_cast<const bf16_t*>(kZeroWords);
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int64_t u = static_cast<int64_t>(blk) * kSkUnits + 4 * (lane >> 4) + r;
-    const bool ok = (w == 0) && u < a.dh;
-    eb[r] = (ok && a.b1) ? a.b1[u] : 0.f;
-    ew0[r] = ok ? bf16_to_f32(W2[u]) : 0.f;
-    ew1[r] = ok ? bf16_to_f32(W2[a.dh + u]) : 0.f;
+    for (int r = 0; r < 4; ++r) {
+      const int64_t u = static_cast<int64_t>(blk) * kSkUnits + 4 * (lane >> 4) + r;
+      const bool ok = u < a.dh;
+      eb[r] = *((ok & has_b1) ? a.b1 + u : kZeroWords);
+      ew0[r] = bf16_to_f32(*(ok ? W2 + u : zero16));
+      ew1[r] = bf16_to_f32(*(ok ? W2 + a.dh + u : zero16));
+    }
+    eb2[0] = *(a.b2 ? a.b2 : kZeroWords);
+    eb2[1] = *(a.b2 ? a.b2 + 1 : kZeroWords);
   }
-  // d is split among kSkSlices slices: slice v takes k-steps v, v+8, ... (32 elements each) and is accumulated on
-  // its own, so the arithmetic does not depend on how many waves the block has (wave w takes slices w, w+WAVES, ..).
+  // d is split among kSkSlices slices, each accumulated on its own, so the arithmetic does not depend on how many
+  // waves the block has (wave w takes slices w, w+WAVES, ..).  The unit of the split is a PAIR of k-steps = 64
+  // elements = one 128-byte memory line per row: slice v takes the pairs v, v+8, ...; its two 64-byte fragment
+  // loads of a row are issued back to back and the line crosses the memory system once.
   // BATCH k-steps are in flight at a time: the routine is a stream over W1, so what matters is the number of
   // outstanding 16-byte loads, not the MFMA rate.
-  const int ksteps = static_cast<int>(d / 32);
-  const int rot = ksteps / nblk > 0 ? ksteps / nblk : 1;
+  const int npairs = static_cast<int>(d / 64);
+  // blocks start at different columns, so that they do not sweep W1 in lockstep through the same few memory
+  // channels (rows are 2*d bytes apart); the order of a block's sum is fixed by its index
+  const int rot = npairs / nblk > 0 ? npairs / nblk : 1;
+  const int shift = (blk * rot) % npairs;  // this block's first column, in pairs
   for (int v = w; v < kSkSlices; v += WAVES) {
     sk_f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = sk_f32x4{0.f, 0.f, 0.f, 0.f};
-    const int n_it = (ksteps - v + kSkSlices - 1) / kSkSlices;
+    const int n_it = 2 * ((npairs - v + kSkSlices - 1) / kSkSlices);
     for (int it0 = 0; it0 < n_it; it0 += BATCH) {
       uint4 ra[BATCH], rb[NT][BATCH];
 #pragma unroll
       for (int u = 0; u < BATCH; ++u) {
         const bool ok = it0 + u < n_it;
-        // blocks start at different columns, so that they do not sweep W1 in lockstep through the same few
-        // memory channels (rows are 2*d bytes apart); the order of a block's sum is fixed by its index
-        const int ks = (v + (ok ? it0 + u : 0) * kSkSlices + blk * rot) % ksteps;
+        // in range: v + 8*i < npairs and shift < npairs, so one wrap at most; past the end: pair 0, result unused
+        int pair = ok ? v + ((it0 + u) >> 1) * kSkSlices + shift : 0;
+        if (pair >= npairs) pair -= npairs;
+        const int ks = 2 * pair + (u & 1);  // it0 and BATCH are even
         const int64_t ko = static_cast<int64_t>(ks) * 32;
         ra[u] = *reinterpret_cast<const uint4*>(wrow + ko);
         if (!ok) ra[u] = make_uint4(0, 0, 0, 0);  // a zero W1 fragment contributes nothing
@@ -136,7 +150,7 @@ __device__ __forceinline__ void score_skinny_block(const ScoreArgs& a, int blk, 
           if (static_cast<int>(old & 0xffull) == nblk - 1) {
             const long long total = static_cast<long long>(old + mine) >> 8;  // arithmetic shift drops the count
             a.logits[2 * tok + c] = static_cast<float>(static_cast<double>(total) * (1.0 / 4294967296.0)) +
-                                    (a.b2 ? a.b2[c] : 0.f);
+                                    eb2[c];
             __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           }
         }
