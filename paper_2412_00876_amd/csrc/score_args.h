@@ -24,7 +24,7 @@ struct ScoreArgs {
 // past dh) are loaded from here through a selected ADDRESS, so the load itself stays unconditional: a load whose
 // result is selected against a constant gets sunk under a branch by the compiler, with a full memory wait at
 // the end of every such branch (measured: a dozen serial round trips per block).
-static __device__ float kZeroWords[4] = {0.f, 0.f, 0.f, 0.f};
+static __device__ __attribute__((aligned(16))) float kZeroWords[4] = {0.f, 0.f, 0.f, 0.f};
 
 // Source row of x for logits row m (vision spans back to back), or -1 if m is beyond the spans.
 __device__ __forceinline__ int64_t score_src_row(const int32_t* seq_off, const int32_t* vis_start,

@@ -13,10 +13,11 @@
 //    barriers, three blocks per compute unit, XCD-aware tile order.  Each block leaves a
 //    partial logit pair per token; the last block of a token tile (device-scope counter) adds the dh/128
 //    partials in tile order and the bias.
-//  * score_skinny_kernel (M <= 64, decode: one row per sequence): bandwidth-bound on W1; see score_skinny.h.
+//  * score_splitk_kernel (M <= 64, decode: one row per sequence): W1 read once, cut over units and d; see
+//    score_splitk.h.
 // All reductions run in a fixed order: results are bit-reproducible.  Counters live at the start of the
 // workspace, start at zero and are returned to zero by the block that consumes them.
-#include "score_skinny.h"
+#include "score_splitk.h"
 
 namespace dllava {
 
@@ -35,17 +36,6 @@ __device__ __forceinline__ bf16x8 as_frag(const uint4& v) {
 
 constexpr size_t kCounterBytes = 4096;  // up to 1024 int32 counters at the start of the workspace
 constexpr int kMaxCounters = 1024;
-
-// ------------------------------------------------------------------------------------------------
-// skinny: M <= 16*NT tokens (score_skinny.h)
-// ------------------------------------------------------------------------------------------------
-constexpr int kSkWaves = 8;
-constexpr int kSkThreads = kSkWaves * kWave;
-
-template <int NT>
-__global__ __launch_bounds__(kSkThreads) void score_skinny_kernel(ScoreArgs a, unsigned long long* acc) {
-  score_skinny_block<NT, kSkWaves, 16>(a, blockIdx.x, gridDim.x, acc);
-}
 
 // ------------------------------------------------------------------------------------------------
 // GEMM: 128 units x 128 tokens per block
@@ -257,10 +247,8 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
 size_t score_mfma_workspace(int64_t M, int64_t d, int64_t dh) {
   (void)d;
   size_t part;
-  if (M <= 64)
-    part = static_cast<size_t>(2 * 64) * kSkAccStride * sizeof(unsigned long long);
-  else
-    part = static_cast<size_t>(ceil_div(dh, kTU)) * M * 2 * sizeof(float);
+  if (M <= 64) return round_up(split_workspace(M, d, dh), 256);
+  part = static_cast<size_t>(ceil_div(dh, kTU)) * M * 2 * sizeof(float);
   return kCounterBytes + round_up(part, 256);
 }
 
@@ -271,16 +259,16 @@ int score_mfma_launch(const ScoreArgs& a, hipStream_t st) {
   float* partial = reinterpret_cast<float*>(static_cast<char*>(a.workspace) + kCounterBytes);
   if (a.M <= 64) {
     if (a.seq_off) return 1;  // span gathering is only wired into the GEMM path
-    const unsigned grid = static_cast<unsigned>(ceil_div(a.dh, kSkUnits));
-    if (grid > 255) return 1;  // the arrival count shares a word with the sum (8 bits)
-    unsigned long long* acc = static_cast<unsigned long long*>(a.workspace);
+    const SplitPlan p = split_plan(a.d, a.dh);
+    if (p.G > kSpMaxGroups) return 1;
+    const dim3 grid(static_cast<unsigned>(p.G * p.KS)), block(kSpThreads);
     if (a.M <= 16)
-      hipLaunchKernelGGL(score_skinny_kernel<1>, dim3(grid), dim3(kSkThreads), 0, st, a, acc);
+      hipLaunchKernelGGL(score_splitk_kernel<1>, grid, block, 0, st, a, p.G, p.KS, p.ppb);
     else if (a.M <= 32)
-      hipLaunchKernelGGL(score_skinny_kernel<2>, dim3(grid), dim3(kSkThreads), 0, st, a, acc);
+      hipLaunchKernelGGL(score_splitk_kernel<2>, grid, block, 0, st, a, p.G, p.KS, p.ppb);
     else
-      hipLaunchKernelGGL(score_skinny_kernel<4>, dim3(grid), dim3(kSkThreads), 0, st, a, acc);
-    DLLAVA_CHECK_LAUNCH("score_skinny_kernel");
+      hipLaunchKernelGGL(score_splitk_kernel<4>, grid, block, 0, st, a, p.G, p.KS, p.ppb);
+    DLLAVA_CHECK_LAUNCH("score_splitk_kernel");
     return DLLAVA_OK;
   }
   const int64_t n_mt = ceil_div(a.M, kTM);
