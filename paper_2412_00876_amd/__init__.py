@@ -1,5 +1,21 @@
-"""MI355X-native sparsify-then-attend hot path of Dynamic-LLaVA (C-ABI library + ctypes binding)."""
-from .binding import (BF16, F32, MODE_THRESHOLD, MODE_TOPK, PAGE_SIZE, DllavaError, KVCache,  # noqa: F401
-                      dllava_decode_attn_append, dllava_decode_workspace, dllava_prefill_attn, dllava_score,
-                      dllava_score_workspace, dllava_select_compact, dllava_select_compact_workspace,
-                      dllava_version)
+"""MI355X-native sparsify-then-attend hot path of Dynamic-LLaVA (C-ABI library + ctypes binding).
+
+The binding (and with it the shared library) is loaded on first use of any of its names, so that the build
+module can be imported before the library exists.  There is no fallback: without the built library the first
+use raises ImportError.
+"""
+_BINDING_NAMES = ("BF16", "F32", "MODE_THRESHOLD", "MODE_TOPK", "PAGE_SIZE", "DllavaError", "KVCache", "EXPORTS",
+                  "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_prefill_attn", "dllava_score",
+                  "dllava_score_workspace",
+                  "dllava_select_compact", "dllava_select_compact_workspace", "dllava_version", "lib")
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES:
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")
+
+
+def __dir__():
+    return sorted(list(globals()) + list(_BINDING_NAMES))

@@ -101,3 +101,14 @@ def test_product_path_has_no_cpu_fallback():
         if fn.endswith(".py"):
             src = open(os.path.join(pkg, fn)).read()
             assert "oracle" not in src, fn
+
+
+def test_build_module_imports_without_loading_the_library():
+    """The package loads the binding (and the shared library) on first use only, so the build module can be imported
+    on a tree where the library does not exist yet or is older than the binding."""
+    import subprocess
+    import sys
+    code = ("import sys; import paper_2412_00876_amd.build as b; "
+            "assert 'paper_2412_00876_amd.binding' not in sys.modules; assert callable(b.build); print('ok')")
+    out = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True)
+    assert out.returncode == 0 and out.stdout.strip() == "ok", out.stderr
