@@ -16,9 +16,10 @@
 // call; each is reset by the block that consumes it):
 //   * cache_len[b] may only advance once every block of sequence b has read it.  Each block draws a ticket
 //     right after its read; the block holding the last ticket commits the keep decision: it stores the new
-//     token's K/V for all heads at position cache_len[b] (a slot no block reads in this launch) and advances
-//     the length.  Same-address atomics are slow (they serialise at the memory side), but drawn at the start
-//     their latency is hidden behind the page stream.
+//     token's K/V for all heads at position cache_len[b] (a slot whose content no block uses in this launch)
+//     and advances the length -- at once when there is one block per (b, h), at its end otherwise.  Same-address
+//     atomics are slow (they serialise at the memory side), but drawn at the start their latency is hidden
+//     behind the page stream.
 //   * with S > 1, the last of the S blocks of (b, h) to finish merges the S partial (max, sum, accumulator)
 //     triples in split order -- a fixed order, so the result is bit-reproducible -- and writes o[b, h].
 #include <limits.h>
@@ -240,6 +241,21 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
   }
   int pg_next = (p + stride < P) ? bt[p + stride] : 0;
 
+  // With one block per (b, h) the block that drew the last ticket of sequence b already knows that every block of
+  // b has read cache_len[b]: it appends and advances the length NOW, while its first page is still on its way,
+  // instead of at its end, where the work would lengthen the tail of the launch.  Slot cache_len[b] lies beyond
+  // what any block of this launch uses (rows past the length are masked by position, whatever they hold).
+  __shared__ int sm_flag, sm_commit;
+  if (S == 1) {
+    if (tid == 0) {
+      const int commit = (ticket == H - 1);
+      if (commit) zero_agent(&a.cnt_b[b * kCnt]);
+      sm_commit = commit;
+    }
+    __syncthreads();
+    if (sm_commit) commit_sequence<T, DH>(a, b);
+  }
+
   LaneDot<T> qd;
   qd.init(qrow, lane % C::G, a.scale_log2);
   AttnState<C::E> st;
@@ -274,7 +290,6 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
 
   __shared__ float sm_acc[NW][DH];
   __shared__ float sm_m[NW], sm_l[NW];
-  __shared__ int sm_flag, sm_commit;
   if (lane < C::G) {
 #pragma unroll
     for (int e = 0; e < C::E; ++e) sm_acc[w][lane * C::E + e] = st.acc[e];
@@ -284,11 +299,9 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
     }
   }
   const int target = H;  // tickets on cnt_b[b] before the sequence may be committed
-  if (tid == 0) {
+  if (S > 1 && tid == 0) {
     int commit = 0;
-    if (S == 1) {
-      commit = (ticket == target - 1);
-    } else if (ticket == S - 1) {
+    if (ticket == S - 1) {
       // every block of (b, h) has read the length once the last reader's ticket is out; that block reports
       // the head to the sequence counter
       zero_agent(&a.cnt_bh[bh * kCnt]);
@@ -358,7 +371,7 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
 
   // The block that drew the last ticket of sequence b knows every block of b has read cache_len[b]: it alone
   // appends and advances the length.
-  if (sm_commit) commit_sequence<T, DH>(a, b);
+  if (S > 1 && sm_commit) commit_sequence<T, DH>(a, b);
 }
 
 template <typename T, int DH, int NW>
