@@ -199,8 +199,8 @@ def cpu_baseline(path, seconds):
 
 
 def pmc_probe(path, torch, L):
-    """Dispatches whose HBM counters are read with `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`:
-    a plain device-to-device copy of known size (the scale of the counters), then the decode kernel."""
+    """Dispatches whose hardware counters are read with `rocprofv3 --pmc ...`: a plain device-to-device copy of known
+    size (the scale of the byte counters), one dispatch of every prefill kernel, then the decode kernel three times."""
     w = path.w
     cap = path.cache.max_pages_per_seq * 16
     if L > cap:
@@ -212,6 +212,8 @@ def pmc_probe(path, torch, L):
     dst.copy_(src)                                   # calibration dispatch: reads n bytes, writes n bytes
     torch.cuda.synchronize()
     path.score_vision(); path.select_compact()      # fills the first kept_len tokens of every sequence
+    path.prefill_attn()                              # (one dispatch each of the prefill kernels, for their counters)
+    path.score_decode(0)
     path.pages.normal_()                             # slots beyond that: arbitrary finite data
     path.cache_len.fill_(L)
     keep0 = torch.zeros(w.B, dtype=torch.uint8, device="cuda:0")
@@ -222,8 +224,13 @@ def pmc_probe(path, torch, L):
                                          path.ws_decode)
     torch.cuda.synchronize()
     es = 2 if w.dtype == "bf16" else 4
+    rows = int(path.out_off[-1].item())
+    n_kept = [int(v) for v in (path.out_off[1:] - path.out_off[:-1]).tolist()]
     print(json.dumps({"pmc_probe": True, "copy_bytes_read": n, "copy_bytes_written": n, "cache_len": L,
-                      "decode_algorithmic_bytes_per_launch": w.B * L * 2 * w.H * w.Dh * es}))
+                      "decode_algorithmic_bytes_per_launch": w.B * L * 2 * w.H * w.Dh * es,
+                      "score_vision_flops": 2.0 * path.M_vis * w.d * w.dh,
+                      "prefill_attn_flops": float(sum(4.0 * w.H * w.Dh * m * (m + 1) / 2 for m in n_kept)),
+                      "compact_algorithmic_bytes": 2 * rows * (2 * w.d + 6 * w.H * w.Dh) * es // 2}))
 
 
 def main():
