@@ -129,6 +129,15 @@ __device__ __forceinline__ void block_publish() {
   __syncthreads();
 }
 
+// LDS-only block barrier: waits for this wave's LDS traffic, not for its outstanding global loads.  The generic
+// __syncthreads() drains the vector-memory counter as well, which would stall every stage of the pipeline on
+// the prefetches that were just issued.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
 // The keep decision of Eq. 5 for one text token: margin of the float32 logits against a threshold.
 __device__ __forceinline__ bool keep_from_logits(const float* logits, int row, float threshold) {
   const float margin = logits[2 * row + 1] - logits[2 * row];

@@ -33,31 +33,33 @@ struct Stage {
 };
 #define DLLAVA_FOR_STAGE(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7)
 
-// address of the 16-byte chunk sc of key `key` (sequence b, head h) in K (kv = 0) or V (kv = 1)
-template <int DH>
-__device__ __forceinline__ const bf16_t* kv_chunk(const PrefillArgs& a, int kv, int b, int r0, int h, int key, int sc) {
-  const int H = a.H;
-  if (a.K) {
-    const size_t o = (static_cast<size_t>(r0 + key) * H + h) * DH + sc * 8;
-    return static_cast<const bf16_t*>(kv ? a.V : a.K) + o;
-  }
-  const int pg = a.block_table[static_cast<size_t>(b) * a.max_pages + key / kPage];
-  const size_t tl = static_cast<size_t>(kPage) * DH;
-  return static_cast<const bf16_t*>(a.pages) + ((static_cast<size_t>(pg) * 2 + kv) * H + h) * tl +
-         static_cast<size_t>(key % kPage) * DH + sc * 8;
-}
-
-// global -> registers: rows of K and V for key tile t (rows past last_key repeat it; the causal test masks them)
-template <int DH, int N, int THREADS>
-__device__ __forceinline__ void stage_load(Stage<N>& st, const PrefillArgs& a, int t, int b, int r0, int h,
-                                           int last_key, int sr, int sc) {
+// global -> registers: rows of K and V for key tile t (rows past last_key repeat it; the causal test masks them).
+// PAGED: K/V come from the cache pages.  A tile of 32 keys lies in two pages whose ids are the same for the whole
+// block, so they arrive as two scalar loads per tile (pg_lo for keys < 16 of the tile, pg_hi for the rest) and the
+// 16-byte loads themselves are straight-line; a page-table lookup per load would put a dependent round trip, and a
+// branch, in front of every one of them.
+template <int DH, int N, int THREADS, bool PAGED>
+__device__ __forceinline__ void stage_load(Stage<N>& st, const PrefillArgs& a, int t, int r0, int h, int last_key,
+                                           int sr, int sc, int pg_lo, int pg_hi) {
   constexpr int kRowStep = THREADS / (DH / 8);
+  const int H = a.H;
+  const size_t tl = static_cast<size_t>(kPage) * DH;
 #define DLLAVA_LD(i)                                                                              \
   if constexpr (i < N) {                                                                          \
     int key = t * kBN + sr + kRowStep * i;                                                        \
     if (key > last_key) key = last_key;                                                           \
-    st.k##i = *reinterpret_cast<const u32x4*>(kv_chunk<DH>(a, 0, b, r0, h, key, sc));             \
-    st.v##i = *reinterpret_cast<const u32x4*>(kv_chunk<DH>(a, 1, b, r0, h, key, sc));             \
+    if constexpr (PAGED) {                                                                        \
+      const int pg = (key - t * kBN) < kPage ? pg_lo : pg_hi;                                     \
+      const size_t o = ((static_cast<size_t>(pg) * 2) * H + h) * tl +                             \
+                       static_cast<size_t>(key % kPage) * DH + sc * 8;                            \
+      const bf16_t* base = static_cast<const bf16_t*>(a.pages) + o;                               \
+      st.k##i = *reinterpret_cast<const u32x4*>(base);                                            \
+      st.v##i = *reinterpret_cast<const u32x4*>(base + static_cast<size_t>(H) * tl);              \
+    } else {                                                                                      \
+      const size_t o = (static_cast<size_t>(r0 + key) * H + h) * DH + sc * 8;                     \
+      st.k##i = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(a.K) + o);             \
+      st.v##i = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(a.V) + o);             \
+    }                                                                                             \
   }
   DLLAVA_FOR_STAGE(DLLAVA_LD)
 #undef DLLAVA_LD
@@ -142,7 +144,19 @@ __global__ __launch_bounds__(NWQ * kWave) void prefill_mfma_kernel(PrefillArgs a
   // staging: thread -> (key row sr + (kThreads/kChunks)*i, chunk sc)
   const int sc = tid % kChunks, sr = tid / kChunks;
   Stage<kLoads> stg;
-#define STAGE_LOAD(t) stage_load<DH, kLoads, kThreads>(stg, a, (t), b, r0, h, last_key, sr, sc)
+  const bool paged = a.K == nullptr;  // block-uniform
+  const int32_t* bt = a.block_table + static_cast<size_t>(b) * a.max_pages;
+  const int last_page = last_key / kPage;
+  // page ids of tile t: block-uniform indices, so these are scalar loads
+#define STAGE_LOAD(t)                                                                                      \
+  {                                                                                                        \
+    if (paged) {                                                                                           \
+      const int p_lo = 2 * (t), p_hi = 2 * (t) + 1 < last_page ? 2 * (t) + 1 : last_page;                  \
+      stage_load<DH, kLoads, kThreads, true>(stg, a, (t), r0, h, last_key, sr, sc, bt[p_lo], bt[p_hi]);    \
+    } else {                                                                                               \
+      stage_load<DH, kLoads, kThreads, false>(stg, a, (t), r0, h, last_key, sr, sc, 0, 0);                 \
+    }                                                                                                      \
+  }
 #define STAGE_STORE() stage_store<DH, kLoads, kThreads>(stg, sK, sVt, sr, sc)
 
   STAGE_LOAD(0);

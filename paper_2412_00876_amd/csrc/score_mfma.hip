@@ -46,15 +46,6 @@ constexpr int kBK = 64;             // hidden-dimension elements per pipeline st
 constexpr int kTileElems = 128 * kBK;
 constexpr int kXcds = 8;            // accelerator complex dies of the chip
 
-// LDS-only block barrier: waits for this wave's LDS traffic, not for its outstanding global loads.  The generic
-// __syncthreads() drains the vector-memory counter as well, which would stall every stage of the pipeline on
-// the prefetches that were just issued.
-__device__ __forceinline__ void lds_barrier() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-}
-
 __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4))) void score_gemm_kernel(
     ScoreArgs a, int32_t* counters, float* partial, int n_unit_tiles) {
   __shared__ __align__(16) bf16_t sA[kTileElems];  // [128][64]  W1 tile (units), chunks swizzled
