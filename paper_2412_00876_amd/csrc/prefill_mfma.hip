@@ -74,7 +74,9 @@ __device__ __forceinline__ void stage_store(const Stage<N>& st, bf16_t* sK, bf16
   if constexpr (i < N) {                                                                          \
     const int row = sr + kRowStep * i;                                                            \
     *reinterpret_cast<u32x4*>(sK + row * kKLd + sc * 8) = st.k##i;                                \
-    bf16_t* vt = sVt + (sc * 8) * kVPad + row; /* dims 8*sc + 0..7 of key `row` */                \
+    /* dims 8*sc + 0..7 of key `row`; the key position is XORed with 8*(dim/32) so that the 16 chunks */ \
+    /* of a key row, whose V^T rows are 8*kVPad elements apart, do not fall on four banks only       */ \
+    bf16_t* vt = sVt + (sc * 8) * kVPad + (row ^ (8 * (sc >> 2)));                                \
     const u32x4 v = st.v##i;                                                                      \
     vt[0 * kVPad] = static_cast<bf16_t>(v.x & 0xffffu);                                           \
     vt[1 * kVPad] = static_cast<bf16_t>(v.x >> 16);                                               \
@@ -90,7 +92,7 @@ __device__ __forceinline__ void stage_store(const Stage<N>& st, bf16_t* sK, bf16
 }
 
 template <int DH, int NWQ>
-__global__ __launch_bounds__(NWQ * kWave) void prefill_mfma_kernel(PrefillArgs a, int tiles_cap) {
+__global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_kernel(PrefillArgs a, int tiles_cap) {
   constexpr int kThreads = NWQ * kWave;
   constexpr int kBM = NWQ * 32;
   constexpr int kKLd = DH + 8;           // K tile row (elements), padded: conflict-free 16-byte fragment reads
@@ -231,10 +233,11 @@ __global__ __launch_bounds__(NWQ * kWave) void prefill_mfma_kernel(PrefillArgs a
       }
 #pragma unroll
       for (int nb = 0; nb < kDB; ++nb) {
-        const bf16_t* vrow = sVt + (nb * 32 + lq) * kVPad + 16 * half + 4 * g;
+        // key positions are XORed with 8*nb in this block of 32 dims (see stage_store)
+        const bf16_t* vrow = sVt + (nb * 32 + lq) * kVPad + 4 * g;
         union { uint2 u[2]; bf16x8 f; } va;
-        va.u[0] = *reinterpret_cast<const uint2*>(vrow);      // keys 16*half + 4g + 0..3
-        va.u[1] = *reinterpret_cast<const uint2*>(vrow + 8);  // keys 16*half + 8 + 4g + 0..3
+        va.u[0] = *reinterpret_cast<const uint2*>(vrow + ((16 * half) ^ (8 * nb)));      // keys 16*half + 4g + 0..3
+        va.u[1] = *reinterpret_cast<const uint2*>(vrow + ((16 * half + 8) ^ (8 * nb)));  // keys 16*half + 8 + 4g + 0..3
         o_acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.f, pb_hi.f, o_acc[nb], 0, 0, 0);
         o_acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.f, pb_lo.f, o_acc[nb], 0, 0, 0);
       }
