@@ -279,9 +279,14 @@ int launch(const PrefillArgs& a, int64_t rows, hipStream_t st) {
 // returns 1 if the shape is not handled here
 int prefill_mfma_launch(const PrefillArgs& a, int64_t rows, int Dh, hipStream_t st) {
   if (a.H > 65535) return 1;
-  // wide tiles when there is enough work to fill the chip with them, narrow ones otherwise
+  // wide tiles (K/V tiles staged once for 128 queries) unless there is too little work to spread over the chip;
+  // measured: 4 waves win from the 7B batch-1 prefill (214 rows x 32 heads) upwards
   const int64_t work = rows * a.H;  // query rows x heads
-  const int nwq = work >= 128 * 2048 ? 4 : (work >= 64 * 1024 ? 2 : 1);
+  int nwq = work >= 4 * 1024 ? 4 : (work >= 1024 ? 2 : 1);
+  if (const char* e = getenv("DLLAVA_PREFILL_WAVES")) {  // tuning override
+    const int v = atoi(e);
+    if (v == 1 || v == 2 || v == 4) nwq = v;
+  }
   if (Dh == 128) {
     if (nwq == 4) return launch<128, 4>(a, rows, st);
     if (nwq == 2) return launch<128, 2>(a, rows, st);

@@ -112,6 +112,29 @@ def test_score_odd_number_of_pipeline_stages(d):
     assert np.abs(g.score_vision().cpu().numpy() - ref[vis]).max() <= TOL
 
 
+@pytest.mark.parametrize("waves", [1, 2, 4])
+@pytest.mark.parametrize("from_cache", [False, True])
+def test_prefill_tile_widths(waves, from_cache, monkeypatch):
+    """The matrix-core prefill kernel with 32, 64 and 128 queries per block (the library picks by problem size;
+    the tuning override forces each), ragged sequence lengths around the tile sizes."""
+    monkeypatch.setenv("DLLAVA_PREFILL_WAVES", str(waves))
+    h = _H()
+    B = 6
+    w = W.make("widths", "bf16", 512, 4, 128, B, 0, [1, 31, 33, 64, 129, 200], 0, 1.0, 0)
+    pre = W.prefill_inputs(w)
+    g = h.GpuPath(w, pre, None)
+    D = rng.normal(w.seed, "w.D", (int(sum(w.n_vis)), 2)).astype(np.float32)
+    out = g.select_compact(torch.from_numpy(D).to(h.DEV), with_hidden=False)
+    off = np.asarray(w.seq_off, np.int32)
+    ref = R.prefill_attn(pre["Q"], pre["K"], pre["V"], off, g.scale, w.dtype)
+    Qc = out["Q_out"].contiguous()
+    if from_cache:
+        O = g.prefill(Qc, out["out_off"])
+    else:
+        O = g.prefill(Qc, out["out_off"], g.pre["K"], g.pre["V"])
+    _assert_out_close(h.as_f64(O), ref, w.dtype, f"prefill {waves} waves")
+
+
 def test_results_are_bit_reproducible():
     """Every reduction runs in a fixed order (or in integer arithmetic): repeating a call must not change a bit."""
     h = _H()
