@@ -2,14 +2,15 @@
 // stream compaction of hidden states, queries and K/V into the reduced token set / paged cache
 // (Eq. 5 line 3 / Eq. 11 line 3).
 //
-// Three launches:
+// Two launches:
 //   1. select_kernel   one block per sequence.  Top-k: the k-th largest score is found exactly by a
 //                      4-pass most-significant-byte radix select over an order-preserving 32-bit key,
 //                      then one in-order pass keeps keys above it plus the first (k - #above) equal keys,
 //                      which is the "ties go to the lower index" rule.  The same pass ranks the kept
 //                      rows of the sequence (prefix sum), so kept positions come out ascending.
-//   2. offsets_kernel  exclusive scan of the per-sequence counts -> out_off, cache_len, capacity check.
-//   3. gather_kernel   one block per (compacted row, tensor): 16-byte coalesced row copies; K/V rows
+//                      The block that finishes last (device-scope ticket) scans the per-sequence counts
+//                      into out_off, sets cache_len and checks the capacity.
+//   2. gather_kernel   one block per (compacted row, tensor): 16-byte coalesced row copies; K/V rows
 //                      are scattered head by head into their page slot.
 // Selection is integer-exact: it only compares float32 keys.
 #include "common.h"
@@ -58,12 +59,21 @@ struct SelectArgs {
   uint8_t* keep_mask;
   int32_t* ws_kept;    // [sumN]: kept positions of sequence b at [seq_off[b] ...)
   int32_t* ws_counts;  // [B]
+  int32_t* ws_ticket;  // one device-scope counter, zero between calls
+  int32_t* out_off;    // [B+1]
+  int32_t* cache_len;  // [B] or null
+  int32_t cap;         // tokens a sequence's pages can hold
+  int32_t* err_flag;
 };
+
+constexpr int kKeyCache = 4096;  // scores of one vision span kept in LDS (16 KiB); longer spans re-read them
 
 __global__ __launch_bounds__(kThreads) void select_kernel(SelectArgs a) {
   __shared__ int hist[256];
   __shared__ int sm_tot[kWaves];
   __shared__ int sm_sel[2];
+  __shared__ uint32_t skey[kKeyCache];
+  __shared__ int sm_last;
   const int b = blockIdx.x, tid = threadIdx.x;
   const int s0 = a.seq_off[b];
   int N = a.seq_off[b + 1] - s0;
@@ -83,6 +93,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectArgs a) {
   block_excl_scan(part, sm_tot, lo);
   const float* D = a.logits + 2 * static_cast<size_t>(lo);
 
+  const bool cached = n <= kKeyCache;
   uint32_t kth = 0;     // key of the k-th largest score
   int need = 0;         // how many rows with key == kth are kept (taken in index order)
   bool all = false, none = false;
@@ -93,11 +104,14 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectArgs a) {
     else {
       uint32_t prefix = 0, mask = 0;
       int remaining = static_cast<int>(k);
+      // the keys are read from memory once (all loads of a thread in flight together) and kept in LDS
+      if (cached)
+        for (int i = tid; i < n; i += kThreads) skey[i] = score_key(D[2 * i + 1]);
       for (int shift = 24; shift >= 0; shift -= 8) {
         hist[tid] = 0;
         __syncthreads();
         for (int i = tid; i < n; i += kThreads) {
-          const uint32_t key = score_key(D[2 * i + 1]);
+          const uint32_t key = cached ? skey[i] : score_key(D[2 * i + 1]);
           if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
         }
         __syncthreads();
@@ -121,64 +135,88 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectArgs a) {
     }
   }
 
-  // in-order pass over all rows of the sequence
+  // In-order pass over all rows of the sequence.  Thread t owns E consecutive rows of a chunk of 256*E rows
+  // (one chunk covers sequences of up to 8192 rows), so the whole pass costs two block scans -- the rank of
+  // the rows that tie with the k-th score, then the rank of the kept rows -- instead of two per 256 rows.
+  const bool partial = a.mode == DLLAVA_MODE_TOPK && !all && !none;
+  int E = (N + kThreads - 1) / kThreads;
+  E = E < 1 ? 1 : (E > 32 ? 32 : E);
   int carry_eq = 0, carry_keep = 0;
-  for (int base = 0; base < N; base += kThreads) {
-    const int p = base + tid;
-    const bool in = p < N;
-    const bool vis = in && p >= v0 && p < v0 + n;
-    bool keep = in && !vis;
-    bool eq = false;
-    if (vis) {
-      const int i = p - v0;
-      if (a.mode == DLLAVA_MODE_TOPK) {
-        if (all) keep = true;
-        else if (!none) {
-          const uint32_t key = score_key(D[2 * i + 1]);
-          keep = key > kth;
-          eq = key == kth;
+  for (int base = 0; base < N; base += kThreads * E) {
+    const int p0 = base + tid * E;
+    uint32_t keep_bits = 0, eq_bits = 0;
+    for (int e = 0; e < E; ++e) {
+      const int p = p0 + e;
+      const bool in = p < N;
+      const bool vis = in && p >= v0 && p < v0 + n;
+      bool keep = in && !vis;
+      bool eq = false;
+      if (vis) {
+        const int i = p - v0;
+        if (a.mode == DLLAVA_MODE_TOPK) {
+          if (all) keep = true;
+          else if (!none) {
+            const uint32_t key = cached ? skey[i] : score_key(D[2 * i + 1]);
+            keep = key > kth;
+            eq = key == kth;
+          }
+        } else {
+          keep = keep_from_logits(D, i, a.threshold);
         }
-      } else {
-        keep = keep_from_logits(D, i, a.threshold);
       }
+      keep_bits |= (keep ? 1u : 0u) << e;
+      eq_bits |= (eq ? 1u : 0u) << e;
     }
-    if (a.mode == DLLAVA_MODE_TOPK && !all && !none) {
+    if (partial) {  // block-uniform
       int tot_eq;
-      const int rank_eq = carry_eq + block_excl_scan(eq ? 1 : 0, sm_tot, tot_eq);
-      if (eq && rank_eq < need) keep = true;
+      int rank_eq = carry_eq + block_excl_scan(__popc(eq_bits), sm_tot, tot_eq);
       carry_eq += tot_eq;
+      for (int e = 0; e < E; ++e)
+        if ((eq_bits >> e) & 1u) {
+          if (rank_eq < need) keep_bits |= 1u << e;
+          ++rank_eq;
+        }
     }
     int tot_keep;
-    const int pos = carry_keep + block_excl_scan(keep ? 1 : 0, sm_tot, tot_keep);
+    int pos = carry_keep + block_excl_scan(__popc(keep_bits), sm_tot, tot_keep);
     carry_keep += tot_keep;
-    if (in) {
-      a.keep_mask[static_cast<size_t>(s0) + p] = keep ? 1 : 0;
-      if (keep) a.ws_kept[static_cast<size_t>(s0) + pos] = p;
+    for (int e = 0; e < E; ++e) {
+      const int p = p0 + e;
+      if (p < N) {
+        const bool keep = (keep_bits >> e) & 1u;
+        a.keep_mask[static_cast<size_t>(s0) + p] = keep ? 1 : 0;
+        if (keep) a.ws_kept[static_cast<size_t>(s0) + pos++] = p;
+      }
     }
   }
-  if (tid == 0) a.ws_counts[b] = carry_keep;
-}
-
-__global__ __launch_bounds__(kThreads) void offsets_kernel(const int32_t* counts, int32_t B, int32_t* out_off,
-                                                           int32_t* cache_len, int32_t cap, int32_t* err_flag) {
-  __shared__ int sm_tot[kWaves];
-  const int tid = threadIdx.x;
+  // The block that finishes last turns the per-sequence counts into offsets (exclusive scan), sets the cache
+  // lengths and checks the capacity: no second launch.  Hand-off through device-scope stores and a ticket.
+  if (tid == 0) {
+    __hip_atomic_store(&a.ws_counts[b], carry_keep, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    wave_stores_done();
+    sm_last = (add_agent(a.ws_ticket, 1) == a.B - 1);
+  }
+  __syncthreads();
+  if (!sm_last) return;
   int carry = 0;
-  for (int base = 0; base < B; base += kThreads) {
-    const int b = base + tid;
-    const int c = b < B ? counts[b] : 0;
+  for (int base = 0; base < a.B; base += kThreads) {
+    const int bb = base + tid;
+    const int c = bb < a.B ? __hip_atomic_load(&a.ws_counts[bb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
     int tot;
     const int ex = carry + block_excl_scan(c, sm_tot, tot);
     carry += tot;
-    if (b < B) {
-      out_off[b] = ex;
-      if (cache_len) {
-        cache_len[b] = c > cap ? cap : c;
-        if (c > cap && err_flag) *err_flag = 1;
+    if (bb < a.B) {
+      a.out_off[bb] = ex;
+      if (a.cache_len) {
+        a.cache_len[bb] = c > a.cap ? a.cap : c;
+        if (c > a.cap && a.err_flag) *a.err_flag = 1;
       }
     }
   }
-  if (tid == 0) out_off[B] = carry;
+  if (tid == 0) {
+    a.out_off[a.B] = carry;
+    zero_agent(a.ws_ticket);
+  }
 }
 
 struct GatherArgs {
@@ -295,15 +333,13 @@ extern "C" int dllava_select_compact(const float* logits, int32_t B, const int32
   int32_t* ws_counts =
       reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + round_up(static_cast<size_t>(sumN) * 4, 256));
 
-  SelectArgs sa{logits, seq_off, vis_start, vis_len, B, mode, keep_ratio, threshold, keep_mask, ws_kept, ws_counts};
-  hipLaunchKernelGGL(select_kernel, dim3(B), dim3(kThreads), 0, st, sa);
-  DLLAVA_CHECK_LAUNCH("select_kernel");
-
+  int32_t* ws_ticket = ws_counts + round_up(static_cast<size_t>(B) * 4, 256) / 4;
   const bool write_cache = K != nullptr;
   const int32_t cap = cache ? cache->max_pages_per_seq * cache->page_size : 0;
-  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kThreads), 0, st, ws_counts, B, out_off,
-                     write_cache ? cache->cache_len : nullptr, cap, err_flag);
-  DLLAVA_CHECK_LAUNCH("offsets_kernel");
+  SelectArgs sa{logits, seq_off, vis_start, vis_len, B, mode, keep_ratio, threshold, keep_mask, ws_kept, ws_counts,
+                ws_ticket, out_off, write_cache ? cache->cache_len : nullptr, cap, err_flag};
+  hipLaunchKernelGGL(select_kernel, dim3(B), dim3(kThreads), 0, st, sa);
+  DLLAVA_CHECK_LAUNCH("select_kernel");
 
   if (sumN == 0) return DLLAVA_OK;
   GatherArgs ga{};
