@@ -10,8 +10,8 @@
 //                      rows of the sequence (prefix sum), so kept positions come out ascending.
 //                      The block that finishes last (device-scope ticket) scans the per-sequence counts
 //                      into out_off, sets cache_len and checks the capacity.
-//   2. gather_kernel   one block per (compacted row, tensor): 16-byte coalesced row copies; K/V rows
-//                      are scattered head by head into their page slot.
+//   2. gather_kernel   one block per compacted row: 16-byte coalesced copies of its hidden, Q, K and V rows;
+//                      K/V rows are scattered head by head into their page slot.
 // Selection is integer-exact: it only compares float32 keys.
 #include "common.h"
 
@@ -232,9 +232,15 @@ struct GatherArgs {
   int32_t max_pages, H, head_chunks;                              // 16-byte chunks per (token, head)
 };
 
-// grid (rows upper bound, 4): y = 0 hidden, 1 Q, 2 K, 3 V
+// 16 readable bytes: the source of the (unused) clamped loads of a tensor that is not being moved
+static __device__ __attribute__((aligned(16))) uint32_t kGatherPad[4] = {0u, 0u, 0u, 0u};
+
+// One block per compacted row moves all of its tensors: hidden, Q, K, V.  The dependent chain in front of the
+// copies (total, binary search for the sequence, kept position) is paid once per row, and every 16-byte load of
+// a trip -- two per thread and tensor, index clamped so that none sits under a condition -- is in flight
+// before the first store.
 __global__ __launch_bounds__(kThreads) void gather_kernel(GatherArgs a) {
-  const int j = blockIdx.x, what = blockIdx.y, tid = threadIdx.x;
+  const int j = blockIdx.x, tid = threadIdx.x;
   const int total = a.out_off[a.B];
   if (j >= total) return;
   int lo = 0, hi = a.B;  // largest b with out_off[b] <= j
@@ -247,29 +253,49 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(GatherArgs a) {
   const int s0 = a.seq_off[b];
   const int rel = a.ws_kept[static_cast<size_t>(s0) + pos];
   const size_t src = static_cast<size_t>(s0) + rel;
-  if (what == 0) {
-    if (tid == 0) a.kept_idx[j] = rel;
-    if (!a.hidden) return;
-    const uint4* in = a.hidden + src * a.hidden_chunks;
-    uint4* out = a.hidden_out + static_cast<size_t>(j) * a.hidden_chunks;
-    for (int64_t c = tid; c < a.hidden_chunks; c += kThreads) out[c] = in[c];
-  } else if (what == 1) {
-    if (!a.Q) return;
-    const uint4* in = a.Q + src * a.q_chunks;
-    uint4* out = a.Q_out + static_cast<size_t>(j) * a.q_chunks;
-    for (int64_t c = tid; c < a.q_chunks; c += kThreads) out[c] = in[c];
-  } else {
-    if (!a.K || pos >= a.max_pages * kPage) return;
-    const int kv = what - 2;
-    const uint4* in = (kv ? a.V : a.K) + src * a.kv_chunks;
+  if (tid == 0) a.kept_idx[j] = rel;
+
+  const bool do_h = a.hidden != nullptr, do_q = a.Q != nullptr;
+  const bool do_kv = a.K != nullptr && pos < a.max_pages * kPage;
+  const int64_t nh = do_h ? a.hidden_chunks : 0, nq = do_q ? a.q_chunks : 0, nkv = do_kv ? a.kv_chunks : 0;
+  // sources (a valid address even when the tensor is absent: the clamped loads are then simply not stored)
+  const uint4* in_h = do_h ? a.hidden + src * a.hidden_chunks : reinterpret_cast<const uint4*>(kGatherPad);
+  const uint4* in_q = do_q ? a.Q + src * a.q_chunks : reinterpret_cast<const uint4*>(kGatherPad);
+  const uint4* in_k = do_kv ? a.K + src * a.kv_chunks : reinterpret_cast<const uint4*>(kGatherPad);
+  const uint4* in_v = do_kv ? a.V + src * a.kv_chunks : reinterpret_cast<const uint4*>(kGatherPad);
+  uint4* out_h = do_h ? a.hidden_out + static_cast<size_t>(j) * a.hidden_chunks : nullptr;
+  uint4* out_q = do_q ? a.Q_out + static_cast<size_t>(j) * a.q_chunks : nullptr;
+  uint4* page_k = nullptr;
+  size_t tile_chunks = 0;
+  if (do_kv) {
     const int pg = a.block_table[static_cast<size_t>(b) * a.max_pages + pos / kPage];
-    const int slot = pos % kPage;
-    const size_t tile_chunks = static_cast<size_t>(kPage) * a.head_chunks;
-    uint4* base = a.pages + (static_cast<size_t>(pg) * 2 + kv) * a.H * tile_chunks +
-                  static_cast<size_t>(slot) * a.head_chunks;
-    for (int64_t c = tid; c < a.kv_chunks; c += kThreads) {
-      const int h = static_cast<int>(c / a.head_chunks), cc = static_cast<int>(c % a.head_chunks);
-      base[h * tile_chunks + cc] = in[c];
+    tile_chunks = static_cast<size_t>(kPage) * a.head_chunks;
+    page_k = a.pages + static_cast<size_t>(pg) * 2 * a.H * tile_chunks + static_cast<size_t>(pos % kPage) * a.head_chunks;
+  }
+  const size_t v_off = static_cast<size_t>(a.H) * tile_chunks;  // from the K half of a page to its V half
+  int64_t nmax = nh > nq ? nh : nq;
+  nmax = nmax > nkv ? nmax : nkv;
+  for (int64_t c0 = tid; c0 < nmax; c0 += 2 * kThreads) {
+    const int64_t c1 = c0 + kThreads;
+#define DLLAVA_CLAMP(c, n) ((n) > 0 ? ((c) < (n) ? (c) : (n)-1) : 0)
+    const uint4 h0 = in_h[DLLAVA_CLAMP(c0, nh)], h1 = in_h[DLLAVA_CLAMP(c1, nh)];
+    const uint4 q0 = in_q[DLLAVA_CLAMP(c0, nq)], q1 = in_q[DLLAVA_CLAMP(c1, nq)];
+    const uint4 k0 = in_k[DLLAVA_CLAMP(c0, nkv)], k1 = in_k[DLLAVA_CLAMP(c1, nkv)];
+    const uint4 v0 = in_v[DLLAVA_CLAMP(c0, nkv)], v1 = in_v[DLLAVA_CLAMP(c1, nkv)];
+#undef DLLAVA_CLAMP
+    if (c0 < nh) out_h[c0] = h0;
+    if (c1 < nh) out_h[c1] = h1;
+    if (c0 < nq) out_q[c0] = q0;
+    if (c1 < nq) out_q[c1] = q1;
+    if (c0 < nkv) {
+      const size_t o = static_cast<size_t>(c0 / a.head_chunks) * tile_chunks + static_cast<size_t>(c0 % a.head_chunks);
+      page_k[o] = k0;
+      page_k[v_off + o] = v0;
+    }
+    if (c1 < nkv) {
+      const size_t o = static_cast<size_t>(c1 / a.head_chunks) * tile_chunks + static_cast<size_t>(c1 % a.head_chunks);
+      page_k[o] = k1;
+      page_k[v_off + o] = v1;
     }
   }
 }
@@ -357,8 +383,7 @@ extern "C" int dllava_select_compact(const float* logits, int32_t B, const int32
   }
   ga.Q = static_cast<const uint4*>(Q); ga.Q_out = static_cast<uint4*>(Q_out);
   ga.K = static_cast<const uint4*>(K); ga.V = static_cast<const uint4*>(V);
-  const int parts = K ? 4 : (Q ? 2 : 1);
-  hipLaunchKernelGGL(gather_kernel, dim3(static_cast<unsigned>(sumN), parts), dim3(kThreads), 0, st, ga);
+  hipLaunchKernelGGL(gather_kernel, dim3(static_cast<unsigned>(sumN)), dim3(kThreads), 0, st, ga);
   DLLAVA_CHECK_LAUNCH("gather_kernel");
   return DLLAVA_OK;
 }
