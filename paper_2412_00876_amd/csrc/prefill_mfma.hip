@@ -113,7 +113,12 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
     r0 = a.off[b];
     n = a.off[b + 1] - r0;
     const int nt = (n + kBM - 1) / kBM;
-    if (tile < nt) break;
+    if (tile < nt) {
+      // Causal attention: a sequence's late query tiles walk the most key tiles.  They are given the low block
+      // ids of the sequence, so that the blocks dispatched last -- the tail of the launch -- are short ones.
+      tile = nt - 1 - tile;
+      break;
+    }
     tile -= nt;
   }
   (void)tiles_cap;
