@@ -1,16 +1,18 @@
 // Matrix-core causal attention over the reduced prefill set (Eq. 1 of the paper applied to S^{P*}), bfloat16.
 //
 // One block serves (sequence, head, tile of NWQ*32 compacted query rows); each of its NWQ waves owns 32
-// queries and walks the key tiles (32 keys) up to its diagonal.  K and V tiles are staged through LDS once
-// per block (next tile prefetched into registers while the current one is used).
+// queries and walks the key tiles (32 keys) up to its diagonal.  K and V tiles go from global memory straight
+// into a ring of three LDS buffers (asynchronous loads, two tiles ahead of the one in use; one block barrier
+// per tile).
 //
 // The score tile is computed TRANSPOSED, S^T = K Q^T (keys down the rows, queries across the columns) with
 // v_mfma_f32_32x32x16_bf16.  In the result layout a lane then holds 16 keys of ONE query (its partner lane
 // l^32 holds the other 16), so the online-softmax maximum and sum are register reductions plus a single
 // cross-lane step, and the probabilities are already laid out as the B operand of the second product
-// O^T = V^T P^T: they are split in place into two bfloat16 operands (16 significant bits) and never leave registers.  The contraction order of
-// that second product is chosen to match the order in which S^T leaves the keys in a lane; V is stored
-// transposed in LDS ([dim][key]) so that the matching A fragments are two 8-byte reads.
+// O^T = V^T P^T: they are split in place into two bfloat16 operands (16 significant bits) and never leave
+// registers.  The contraction order of that second product is chosen to match the order in which S^T leaves
+// the keys in a lane; V stays row-major ([key][dim]) in LDS and the matching A fragments (four consecutive keys
+// of one dim per lane) come from the transposing LDS read of this target.
 #include "attend.h"
 #include "prefill_args.h"
 
@@ -22,104 +24,257 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // native vector: always promoted to registers
 
-constexpr int kBN = 32;         // keys per tile
-constexpr int kVPad = kBN + 4;  // V^T row (keys) padded: conflict-free 8-byte fragment reads
+constexpr int kBN = 32;  // keys per tile
+#define DLLAVA_LDS __attribute__((address_space(3)))
+#define DLLAVA_GLB __attribute__((address_space(1)))
 
-// Staging registers are named scalars (not arrays) so that they are certain to live in VGPRs.
-template <int N>
-struct Stage {
-  u32x4 k0, k1, k2, k3, k4, k5, k6, k7;
-  u32x4 v0, v1, v2, v3, v4, v5, v6, v7;
-};
-#define DLLAVA_FOR_STAGE(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7)
+// Tile staging.  K and V rows of a key tile go from global memory straight into LDS (no registers in between):
+// a wave-wide 16-byte load deposits its 64 pieces at consecutive LDS addresses, i.e. 1 KiB = 64/(DH/8) whole rows,
+// so a tile is row-major without padding and bank conflicts are avoided by permuting the 16-byte chunks of a row
+// on the way in (the lane that fills physical chunk pc of tile row rr fetches logical chunk pc ^ f(rr)):
+//   K: f(rr) = rr mod chunks-per-row.  The 16 lanes that read one logical chunk of 16 different rows hit 16 different bank groups.
+//   V: f(rr) = 4*(rr mod chunks/4).   V is read with the transposing LDS load (4 keys x 16 dims per 16 lanes); the
+//      4 keys of such a read then lie in 4 different 64-byte bank groups.
+// Rows past the last needed key repeat it (lim = last_key - t*kBN): the causal test masks them, but they must
+// hold finite data, which unwritten page slots need not.
+template <int DH, int NWQ>
+struct Dma {
+  static constexpr int kChunks = DH / 8;            // 16-byte chunks per row
+  static constexpr int kRowsPerLoad = kWave / kChunks;
+  static constexpr int kLoads = kBN / (kRowsPerLoad * NWQ);  // wave-wide loads per wave per tile, for K and again for V
+  static_assert(kLoads >= 1 && kLoads * kRowsPerLoad * NWQ == kBN, "tile does not divide among the waves");
 
-// global -> registers: rows of K and V for key tile t (rows past last_key repeat it; the causal test masks them).
-// PAGED: K/V come from the cache pages.  A tile of 32 keys lies in two pages whose ids are the same for the whole
-// block, so they arrive as two scalar loads per tile (pg_lo for keys < 16 of the tile, pg_hi for the rest) and the
-// 16-byte loads themselves are straight-line; a page-table lookup per load would put a dependent round trip, and a
-// branch, in front of every one of them.
-template <int DH, int N, int THREADS, bool PAGED>
-__device__ __forceinline__ void stage_load(Stage<N>& st, const PrefillArgs& a, int t, int r0, int h, int last_key,
-                                           int sr, int sc, int pg_lo, int pg_hi) {
-  constexpr int kRowStep = THREADS / (DH / 8);
-  const int H = a.H;
-  const size_t tl = static_cast<size_t>(kPage) * DH;
-#define DLLAVA_LD(i)                                                                              \
-  if constexpr (i < N) {                                                                          \
-    int key = t * kBN + sr + kRowStep * i;                                                        \
-    if (key > last_key) key = last_key;                                                           \
-    if constexpr (PAGED) {                                                                        \
-      const int pg = (key - t * kBN) < kPage ? pg_lo : pg_hi;                                     \
-      const size_t o = ((static_cast<size_t>(pg) * 2) * H + h) * tl +                             \
-                       static_cast<size_t>(key % kPage) * DH + sc * 8;                            \
-      const bf16_t* base = static_cast<const bf16_t*>(a.pages) + o;                               \
-      st.k##i = *reinterpret_cast<const u32x4*>(base);                                            \
-      st.v##i = *reinterpret_cast<const u32x4*>(base + static_cast<size_t>(H) * tl);              \
-    } else {                                                                                      \
-      const size_t o = (static_cast<size_t>(r0 + key) * H + h) * DH + sc * 8;                     \
-      st.k##i = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(a.K) + o);             \
-      st.v##i = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(a.V) + o);             \
-    }                                                                                             \
+  // paged: lo/hi = this head's K rows of the two pages of the tile, V rows v_off elements further
+  static __device__ __forceinline__ void paged(bf16_t* sK, bf16_t* sV, const bf16_t* lo, const bf16_t* hi, uint32_t v_off,
+                                               int lim, int wq, int lane) {
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+      const int slab = wq + NWQ * i;  // which 1 KiB of the tile
+      const int rr = kRowsPerLoad * slab + lane / kChunks, pc = lane % kChunks;
+      const int row = rr < lim ? rr : lim;
+      const bf16_t* src = (row < kPage ? lo : hi) + (row % kPage) * DH;
+      __builtin_amdgcn_global_load_lds((const DLLAVA_GLB void*)(src + 8 * (pc ^ (rr % kChunks))),
+                                       (DLLAVA_LDS void*)(sK + slab * (kWave * 8)), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const DLLAVA_GLB void*)(src + v_off + 8 * (pc ^ (4 * (rr % (kChunks / 4))))),
+                                       (DLLAVA_LDS void*)(sV + slab * (kWave * 8)), 16, 0, 0);
+    }
   }
-  DLLAVA_FOR_STAGE(DLLAVA_LD)
-#undef DLLAVA_LD
+  // plain rows: gk / gv = row 0 of the tile for this head, consecutive rows row_stride elements apart
+  static __device__ __forceinline__ void rows(bf16_t* sK, bf16_t* sV, const bf16_t* gk, const bf16_t* gv,
+                                              uint32_t row_stride, int lim, int wq, int lane) {
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+      const int slab = wq + NWQ * i;
+      const int rr = kRowsPerLoad * slab + lane / kChunks, pc = lane % kChunks;
+      const int row = rr < lim ? rr : lim;
+      const uint32_t o = static_cast<uint32_t>(row) * row_stride;
+      __builtin_amdgcn_global_load_lds((const DLLAVA_GLB void*)(gk + o + 8 * (pc ^ (rr % kChunks))),
+                                       (DLLAVA_LDS void*)(sK + slab * (kWave * 8)), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const DLLAVA_GLB void*)(gv + o + 8 * (pc ^ (4 * (rr % (kChunks / 4))))),
+                                       (DLLAVA_LDS void*)(sV + slab * (kWave * 8)), 16, 0, 0);
+    }
+  }
+};
+
+// The running maximum is only a reference point of the exponentials: any value within a few powers of two of the
+// true maximum serves.  The accumulators are rescaled only when some query's tile maximum exceeds its reference by
+// more than this many powers of two (probabilities then stay below 2^kSlack; their bfloat16 split is relative, so
+// nothing is lost), which after the first tile of a sequence is rare: the 64 multiplications of the output
+// accumulator leave the common path.
+constexpr float kSlack = 8.f;
+
+// LDS reads of the tiles are written as instructions: the compiler would otherwise order every LDS read after ALL
+// outstanding asynchronous fills (it cannot tell the buffers apart) and so wait for the tiles just requested.
+// The reads return in order; lds_wait() is the point after which all of them have arrived.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x4 lds_read16(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_read8_tr16(uint32_t addr) {
+  u32x2 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
 }
 
-// registers -> LDS: K rows as they are, V transposed to [dim][key]
-template <int DH, int N, int THREADS>
-__device__ __forceinline__ void stage_store(const Stage<N>& st, bf16_t* sK, bf16_t* sVt, int sr, int sc) {
-  constexpr int kRowStep = THREADS / (DH / 8);
-  constexpr int kKLd = DH + 8;
-#define DLLAVA_ST(i)                                                                              \
-  if constexpr (i < N) {                                                                          \
-    const int row = sr + kRowStep * i;                                                            \
-    *reinterpret_cast<u32x4*>(sK + row * kKLd + sc * 8) = st.k##i;                                \
-    /* dims 8*sc + 0..7 of key `row`; the key position is XORed with 8*(dim/32) so that the 16 chunks */ \
-    /* of a key row, whose V^T rows are 8*kVPad elements apart, do not fall on four banks only       */ \
-    bf16_t* vt = sVt + (sc * 8) * kVPad + (row ^ (8 * (sc >> 2)));                                \
-    const u32x4 v = st.v##i;                                                                      \
-    vt[0 * kVPad] = static_cast<bf16_t>(v.x & 0xffffu);                                           \
-    vt[1 * kVPad] = static_cast<bf16_t>(v.x >> 16);                                               \
-    vt[2 * kVPad] = static_cast<bf16_t>(v.y & 0xffffu);                                           \
-    vt[3 * kVPad] = static_cast<bf16_t>(v.y >> 16);                                               \
-    vt[4 * kVPad] = static_cast<bf16_t>(v.z & 0xffffu);                                           \
-    vt[5 * kVPad] = static_cast<bf16_t>(v.z >> 16);                                               \
-    vt[6 * kVPad] = static_cast<bf16_t>(v.w & 0xffffu);                                           \
-    vt[7 * kVPad] = static_cast<bf16_t>(v.w >> 16);                                               \
+// One key tile for one wave.  diag: the tile reaches above the diagonal of some query of the wave.
+// kb / vb: LDS byte addresses of this lane's first K and V fragment pieces in the tile (see the kernel).
+template <int DH>
+__device__ __forceinline__ void tile_step(uint32_t kb, uint32_t vb_in, const uint4 (&qf)[DH / 16],
+                                          f32x16 (&o_acc)[DH / 32], float& m_ref, float& l_run, float scale_log2,
+                                          int j0, int qi, int g, bool diag) {
+  constexpr int kDB = DH / 32;
+  constexpr int kRowBytes = DH * 2;
+  uint32_t vb = vb_in;
+  // S^T = K Q^T : rows = keys j0..j0+31, columns = queries
+  u32x4 kf[DH / 16];
+#pragma unroll
+  for (int ks = 0; ks < DH / 16; ++ks) kf[ks] = lds_read16(kb ^ (ks * 32));
+  // The fragments pass through the waiting statement, so that nothing that uses them can be scheduled ahead of it.
+  static_assert(DH == 128 || DH == 64, "fragment lists below are written out for these head sizes");
+  if constexpr (DH == 128)
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]), "+v"(kf[7])
+                 :
+                 : "memory");
+  else
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3])
+                 :
+                 : "memory");
+  f32x16 s;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < DH / 16; ++ks) {
+    union { u32x4 u; bf16x8 f; } ka;
+    union { uint4 u; bf16x8 f; } qb;
+    ka.u = kf[ks];
+    qb.u = qf[ks];
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.f, qb.f, s, 0, 0, 0);
   }
-  DLLAVA_FOR_STAGE(DLLAVA_ST)
-#undef DLLAVA_ST
+  // V^T fragments: slot e of lane group g <-> the key held in s[8*half + e], i.e. keys 16*half + 8*u + 4*g + 0..3
+  // for u = e/4: one transposing read each.  Requested once the
+  // K fragments are used up (the address passes through a statement that reads the scores), they arrive while the
+  // softmax runs.
+  u32x2 vf[kDB][2][2];
+  asm volatile("" : "+v"(vb) : "v"(s[0]));
+#pragma unroll
+  for (int nb = 0; nb < kDB; ++nb) {
+    const uint32_t va = vb ^ (nb * 64);
+    vf[nb][0][0] = lds_read8_tr16<0 * kRowBytes>(va);
+    vf[nb][0][1] = lds_read8_tr16<8 * kRowBytes>(va);
+    vf[nb][1][0] = lds_read8_tr16<16 * kRowBytes>(va);
+    vf[nb][1][1] = lds_read8_tr16<24 * kRowBytes>(va);
+  }
+  // lane holds keys j0 + 8*(r/4) + 4*g + r%4 of query qi
+  if (diag) {  // wave-uniform; kept a branch (not sixteen selects on every tile) by the empty statement
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = j0 + 8 * (r >> 2) + 4 * g + (r & 3);
+      if (key > qi) s[r] = -INFINITY;
+    }
+  }
+  float tmax = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[r]);
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+  const float m_t = tmax * scale_log2;  // scale > 0: the maximum of the scaled scores; finite (key j0 <= qi is never masked)
+  if (__any(m_t > m_ref + kSlack)) {
+    const float m_new = fmaxf(m_ref, m_t);
+    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+    m_ref = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int nb = 0; nb < kDB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o_acc[nb][r] *= alpha;
+  }
+  // probabilities as TWO bfloat16 operands, p = p_hi + p_lo with p_hi the top 16 bits of p and p_lo the
+  // top 16 bits of the (exact) remainder: 16 significant bits in all, so the second product is as accurate
+  // as the float32 accumulation around it instead of carrying 2^-9 relative rounding on every weight
+  float psum = 0.f;
+  uint32_t pk_hi[8], pk_lo[8];
+#pragma unroll
+  for (int r = 0; r < 16; r += 2) {
+    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -m_ref));
+    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], scale_log2, -m_ref));
+    psum += p0 + p1;
+    const uint32_t b0 = __float_as_uint(p0), b1 = __float_as_uint(p1);
+    pk_hi[r >> 1] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);  // {hi16(p0), hi16(p1)}
+    const float r0 = p0 - __uint_as_float(b0 & 0xffff0000u);
+    const float r1 = p1 - __uint_as_float(b1 & 0xffff0000u);
+    pk_lo[r >> 1] = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
+  }
+  l_run += psum;
+
+  // O^T += V^T P^T, two contraction steps of 16 keys
+#pragma unroll
+  for (int nb = 0; nb < kDB; ++nb)  // as above: all reads have arrived, and the V fragments are used after this point only
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(vf[nb][0][0]), "+v"(vf[nb][0][1]), "+v"(vf[nb][1][0]), "+v"(vf[nb][1][1])
+                 :
+                 : "memory");
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    union { uint32_t u[4]; bf16x8 f; } pb_hi, pb_lo;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      pb_hi.u[e] = pk_hi[4 * half + e];
+      pb_lo.u[e] = pk_lo[4 * half + e];
+    }
+#pragma unroll
+    for (int nb = 0; nb < kDB; ++nb) {
+      union { u32x2 h[2]; bf16x8 f; } va;
+      va.h[0] = vf[nb][half][0];
+      va.h[1] = vf[nb][half][1];
+      o_acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.f, pb_hi.f, o_acc[nb], 0, 0, 0);
+      o_acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.f, pb_lo.f, o_acc[nb], 0, 0, 0);
+    }
+  }
 }
 
 template <int DH, int NWQ>
 __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_kernel(PrefillArgs a, int tiles_cap) {
-  constexpr int kThreads = NWQ * kWave;
   constexpr int kBM = NWQ * 32;
-  constexpr int kKLd = DH + 8;           // K tile row (elements), padded: conflict-free 16-byte fragment reads
-  constexpr int kChunks = DH / 8;        // 16-byte chunks per row
-  constexpr int kLoads = kBN * kChunks / kThreads;  // staging loads per thread per tile (K, and again V)
-  constexpr int kDB = DH / 32;           // 32-dim blocks of the output
-  static_assert(kLoads >= 1 && kLoads <= 8 && kLoads * kThreads == kBN * kChunks, "tile does not divide among the threads");
+  constexpr int kChunks = DH / 8;  // 16-byte chunks per row
+  constexpr int kDB = DH / 32;     // 32-dim blocks of the output
+  constexpr int kRowBytes = DH * 2;
+  constexpr int kTileElems = kBN * DH;
+  constexpr int kStages = 3;
+  using D = Dma<DH, NWQ>;
 
-  __shared__ __align__(16) bf16_t sK[kBN * kKLd];
-  __shared__ __align__(16) bf16_t sVt[DH * kVPad];
+  // a ring of three K tiles and three V tiles: tile t+2 is requested while tile t is used
+  __shared__ __align__(1024) bf16_t sK[kStages * kTileElems];
+  __shared__ __align__(1024) bf16_t sV[kStages * kTileElems];
 
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wq = tid / kWave;
-  const int h = blockIdx.y, H = a.H;
-  // which (sequence, query tile) is this block?  tiles are numbered sequence by sequence
-  int b = 0, tile = blockIdx.x, n = 0, r0 = 0;
-  for (;; ++b) {
-    if (b >= a.B) return;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wq = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int h = blockIdx.x, H = a.H;
+  // Which (sequence, query tile) is this block?  Causal attention: query tile i of a sequence walks i+1 key-tile
+  // groups, so the work of a block grows with its tile index.  Blocks are therefore numbered by DESCENDING tile
+  // index over all sequences (all heads of a tile adjacent): the launch starts with the longest blocks and its tail
+  // consists of the shortest ones.  (The heads being the fast dimension also puts all query tiles of one
+  // (sequence, head) pair, which read the same K/V, on the same XCD when H is a multiple of 8.)
+  // Every wave works the numbering out for itself: lane = sequence, counting with ballots.
+  int b = 0, tile = 0, n = 0, r0 = 0;
+  if (a.B <= kWave) {
+    const int nb_l = lane < a.B ? (a.off[lane + 1] - a.off[lane] + kBM - 1) / kBM : 0;  // tiles of sequence `lane`
+    int total = 0, cnt = 0;
+    for (int i = 0; (cnt = __builtin_popcountll(__ballot(nb_l > i))) != 0; ++i) total += cnt;
+    const int y = total - 1 - static_cast<int>(blockIdx.y);  // position in ASCENDING tile-index order
+    if (y < 0) return;                                       // beyond the last tile
+    int below = 0;  // tiles with a smaller index
+    for (tile = 0;; ++tile) {
+      cnt = __builtin_popcountll(__ballot(nb_l > tile));
+      if (below + cnt > y) break;
+      below += cnt;
+    }
+    // the (y - below)-th sequence, in ascending order, that has a tile of this index
+    const unsigned long long has = __ballot(nb_l > tile);
+    const int before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(has >> 32),
+                                                 __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(has), 0));
+    const unsigned long long me = __ballot(nb_l > tile && before == y - below);
+    b = __builtin_ctzll(me);
     r0 = a.off[b];
     n = a.off[b + 1] - r0;
-    const int nt = (n + kBM - 1) / kBM;
-    if (tile < nt) {
-      // Causal attention: a sequence's late query tiles walk the most key tiles.  They are given the low block
-      // ids of the sequence, so that the blocks dispatched last -- the tail of the launch -- are short ones.
-      tile = nt - 1 - tile;
-      break;
+  } else {
+    // many sequences: numbered sequence by sequence, the late (long) tiles of each first
+    tile = blockIdx.y;
+    for (;; ++b) {
+      if (b >= a.B) return;
+      r0 = a.off[b];
+      n = a.off[b + 1] - r0;
+      const int nt = (n + kBM - 1) / kBM;
+      if (tile < nt) {
+        tile = nt - 1 - tile;
+        break;
+      }
+      tile -= nt;
     }
-    tile -= nt;
   }
   (void)tiles_cap;
   const int i0 = tile * kBM;            // first query row of the block (sequence-relative)
@@ -143,114 +298,86 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
   for (int nb = 0; nb < kDB; ++nb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o_acc[nb][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_ref = -INFINITY, l_run = 0.f;
 
   const int last_key = (i0 + kBM < n ? i0 + kBM : n) - 1;  // keys 0..last_key are needed by this block
   const int n_tiles = last_key / kBN + 1;
 
-  // staging: thread -> (key row sr + (kThreads/kChunks)*i, chunk sc)
-  const int sc = tid % kChunks, sr = tid / kChunks;
-  Stage<kLoads> stg;
+  // Fragment addresses (LDS bytes, stage 0).  K: row lq, logical chunk 2*ks + g, stored at chunk ^ (lq mod chunks):
+  // the step ks enters as an exclusive-or with 32*ks.  V: the transposing read of 16 lanes (j = lane mod 16) returns
+  // to lane j four keys of dim j; lane j points at key j/4, dims 4*(j mod 4)..+3 of the 16 dims of its group.
+  const uint32_t kb0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((DLLAVA_LDS bf16_t*)sK)) + lq * kRowBytes +
+                       (((lq % kChunks) & ~1) * 16) + ((g ^ (lq & 1)) * 16);
+  const int j = lane & 15, lqh = (lane >> 4) & 1;
+  const uint32_t vb0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((DLLAVA_LDS bf16_t*)sV)) +
+                       (4 * g + (j >> 2)) * kRowBytes + ((j >> 2) % (kChunks / 4)) * 64 + lqh * 32 + (j & 3) * 8;
+
   const bool paged = a.K == nullptr;  // block-uniform
   const int32_t* bt = a.block_table + static_cast<size_t>(b) * a.max_pages;
   const int last_page = last_key / kPage;
-  // page ids of tile t: block-uniform indices, so these are scalar loads
-#define STAGE_LOAD(t)                                                                                      \
-  {                                                                                                        \
-    if (paged) {                                                                                           \
-      const int p_lo = 2 * (t), p_hi = 2 * (t) + 1 < last_page ? 2 * (t) + 1 : last_page;                  \
-      stage_load<DH, kLoads, kThreads, true>(stg, a, (t), r0, h, last_key, sr, sc, bt[p_lo], bt[p_hi]);    \
-    } else {                                                                                               \
-      stage_load<DH, kLoads, kThreads, false>(stg, a, (t), r0, h, last_key, sr, sc, 0, 0);                 \
-    }                                                                                                      \
+  const size_t tl = static_cast<size_t>(kPage) * DH;           // one head's K (or V) rows of a page
+  const uint32_t v_off = static_cast<uint32_t>(H * tl);        // from a page's K block to its V block
+  const uint32_t row_stride = static_cast<uint32_t>(H) * DH;   // between consecutive rows of K / V
+  // page ids of a tile: block-uniform indices, so these are scalar loads; fetched one step before they are used
+  int pg_lo = 0, pg_hi = 0;
+#define PAGE_IDS(t)                                                                    \
+  if (paged) {                                                                         \
+    const int p_lo = 2 * (t) < last_page ? 2 * (t) : last_page;                        \
+    const int p_hi = 2 * (t) + 1 < last_page ? 2 * (t) + 1 : last_page;                \
+    pg_lo = bt[p_lo];                                                                  \
+    pg_hi = bt[p_hi];                                                                  \
   }
-#define STAGE_STORE() stage_store<DH, kLoads, kThreads>(stg, sK, sVt, sr, sc)
+#define ISSUE(t, stage)                                                                                        \
+  {                                                                                                            \
+    const int lim = last_key - (t) * kBN;                                                                      \
+    bf16_t* dk = sK + (stage) * kTileElems;                                                                    \
+    bf16_t* dv = sV + (stage) * kTileElems;                                                                    \
+    if (paged) {                                                                                               \
+      const bf16_t* pages = static_cast<const bf16_t*>(a.pages);                                               \
+      D::paged(dk, dv, pages + (static_cast<size_t>(pg_lo) * 2 * H + h) * tl,                                  \
+               pages + (static_cast<size_t>(pg_hi) * 2 * H + h) * tl, v_off, lim, wq, lane);                   \
+    } else {                                                                                                   \
+      const size_t o = (static_cast<size_t>(r0 + (t) * kBN) * H + h) * DH;                                     \
+      D::rows(dk, dv, static_cast<const bf16_t*>(a.K) + o, static_cast<const bf16_t*>(a.V) + o, row_stride,    \
+              lim, wq, lane);                                                                                  \
+    }                                                                                                          \
+  }
 
-  STAGE_LOAD(0);
+  PAGE_IDS(0);
+  ISSUE(0, 0);
+  if (n_tiles > 1) {
+    PAGE_IDS(1);
+    ISSUE(1, 1);
+  }
+  PAGE_IDS(2);
+  // the query fragments have arrived before the loop starts (the tiles requested after them may still be on their way)
+#pragma unroll
+  for (int ks = 0; ks < DH / 16; ++ks) asm volatile("" ::"v"(qf[ks].x), "v"(qf[ks].y), "v"(qf[ks].z), "v"(qf[ks].w));
+
+  int cur = 0;  // stage of tile t
   for (int t = 0; t < n_tiles; ++t) {
-    __syncthreads();  // the previous tile has been consumed
-    STAGE_STORE();
-    __syncthreads();
-    if (t + 1 < n_tiles) STAGE_LOAD(t + 1);
-
+    // This wave's own loads of tile t are waited for (those of tile t+1, issued later, may stay in flight), then
+    // the barrier makes every wave's part of the tile visible and says that all waves have left tile t-1.
+    if (t + 1 < n_tiles)
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * D::kLoads) : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    const int prv = cur == 0 ? kStages - 1 : cur - 1;  // the stage tile t-1 used: free now, tile t+2 goes there
+    if (t + 2 < n_tiles) {
+      ISSUE(t + 2, prv);
+      PAGE_IDS(t + 3);
+    }
     const int j0 = t * kBN;
-    if (j0 > iw + 31) continue;  // tile lies entirely above this wave's diagonal (wave-uniform)
-
-    // S^T = K Q^T : rows = keys j0..j0+31, columns = queries
-    f32x16 s;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < DH / 16; ++ks) {
-      const uint4 kf = *reinterpret_cast<const uint4*>(sK + lq * kKLd + 16 * ks + 8 * g);
-      union { uint4 u; bf16x8 f; } ka, qb;
-      ka.u = kf;
-      qb.u = qf[ks];
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.f, qb.f, s, 0, 0, 0);
+    if (j0 <= iw + 31) {  // else the tile lies entirely above this wave's diagonal (wave-uniform)
+      const uint32_t kb = kb0 + cur * (kTileElems * 2), vb = vb0 + cur * (kTileElems * 2);
+      // diag: some key of the tile may exceed some query of the wave
+      tile_step<DH>(kb, vb, qf, o_acc, m_ref, l_run, a.scale_log2, j0, qi, g, j0 + kBN - 1 > iw);
     }
-    // lane holds keys j0 + 8*(r/4) + 4*g + r%4 of query qi
-    const bool diag = j0 + kBN - 1 > iw;  // some key of the tile may exceed some query of the wave
-    float tmax = -INFINITY;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float v = s[r] * a.scale_log2;
-      if (diag) {
-        const int key = j0 + 8 * (r >> 2) + 4 * g + (r & 3);
-        if (key > qi) v = -INFINITY;
-      }
-      s[r] = v;
-      tmax = fmaxf(tmax, v);
-    }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-    const float m_new = fmaxf(m_run, tmax);  // finite: key j0 <= iw <= qi is never masked in a visited tile
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    // probabilities as TWO bfloat16 operands, p = p_hi + p_lo with p_hi the top 16 bits of p and p_lo the
-    // top 16 bits of the (exact) remainder: 16 significant bits in all, so the second product is as accurate
-    // as the float32 accumulation around it instead of carrying 2^-9 relative rounding on every weight
-    float psum = 0.f;
-    uint32_t pk_hi[8], pk_lo[8];
-#pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(s[r] - m_new);
-      const float p1 = __builtin_amdgcn_exp2f(s[r + 1] - m_new);
-      psum += p0 + p1;
-      const uint32_t b0 = __float_as_uint(p0), b1 = __float_as_uint(p1);
-      pk_hi[r >> 1] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);  // {hi16(p0), hi16(p1)}
-      const float r0 = p0 - __uint_as_float(b0 & 0xffff0000u);
-      const float r1 = p1 - __uint_as_float(b1 & 0xffff0000u);
-      pk_lo[r >> 1] = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
-    }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int nb = 0; nb < kDB; ++nb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o_acc[nb][r] *= alpha;
-
-    // O^T += V^T P^T, two contraction steps of 16 keys; slot e of lane group g <-> the key held in s[8*half + e]
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      union { uint32_t u[4]; bf16x8 f; } pb_hi, pb_lo;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        pb_hi.u[e] = pk_hi[4 * half + e];
-        pb_lo.u[e] = pk_lo[4 * half + e];
-      }
-#pragma unroll
-      for (int nb = 0; nb < kDB; ++nb) {
-        // key positions are XORed with 8*nb in this block of 32 dims (see stage_store)
-        const bf16_t* vrow = sVt + (nb * 32 + lq) * kVPad + 4 * g;
-        union { uint2 u[2]; bf16x8 f; } va;
-        va.u[0] = *reinterpret_cast<const uint2*>(vrow + ((16 * half) ^ (8 * nb)));      // keys 16*half + 4g + 0..3
-        va.u[1] = *reinterpret_cast<const uint2*>(vrow + ((16 * half + 8) ^ (8 * nb)));  // keys 16*half + 8 + 4g + 0..3
-        o_acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.f, pb_hi.f, o_acc[nb], 0, 0, 0);
-        o_acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.f, pb_lo.f, o_acc[nb], 0, 0, 0);
-      }
-    }
+    cur = cur == kStages - 1 ? 0 : cur + 1;
   }
-
-#undef STAGE_LOAD
-#undef STAGE_STORE
+#undef ISSUE
+#undef PAGE_IDS
 
   // l is split between the two lanes of a query
   l_run += __shfl_xor(l_run, 32, kWave);
@@ -273,7 +400,8 @@ int launch(const PrefillArgs& a, int64_t rows, hipStream_t st) {
   constexpr int kBM = NWQ * 32;
   const int64_t tiles = ceil_div(rows, kBM) + a.B;  // upper bound on sum_b ceil(n_b / kBM)
   if (tiles > 0x7fffffffLL) return 1;
-  dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(a.H));
+  if (tiles > 65535) return 1;
+  dim3 grid(static_cast<unsigned>(a.H), static_cast<unsigned>(tiles));
   hipLaunchKernelGGL((prefill_mfma_kernel<DH, NWQ>), grid, dim3(NWQ * kWave), 0, st, a, static_cast<int>(tiles));
   DLLAVA_CHECK_LAUNCH("prefill_mfma_kernel");
   return DLLAVA_OK;

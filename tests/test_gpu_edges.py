@@ -135,6 +135,34 @@ def test_prefill_tile_widths(waves, from_cache, monkeypatch):
     _assert_out_close(h.as_f64(O), ref, w.dtype, f"prefill {waves} waves")
 
 
+@pytest.mark.parametrize("B,Dh,lens", [
+    (7, 128, [300, 1, 129, 0, 257, 40, 128]),      # ragged, an empty sequence in the middle: block numbering by tile index
+    (70, 128, None),                                # more sequences than lanes of a wave: numbering sequence by sequence
+    (5, 64, [130, 33, 0, 64, 97]),                  # the smaller head size
+])
+@pytest.mark.parametrize("from_cache", [False, True])
+def test_prefill_block_numbering(B, Dh, lens, from_cache):
+    """Blocks of the matrix-core prefill kernel are numbered by descending query-tile index over all sequences
+    (each wave works out which (sequence, tile) it serves): every row of every sequence must still be produced
+    exactly once, whatever the mix of lengths."""
+    h = _H()
+    if lens is None:
+        lens = [1 + (37 * i) % 90 for i in range(B)]
+    w = W.make("numbering", "bf16", 256, 2, Dh, B, 0, lens, 0, 1.0, 0)
+    pre = W.prefill_inputs(w)
+    g = h.GpuPath(w, pre, None)
+    D = rng.normal(w.seed, "w.D", (int(sum(w.n_vis)), 2)).astype(np.float32)
+    out = g.select_compact(torch.from_numpy(D).to(h.DEV), with_hidden=False)
+    off = np.asarray(w.seq_off, np.int32)
+    ref = R.prefill_attn(pre["Q"], pre["K"], pre["V"], off, g.scale, w.dtype)
+    Qc = out["Q_out"].contiguous()
+    if from_cache:
+        O = g.prefill(Qc, out["out_off"])
+    else:
+        O = g.prefill(Qc, out["out_off"], g.pre["K"], g.pre["V"])
+    _assert_out_close(h.as_f64(O), ref, w.dtype, f"prefill numbering B={B} Dh={Dh}")
+
+
 def test_results_are_bit_reproducible():
     """Every reduction runs in a fixed order (or in integer arithmetic): repeating a call must not change a bit."""
     h = _H()
