@@ -242,7 +242,8 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
   // Every wave works the numbering out for itself: lane = sequence, counting with ballots.
   int b = 0, tile = 0, n = 0, r0 = 0;
   if (a.B <= kWave) {
-    const int nb_l = lane < a.B ? (a.off[lane + 1] - a.off[lane] + kBM - 1) / kBM : 0;  // tiles of sequence `lane`
+    const int off_l = lane < a.B ? a.off[lane] : 0, end_l = lane < a.B ? a.off[lane + 1] : 0;
+    const int nb_l = (end_l - off_l + kBM - 1) / kBM;  // tiles of sequence `lane`
     int total = 0, cnt = 0;
     for (int i = 0; (cnt = __builtin_popcountll(__ballot(nb_l > i))) != 0; ++i) total += cnt;
     const int y = total - 1 - static_cast<int>(blockIdx.y);  // position in ASCENDING tile-index order
@@ -259,8 +260,8 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
                                                  __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(has), 0));
     const unsigned long long me = __ballot(nb_l > tile && before == y - below);
     b = __builtin_ctzll(me);
-    r0 = a.off[b];
-    n = a.off[b + 1] - r0;
+    r0 = __builtin_amdgcn_readlane(off_l, b);  // no second trip to memory for the offsets
+    n = __builtin_amdgcn_readlane(end_l, b) - r0;
   } else {
     // many sequences: numbered sequence by sequence, the late (long) tiles of each first
     tile = blockIdx.y;
@@ -369,7 +370,7 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
       PAGE_IDS(t + 3);
     }
     const int j0 = t * kBN;
-    if (j0 <= iw + 31) {  // else the tile lies entirely above this wave's diagonal (wave-uniform)
+    if (j0 <= iw + 31 && iw < n) {  // else the tile lies entirely above this wave's diagonal, or the wave has no query (wave-uniform)
       const uint32_t kb = kb0 + cur * (kTileElems * 2), vb = vb0 + cur * (kTileElems * 2);
       // diag: some key of the tile may exceed some query of the wave
       tile_step<DH>(kb, vb, qf, o_acc, m_ref, l_run, a.scale_log2, j0, qi, g, j0 + kBN - 1 > iw);
@@ -413,9 +414,9 @@ int launch(const PrefillArgs& a, int64_t rows, hipStream_t st) {
 int prefill_mfma_launch(const PrefillArgs& a, int64_t rows, int Dh, hipStream_t st) {
   if (a.H > 65535) return 1;
   // wide tiles (K/V tiles staged once for 128 queries) unless there is too little work to spread over the chip;
-  // measured: 4 waves win from the 7B batch-1 prefill (214 rows x 32 heads) upwards
+  // measured: 2 waves win for the 7B batch-1 prefill (214 rows x 32 heads), 4 waves from batch 2 upwards
   const int64_t work = rows * a.H;  // query rows x heads
-  int nwq = work >= 4 * 1024 ? 4 : (work >= 1024 ? 2 : 1);
+  int nwq = work >= 8 * 1024 ? 4 : (work >= 1024 ? 2 : 1);
   if (const char* e = getenv("DLLAVA_PREFILL_WAVES")) {  // tuning override
     const int v = atoi(e);
     if (v == 1 || v == 2 || v == 4) nwq = v;
