@@ -26,10 +26,15 @@ Conventions
   * Paged cache layout: pages[n_pages][2 (K,V)][H][page_size][Dh]; token t of
     sequence b lives in page block_table[b, t // page_size], slot t % page_size.
 
+  * Projection of the reduced set (Eq. 3, first line, applied to S^{P*}): Q, K, V
+    of the kept rows only; queries and keys optionally rotated by the ORIGINAL
+    position of each kept token (rotary embedding of the LLaMA decoder).
+
 Parity unpinned (fixed by the benchmark definition, nothing in the paper can
 confirm them): the two-layer predictor shape and its GELU variant, ranking by
 the raw keep logit rather than the margin, the tie-break direction, the
-threshold value and the weight initialisation.
+threshold value and the weight initialisation; the rotary convention, its base
+and the use of original positions (the paper does not mention positions).
 """
 from __future__ import annotations
 
@@ -52,6 +57,22 @@ def widen(a: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "bf16":
         bits = np.asarray(a, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
         return bits.view(np.float32).astype(np.float64)
+    raise ValueError(dtype)
+
+
+def narrow(a: np.ndarray, dtype: str) -> np.ndarray:
+    """float64 values -> stored form: float32, or bfloat16 bit patterns rounded to nearest even."""
+    f = np.asarray(a, dtype=np.float64).astype(np.float32)
+    if dtype == "f32":
+        return f
+    if dtype == "bf16":
+        u = np.ascontiguousarray(f).view(np.uint32)
+        r = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+        out = (r >> np.uint32(16)).astype(np.uint16)
+        nan = np.isnan(f)
+        if nan.any():
+            out = np.where(nan, np.uint16(0x7FC0), out)
+        return out
     raise ValueError(dtype)
 
 
@@ -260,6 +281,57 @@ def decode_attn_append(q, k_new, v_new, keep, cache: PagedCache, scale: float,
             cache.put(b, L, k_new[b], v_new[b])
             cache.cache_len[b] = L + 1
     return o, err
+
+
+# ----------------------------------------------------------------------------- Eq. 3 line 1 over the reduced set
+
+def rope_rotate(x: np.ndarray, pos: np.ndarray, base: float) -> np.ndarray:
+    """Rotary position embedding of x [n,H,Dh] at integer positions pos [n] (float64).
+
+    The decoder the paper sparsifies is LLaMA-style; its attention rotates queries and keys by position before the
+    dot product (RoFormer; the pairing used by LLaMA: feature i goes with feature i + Dh/2, angle
+    pos * base^(-2i/Dh)).  The paper never mentions positions (parity unpinned: the convention and the use of the
+    ORIGINAL positions of the kept tokens are this library's reading).
+    """
+    n, H, Dh = x.shape
+    half = Dh // 2
+    i = np.arange(half, dtype=np.float64)
+    ang = np.asarray(pos, dtype=np.float64)[:, None] * base ** (-2.0 * i / Dh)[None, :]      # [n, half]
+    c, s_ = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * c - hi * s_, hi * c + lo * s_], axis=-1)
+
+
+def qkv_project(x, off, pos, Wq, Wk, Wv, H: int, Dh: int, dtype: str, rope_base: Optional[float] = None,
+                cache: Optional[PagedCache] = None):
+    """Q, K, V = W^Q S, W^K S, W^V S (Eq. 3, first line) for the rows of the REDUCED set only.
+
+    x [rows,d] are the compacted hidden states S^{P*} (Eq. 5 line 3) in stored form, off [B+1] their sequence
+    offsets, pos [rows] the original sequence-relative position of every kept row (kept_idx of `select`).
+    W* are [H*Dh, d] stored.  Queries and keys are rotated (rope_rotate) when rope_base is given.
+    Returns float64 Q, K, V [rows,H,Dh]; when a cache is given, K and V are rounded to its stored form and
+    written at positions 0..n_b-1 of every sequence, and cache_len[b] = n_b.
+    """
+    xs = widen(x, dtype)
+    rows = xs.shape[0]
+    out = []
+    for W in (Wq, Wk, Wv):
+        out.append((xs @ widen(W, dtype).T).reshape(rows, H, Dh))
+    Q, K, V = out
+    if rope_base is not None:
+        Q = rope_rotate(Q, pos, rope_base)
+        K = rope_rotate(K, pos, rope_base)
+    if cache is not None:
+        Ks, Vs = narrow(K, dtype), narrow(V, dtype)
+        B = len(off) - 1
+        for b in range(B):
+            n = int(off[b + 1] - off[b])
+            if n > cache.capacity:
+                raise ValueError("cache capacity exceeded")
+            for t in range(n):
+                cache.put(b, t, Ks[off[b] + t], Vs[off[b] + t])
+            cache.cache_len[b] = n
+    return Q, K, V
 
 
 # ----------------------------------------------------------------------------- Appendix A.4.2, Eq. 13

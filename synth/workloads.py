@@ -189,6 +189,12 @@ def _qkv_from(w: Workload, x_stored_f32: np.ndarray):
     return out
 
 
+def attn_weights(w: Workload) -> Dict[str, np.ndarray]:
+    """Stored Xavier-uniform projection weights Wq, Wk, Wv [H*Dh, d] (the ones prefill_inputs / decode_inputs
+    use when the workload projects Q/K/V from the hidden states)."""
+    return {nm: store(_xavier(w.seed, f"attn.W{nm}", w.H * w.Dh, w.d), w.dtype) for nm in ("q", "k", "v")}
+
+
 def prefill_inputs(w: Workload) -> Dict[str, np.ndarray]:
     """hidden [sumN,d]; Q,K,V [sumN,H,Dh] for every prompt token (before sparsification)."""
     rows = w.sumN

@@ -353,3 +353,90 @@ def test_compact_copies_kept_rows_bit_exactly():
             assert np.array_equal(Kc[t], pre["K"][src]) and np.array_equal(Vc[t], pre["V"][src])
             j += 1
     assert j == off[-1] == len(h_out)
+
+
+# ------------------------------------------------------------------ projection of the reduced set (Eq. 3 line 1)
+
+def test_narrow_rounds_to_nearest_even_and_inverts_widen():
+    # 1 + 2^-8 lies exactly between two bfloat16 values: the even mantissa (1.0) wins; 1 + 3*2^-8 goes up to 1 + 2^-6
+    a = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 1.0 + 2.0 ** -8 + 2.0 ** -20, 0.0, -0.0])
+    got = R.widen(R.narrow(a, "bf16"), "bf16")
+    assert np.array_equal(got, np.array([1.0, 1.0 + 2.0 ** -6, -1.0, 1.0 + 2.0 ** -7, 0.0, 0.0]))
+    bits = np.arange(0, 0x7F80, 7, dtype=np.uint16)  # every 7th finite positive pattern
+    assert np.array_equal(R.narrow(R.widen(bits, "bf16"), "bf16"), bits)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_projection_vs_triple_loop(dtype):
+    rows, d, H, Dh = 5, 24, 2, 8
+    x = W.store(rng.normal(5, "x", (rows, d)).astype(np.float32), dtype)
+    Ws = [W.store(rng.normal(5, f"W{i}", (H * Dh, d)).astype(np.float32) * 0.3, dtype) for i in range(3)]
+    Q, K, V = R.qkv_project(x, np.array([0, 2, 5]), np.zeros(rows, np.int64), *Ws, H, Dh, dtype)
+    xf = [[float(v) for v in r] for r in W.stored_to_f32(x, dtype)]
+    for got, Wm in zip((Q, K, V), Ws):
+        wf = [[float(v) for v in r] for r in W.stored_to_f32(Wm, dtype)]
+        for r in range(rows):
+            for f in range(H * Dh):
+                acc = 0.0
+                for c in range(d):
+                    acc += xf[r][c] * wf[f][c]      # feature f of row r = <W[f,:], x[r,:]>
+                assert abs(got[r, f // Dh, f % Dh] - acc) <= 1e-12 * max(1.0, abs(acc))
+
+
+def test_rotary_is_a_complex_rotation_by_position():
+    """Feature pair (i, i + Dh/2) read as the complex number x_i + j x_{i+Dh/2} is multiplied by
+    exp(j pos base^(-2i/Dh)): position 0 is the identity, norms are preserved, and the product of a rotated
+    query with a rotated key depends on the difference of their positions only."""
+    n, H, Dh, base = 6, 3, 16, 10000.0
+    x = rng.normal(6, "x", (n, H, Dh)).astype(np.float64)
+    pos = np.array([0, 1, 2, 7, 100, 4095])
+    y = R.rope_rotate(x, pos, base)
+    half = Dh // 2
+    for t in range(n):
+        for i in range(half):
+            w = complex(math.cos(pos[t] * base ** (-2.0 * i / Dh)), math.sin(pos[t] * base ** (-2.0 * i / Dh)))
+            for h in range(H):
+                z = complex(x[t, h, i], x[t, h, i + half]) * w
+                assert abs(y[t, h, i] - z.real) < 1e-9 and abs(y[t, h, i + half] - z.imag) < 1e-9
+    assert np.array_equal(y[0], x[0])
+    assert np.allclose((y ** 2).sum(-1), (x ** 2).sum(-1), rtol=1e-12)
+    q, k = x[:3], x[3:]
+    d0 = np.einsum("thd,thd->th", R.rope_rotate(q, [5, 9, 40], base), R.rope_rotate(k, [2, 9, 31], base))
+    d1 = np.einsum("thd,thd->th", R.rope_rotate(q, [105, 1009, 47], base), R.rope_rotate(k, [102, 1009, 38], base))
+    assert np.allclose(d0, d1, atol=1e-9)
+    # angle of the first pair grows by one radian per position (base^0 = 1), the last pair turns slowest
+    e = np.zeros((1, 1, Dh)); e[0, 0, 0] = 1.0
+    r = R.rope_rotate(e, [1], base)
+    assert abs(r[0, 0, 0] - math.cos(1.0)) < 1e-12 and abs(r[0, 0, half] - math.sin(1.0)) < 1e-12
+
+
+def test_projecting_kept_rows_equals_compacting_the_full_projection():
+    """Row-wise operations commute with the gather of Eq. 5 line 3: projecting (and rotating by ORIGINAL
+    positions) only the kept rows gives the kept rows of the full sequence's projection; the cache then holds
+    exactly those K/V rows."""
+    w = W.make("proj", "bf16", 64, 2, 16, 3, [2, 0, 1], [9, 6, 0], [3, 2, 4], 0.4, 0, project_qkv=True)
+    pre, pred, aw = W.prefill_inputs(w), W.predictor(w), W.attn_weights(w)
+    vis = np.concatenate([np.arange(w.seq_off[b] + w.n_sys[b], w.seq_off[b] + w.n_sys[b] + w.n_vis[b])
+                          for b in range(w.B)]).astype(np.int64)
+    D = R.score(pre["hidden"][vis], pred["W1"], pred["b1"], pred["W2"], pred["b2"], w.dtype)
+    mask, idx, off = R.select(D, w.seq_off, w.vis_start, w.vis_len, R.TOPK, w.keep_ratio, 0.0)
+    total = int(off[-1])
+    h_star, _ = R.compact(idx, off, w.seq_off, hidden=pre["hidden"])
+    bt, n_pages = W.block_table(w)
+    cache = R.PagedCache(n_pages, bt, w.H, w.Dh, w.dtype)
+    Q, K, V = R.qkv_project(h_star, off, idx[:total], aw["q"], aw["k"], aw["v"], w.H, w.Dh, w.dtype, 10000.0, cache)
+    # the other way round: every row of every sequence at its own position, then the gather
+    seq_pos = np.concatenate([np.arange(w.seq_off[b + 1] - w.seq_off[b]) for b in range(w.B)])
+    Qf, Kf, Vf = R.qkv_project(pre["hidden"], w.seq_off, seq_pos, aw["q"], aw["k"], aw["v"], w.H, w.Dh, w.dtype, 10000.0)
+    src = np.concatenate([w.seq_off[b] + idx[off[b]:off[b + 1]] for b in range(w.B)])
+    assert np.array_equal(Q, Qf[src]) and np.array_equal(K, Kf[src]) and np.array_equal(V, Vf[src])
+    # without the rotation the projections are the ones the workload generator made for these hidden states
+    Q0, K0, V0 = R.qkv_project(h_star, off, idx[:total], aw["q"], aw["k"], aw["v"], w.H, w.Dh, w.dtype)
+    assert np.abs(Q0 - R.widen(pre["Q"], w.dtype)[src]).max() < 0.02 and np.abs(V0 - R.widen(pre["V"], w.dtype)[src]).max() < 0.02
+    assert np.array_equal(V0, V)
+    for b in range(w.B):
+        n = int(off[b + 1] - off[b])
+        assert cache.cache_len[b] == n
+        Kc, Vc = cache.rows(b)
+        assert np.array_equal(Kc, R.narrow(K[off[b]:off[b + 1]], w.dtype))
+        assert np.array_equal(Vc, R.narrow(V[off[b]:off[b + 1]], w.dtype))
