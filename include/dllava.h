@@ -2,12 +2,13 @@
  * dllava — token sparsification followed by attention over the reduced context
  * (Dynamic-LLaVA, arXiv 2412.00876), as a C-ABI library for one AMD MI355X (gfx950).
  *
- * The four entry points are the steps of the paper's sparsification inference
+ * The entry points are the steps of the paper's sparsification inference
  * (Sec. 3.3.2; batch-parallel form in Appendix A.1):
  *   dllava_score               predictor logits D = P(S_l)                 (Eq. 5 line 1, Eq. 11 line 1)
  *   dllava_select_compact      keep decisions + reduced token set / cache  (Eq. 5 lines 2-3, Eq. 11 lines 2-3)
  *   dllava_prefill_attn        Attention over the reduced prefill set      (Eq. 1 with S^{P*}, Sec. 3.3.2)
  *   dllava_decode_attn_append  decode step with online KV-cache reduction  (Eq. 6)
+ *   dllava_qkv_project         Q, K, V of the reduced set, K/V into the cache (Eq. 3 line 1 with S^{P*})
  *
  * General conventions
  *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller
@@ -192,6 +193,37 @@ int dllava_decode_attn_append(const void* q, const void* k_new, const void* v_ne
                               void* o, uint8_t* keep_out, int32_t* err_flag,
                               void* workspace, size_t workspace_bytes, void* stream);
 size_t dllava_decode_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pages_per_seq);
+
+/*
+ * Projections of the reduced prefill set (Eq. 3 line 1 applied to S^{P*}; Sec. 3.2: the linear layers carry
+ * most of the prefill cost, so they run over the kept rows only):
+ *     Q, K, V = W^Q x, W^K x, W^V x     for every compacted row x,
+ * queries and keys then rotated by the ORIGINAL position p of their token: with half = Dh/2 and, per head,
+ * the pair (i, i + half), i < half, angle = p * rope_base^(-2 i / Dh):
+ *     y[i] = x[i] cos(angle) - x[i+half] sin(angle),   y[i+half] = x[i+half] cos(angle) + x[i] sin(angle)
+ * (rotary position embedding in the pairing of the LLaMA decoder; the paper itself does not mention
+ * positions).  Q goes to Q_out; K and V of token j of sequence b go through cache->block_table into
+ * cache->pages at position j, and cache->cache_len[b] = n_b = off[b+1] - off[b].  With this call,
+ * dllava_select_compact only has to gather the hidden states (its Q, K, V arguments NULL).
+ *
+ *   x        [rows, d] dtype, compacted hidden states (hidden_out of dllava_select_compact), row stride ldx
+ *   rows     host upper bound on off[B] (capacity of x, pos and Q_out); only rows < off[B] are computed
+ *   off      [B+1] row offsets of the sequences in the compacted order (out_off of dllava_select_compact)
+ *   pos      [rows] int32 original sequence-relative position of every compacted row (kept_idx of
+ *            dllava_select_compact), 0 <= pos < 2^24; may be NULL when rope_base <= 0
+ *   Wq, Wk, Wv  [H*Dh, d] dtype, row-major (H, Dh from `cache`)
+ *   rope_base   > 0: rotate as above (LLaMA uses 10000); <= 0: no rotation
+ *   Q_out    [rows, H, Dh] dtype, out
+ *   err_flag device int32, may be NULL: set to 1 if some n_b exceeds the cache capacity
+ *            max_pages_per_seq * page_size; K/V rows beyond capacity are then not written and cache_len[b]
+ *            is clamped to the capacity.  Never cleared by the library.
+ * Sizes: d * sizeof(dtype) and ldx * sizeof(dtype) multiples of 16.  rows == 0 or B == 0 is a no-op.
+ */
+int dllava_qkv_project(const void* x, int64_t ldx, int64_t rows, int64_t d,
+                       int32_t B, const int32_t* off, const int32_t* pos,
+                       const void* Wq, const void* Wk, const void* Wv, float rope_base,
+                       void* Q_out, const dllava_kv_cache* cache, int32_t* err_flag,
+                       int dtype, void* stream);
 
 #ifdef __cplusplus
 }

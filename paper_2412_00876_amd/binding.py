@@ -58,13 +58,16 @@ def _load() -> C.CDLL:
                                               vp, sz, vp]
     lib.dllava_decode_workspace.restype = sz
     lib.dllava_decode_workspace.argtypes = [i32, i32, i32, i32]
+    lib.dllava_qkv_project.restype = C.c_int
+    lib.dllava_qkv_project.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, vp, vp, f32, vp, C.POINTER(_KvCache), vp,
+                                       C.c_int, vp]
     return lib
 
 
 _lib = _load()
 EXPORTS = ("dllava_version", "dllava_last_error", "dllava_score", "dllava_score_workspace",
            "dllava_select_compact", "dllava_select_compact_workspace", "dllava_prefill_attn",
-           "dllava_decode_attn_append", "dllava_decode_workspace")
+           "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_qkv_project")
 
 
 def lib() -> C.CDLL:
@@ -157,6 +160,12 @@ def dllava_prefill_attn(Q, K, V, cache: Optional[KVCache], B, off, rows, H, Dh, 
                         stream=None) -> None:
     _check(_lib.dllava_prefill_attn(_p(Q), _p(K), _p(V), cache.ref if cache is not None else None, B, _p(off),
                                     rows, H, Dh, scale, _p(O), dtype, _stream(stream)))
+
+
+def dllava_qkv_project(x, ldx, rows, d, B, off, pos, Wq, Wk, Wv, rope_base, Q_out, cache: KVCache, err_flag, dtype,
+                       stream=None) -> None:
+    _check(_lib.dllava_qkv_project(_p(x), ldx, rows, d, B, _p(off), _p(pos), _p(Wq), _p(Wk), _p(Wv), rope_base,
+                                   _p(Q_out), cache.ref, _p(err_flag), dtype, _stream(stream)))
 
 
 def dllava_decode_attn_append(q, k_new, v_new, B, logits, threshold, keep_override, cache: KVCache, scale,

@@ -17,22 +17,14 @@
 //    score_splitk.h.
 // All reductions run in a fixed order: results are bit-reproducible.  Counters live at the start of the
 // workspace, start at zero and are returned to zero by the block that consumes them.
+#include "gemm_tile.h"
 #include "score_splitk.h"
 
 namespace dllava {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ bf16x8 as_frag(const uint4& v) {
-  union { uint4 u; bf16x8 f; } c;
-  c.u = v;
-  return c.f;
-}
 
 constexpr size_t kCounterBytes = 4096;  // up to 1024 int32 counters at the start of the workspace
 constexpr int kMaxCounters = 1024;
@@ -40,10 +32,7 @@ constexpr int kMaxCounters = 1024;
 // ------------------------------------------------------------------------------------------------
 // GEMM: 128 units x 128 tokens per block
 // ------------------------------------------------------------------------------------------------
-constexpr int kGThreads = 256;
 constexpr int kTU = 128, kTM = 128;
-constexpr int kBK = 64;             // hidden-dimension elements per pipeline stage: 128 bytes per row, one memory line
-constexpr int kTileElems = 128 * kBK;
 constexpr int kXcds = 8;            // accelerator complex dies of the chip
 
 __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4))) void score_gemm_kernel(
@@ -66,14 +55,8 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
   const bf16_t* W1 = static_cast<const bf16_t*>(a.W1);
   const bf16_t* X = static_cast<const bf16_t*>(a.x);
 
-  // Global -> registers -> LDS staging.  A stage is 128 bytes of each row, and 8 consecutive lanes fetch one
-  // row's piece as one whole memory line: a half-line piece (32 elements) moves the full line through the
-  // caches anyway and was measured at half the load throughput.  Thread: 16-byte chunk lc of rows lr + 32*j.
-  // LDS swizzle: chunk c of row r sits at chunk position c ^ ((r / 2) % 8).  The LDS serves a 16-byte access 16
-  // lanes at a time over 64 banks (16 bank groups of 16 bytes); with this placement the staging stores (2 rows
-  // x 8 chunks per 16 lanes) and the fragment loads (16 rows x 1 chunk) each touch 16 different bank groups.
+  // staging thread: 16-byte chunk lc of rows lr + 32*j of both tiles (see gemm_tile.h)
   const int lc = tid & 7, lr = tid >> 3;
-  const int st_off = lr * kBK + (lc ^ ((lr >> 1) & 7)) * 8;
   const bf16_t *gA0, *gA1, *gA2, *gA3, *gB0, *gB1, *gB2, *gB3;
   {
     const bf16_t* ga[4];
@@ -93,40 +76,7 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
     gB0 = gb[0]; gB1 = gb[1]; gB2 = gb[2]; gB3 = gb[3];
   }
   const int nk = static_cast<int>(d / kBK);
-  // two register sets: the loads of stages kt+1 and kt+2 are in flight while stage kt is multiplied
-  u32x4 pa0, pa1, pa2, pa3, pb0, pb1, pb2, pb3, qa0, qa1, qa2, qa3, qb0, qb1, qb2, qb3;
-  // Loads are issued unconditionally (past the end they re-read the last stage): a conditional load would make
-  // the number of outstanding loads path-dependent, and the compiler would then wait for all of them before
-  // every LDS store instead of only for the older register set.
-#define DLLAVA_GLOAD(S, kt)                                                      \
-  {                                                                              \
-    const int64_t ko = static_cast<int64_t>((kt) < nk ? (kt) : nk - 1) * kBK;    \
-    S##a0 = *reinterpret_cast<const u32x4*>(gA0 + ko);                           \
-    S##a1 = *reinterpret_cast<const u32x4*>(gA1 + ko);                           \
-    S##a2 = *reinterpret_cast<const u32x4*>(gA2 + ko);                           \
-    S##a3 = *reinterpret_cast<const u32x4*>(gA3 + ko);                           \
-    S##b0 = *reinterpret_cast<const u32x4*>(gB0 + ko);                           \
-    S##b1 = *reinterpret_cast<const u32x4*>(gB1 + ko);                           \
-    S##b2 = *reinterpret_cast<const u32x4*>(gB2 + ko);                           \
-    S##b3 = *reinterpret_cast<const u32x4*>(gB3 + ko);                           \
-  }
-  // a stage past the end (odd stage count) is stored with a zero W1 tile, so it adds nothing
-#define DLLAVA_SSTORE(S, kt)                                                     \
-  {                                                                              \
-    if ((kt) >= nk) S##a0 = S##a1 = S##a2 = S##a3 = u32x4{0u, 0u, 0u, 0u};       \
-    *reinterpret_cast<u32x4*>(sA + st_off) = S##a0;                              \
-    *reinterpret_cast<u32x4*>(sA + st_off + 32 * kBK) = S##a1;                   \
-    *reinterpret_cast<u32x4*>(sA + st_off + 64 * kBK) = S##a2;                   \
-    *reinterpret_cast<u32x4*>(sA + st_off + 96 * kBK) = S##a3;                   \
-    *reinterpret_cast<u32x4*>(sB + st_off) = S##b0;                              \
-    *reinterpret_cast<u32x4*>(sB + st_off + 32 * kBK) = S##b1;                   \
-    *reinterpret_cast<u32x4*>(sB + st_off + 64 * kBK) = S##b2;                   \
-    *reinterpret_cast<u32x4*>(sB + st_off + 96 * kBK) = S##b3;                   \
-  }
-
   const int wu = (w >> 1) * 64, wm = (w & 1) * 64;  // this wave's 64 units x 64 tokens
-  // fragment of k-step ks: chunk 2*ks + lane/32 of row lane%32 (+ multiples of 32), at its swizzled position
-  const int ld_off = (lane & 31) * kBK + ((lane >> 5) ^ ((lane >> 1) & 7)) * 8;
   f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -134,44 +84,7 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-#define DLLAVA_COMPUTE()                                                                                 \
-  {                                                                                                      \
-    const bf16_t* tA = sA + wu * kBK;                                                                    \
-    const bf16_t* tB = sB + wm * kBK;                                                                    \
-    _Pragma("unroll") for (int ks = 0; ks < kBK / 16; ++ks) {                                            \
-      bf16x8 fa[2], fb[2];                                                                               \
-      _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                    \
-        fa[i] = as_frag(*reinterpret_cast<const uint4*>(tA + i * 32 * kBK + (ld_off ^ (ks * 16))));      \
-        fb[i] = as_frag(*reinterpret_cast<const uint4*>(tB + i * 32 * kBK + (ld_off ^ (ks * 16))));      \
-      }                                                                                                  \
-      _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                      \
-        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                    \
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);         \
-    }                                                                                                    \
-  }
-
-  // One LDS buffer (32 KiB, so three blocks share a compute unit): multiply stage kt, barrier, overwrite it with
-  // stage kt+1 from the older register set, barrier.  Other resident blocks fill the barrier gaps.
-  DLLAVA_GLOAD(p, 0)
-  DLLAVA_GLOAD(q, 1)
-  DLLAVA_SSTORE(p, 0)
-  lds_barrier();
-  for (int kt = 0; kt < nk; kt += 2) {
-    DLLAVA_GLOAD(p, kt + 2)
-    DLLAVA_COMPUTE()
-    lds_barrier();
-    DLLAVA_SSTORE(q, kt + 1)
-    lds_barrier();
-    DLLAVA_GLOAD(q, kt + 3)
-    DLLAVA_COMPUTE()
-    lds_barrier();
-    DLLAVA_SSTORE(p, kt + 2)
-    lds_barrier();
-  }
-#undef DLLAVA_GLOAD
-#undef DLLAVA_SSTORE
-#undef DLLAVA_COMPUTE
+  gemm_tile_128x128<32>(gA0, gA1, gA2, gA3, gB0, gB1, gB2, gB3, nk, sA, sB, wu, wm, acc);
 
   // epilogue: lane holds, for token column (lane%32) of token tile j, units 8*(r/4) + 4*(lane/32) + r%4 of unit tile i
   const bf16_t* W2 = static_cast<const bf16_t*>(a.W2);
