@@ -72,20 +72,29 @@ __device__ __forceinline__ void gemm_tile_128x128(const bf16_t* gA0, const bf16_
 
   // fragment of k-step ks: chunk 2*ks + lane/32 of row lane%32 (+ multiples of 32), at its swizzled position
   const int ld_off = (lane & 31) * kBK + ((lane >> 5) ^ ((lane >> 1) & 7)) * 8;
+#define DLLAVA_FRAGS(F, ks)                                                                              \
+  _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                        \
+    F##a[i] = as_frag(*reinterpret_cast<const uint4*>(tA + i * A_FRAG_STRIDE * kBK + (ld_off ^ ((ks) * 16)))); \
+    F##b[i] = as_frag(*reinterpret_cast<const uint4*>(tB + i * 32 * kBK + (ld_off ^ ((ks) * 16))));      \
+  }
+#define DLLAVA_MFMAS(F)                                                                                  \
+  _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                          \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                        \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F##a[i], F##b[j], acc[i][j], 0, 0, 0);
+  // two fragment sets: the LDS reads of k-step ks+1 are in flight while the products of ks are issued
 #define DLLAVA_COMPUTE()                                                                                 \
   {                                                                                                      \
-    const bf16_t* tA = sA + a_row0 * kBK;                                                                    \
-    const bf16_t* tB = sB + b_row0 * kBK;                                                                    \
-    _Pragma("unroll") for (int ks = 0; ks < kBK / 16; ++ks) {                                            \
-      bf16x8 fa[2], fb[2];                                                                               \
-      _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                    \
-        fa[i] = as_frag(*reinterpret_cast<const uint4*>(tA + i * A_FRAG_STRIDE * kBK + (ld_off ^ (ks * 16))));      \
-        fb[i] = as_frag(*reinterpret_cast<const uint4*>(tB + i * 32 * kBK + (ld_off ^ (ks * 16))));      \
-      }                                                                                                  \
-      _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                      \
-        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                    \
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);         \
-    }                                                                                                    \
+    const bf16_t* tA = sA + a_row0 * kBK;                                                                \
+    const bf16_t* tB = sB + b_row0 * kBK;                                                                \
+    bf16x8 ua[2], ub[2], va[2], vb[2];                                                                   \
+    DLLAVA_FRAGS(u, 0)                                                                                   \
+    DLLAVA_FRAGS(v, 1)                                                                                   \
+    DLLAVA_MFMAS(u)                                                                                      \
+    DLLAVA_FRAGS(u, 2)                                                                                   \
+    DLLAVA_MFMAS(v)                                                                                      \
+    DLLAVA_FRAGS(v, 3)                                                                                   \
+    DLLAVA_MFMAS(u)                                                                                      \
+    DLLAVA_MFMAS(v)                                                                                      \
   }
 
   // One LDS buffer (32 KiB, so three blocks share a compute unit): multiply stage kt, barrier, overwrite it with
@@ -109,6 +118,8 @@ __device__ __forceinline__ void gemm_tile_128x128(const bf16_t* gA0, const bf16_
 #undef DLLAVA_GLOAD
 #undef DLLAVA_SSTORE
 #undef DLLAVA_COMPUTE
+#undef DLLAVA_FRAGS
+#undef DLLAVA_MFMAS
 
 }
 
