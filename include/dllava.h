@@ -56,7 +56,7 @@ typedef enum {
   DLLAVA_ELAUNCH = -7     /* the HIP runtime refused a launch                      */
 } dllava_status;
 
-typedef enum { DLLAVA_MODE_TOPK = 0, DLLAVA_MODE_THRESHOLD = 1 } dllava_mode;
+typedef enum { DLLAVA_MODE_TOPK = 0, DLLAVA_MODE_THRESHOLD = 1, DLLAVA_MODE_THRESHOLD_KEEP_LAST = 2 } dllava_mode;
 
 /*
  * Paged KV cache of ONE decoder layer; caller-owned (the per-sample caches {S^K(b), S^V(b)} of
@@ -122,6 +122,12 @@ size_t dllava_score_workspace(int64_t M, int64_t d, int64_t dh, int dtype);
  *                          number; -0 equals +0.
  *   DLLAVA_MODE_THRESHOLD  keep row i iff logits[i,1] - logits[i,0] > threshold (float32,
  *                          strict; threshold 0 is the argmax rule of Eq. 5).
+ *   DLLAVA_MODE_THRESHOLD_KEEP_LAST
+ *                          the same, and the last row of the span is kept whatever its logits: decoding
+ *                          WITHOUT KV cache (Sec. 3.3.2; Eq. 12), where the span is the output text S^OT
+ *                          appended to the already reduced prompt, the mask entry of the last output token
+ *                          is set to 1 because that token generates the next one, and dllava_prefill_attn
+ *                          then runs over S^{P*} u S^{OT*}.
  * Text rows are always kept.  Kept rows keep their original relative order, which is what
  * makes causal attention over the reduced set equal the masked attention of Eq. 7.
  *

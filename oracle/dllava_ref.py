@@ -46,6 +46,7 @@ from scipy.special import erf as _erf
 
 TOPK = 0
 THRESHOLD = 1
+THRESHOLD_KEEP_LAST = 2   # Sec. 3.3.2, decoding without KV cache: the mask entry of the last output token is 1
 
 
 # ----------------------------------------------------------------------------- storage
@@ -146,6 +147,10 @@ def select(logits, seq_off, vis_start, vis_len, mode: int, keep_ratio: float, th
             m[select_topk(Db[:, 1], keep_count(keep_ratio, n))] = 1
         elif mode == THRESHOLD:
             m = select_threshold(Db, theta)
+        elif mode == THRESHOLD_KEEP_LAST:
+            m = select_threshold(Db, theta)
+            if n:
+                m[n - 1] = 1
         else:
             raise ValueError(mode)
         base = int(seq_off[b])
@@ -281,6 +286,30 @@ def decode_attn_append(q, k_new, v_new, keep, cache: PagedCache, scale: float,
             cache.put(b, L, k_new[b], v_new[b])
             cache.cache_len[b] = L + 1
     return o, err
+
+
+# ----------------------------------------------------------------------------- Sec. 3.3.2 / Eq. 12: decoding without KV cache
+
+def decode_nocache_step(Qp, Kp, Vp, p_off, Qo, Ko, Vo, o_off, logits_ot, theta: float, scale: float, dtype: str):
+    """One decoding step WITHOUT KV cache for a batch.
+
+    Sequence b consists of its reduced prompt S^{P*}(b) (rows p_off[b]:p_off[b+1] of Qp/Kp/Vp) followed by ALL its
+    output text tokens so far (rows o_off[b]:o_off[b+1] of Qo/Ko/Vo, logits_ot [sum n_ot, 2] their predictor
+    logits).  The output tokens are masked by the threshold rule with the last one kept regardless (it generates
+    the next token), the kept rows are compacted in order, and causal attention (Eq. 1) runs over S^{P*} u S^{OT*}.
+    Returns (O [sum kept rows, H, Dh], out_off [B+1], keep_mask over the concatenated sequences).
+    """
+    B = len(p_off) - 1
+    n_p = [int(p_off[b + 1] - p_off[b]) for b in range(B)]
+    n_o = [int(o_off[b + 1] - o_off[b]) for b in range(B)]
+    cat = lambda P_, O_: np.concatenate([np.concatenate([P_[p_off[b]:p_off[b + 1]], O_[o_off[b]:o_off[b + 1]]])
+                                         for b in range(B)]) if B else P_[:0]
+    Q, K, V = cat(Qp, Qo), cat(Kp, Ko), cat(Vp, Vo)
+    seq_off = np.concatenate([[0], np.cumsum([n_p[b] + n_o[b] for b in range(B)])]).astype(np.int64)
+    mask, idx, off = select(logits_ot, seq_off, n_p, n_o, THRESHOLD_KEEP_LAST, 0.0, theta)
+    src = np.concatenate([seq_off[b] + idx[off[b]:off[b + 1]] for b in range(B)]) if B else np.zeros(0, np.int64)
+    O = prefill_attn(Q[src], K[src], V[src], off, scale, dtype)
+    return O, off, mask
 
 
 # ----------------------------------------------------------------------------- Eq. 3 line 1 over the reduced set

@@ -4,7 +4,7 @@ The binding (and with it the shared library) is loaded on first use of any of it
 module can be imported before the library exists.  There is no fallback: without the built library the first
 use raises ImportError.
 """
-_BINDING_NAMES = ("BF16", "F32", "MODE_THRESHOLD", "MODE_TOPK", "PAGE_SIZE", "DllavaError", "KVCache", "EXPORTS",
+_BINDING_NAMES = ("BF16", "F32", "MODE_THRESHOLD", "MODE_THRESHOLD_KEEP_LAST", "MODE_TOPK", "PAGE_SIZE", "DllavaError", "KVCache", "EXPORTS",
                   "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_prefill_attn", "dllava_score",
                   "dllava_score_workspace", "dllava_qkv_project",
                   "dllava_select_compact", "dllava_select_compact_workspace", "dllava_version", "lib")

@@ -16,7 +16,7 @@ import torch
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libdllava.so")
 
 F32, BF16 = 0, 1
-MODE_TOPK, MODE_THRESHOLD = 0, 1
+MODE_TOPK, MODE_THRESHOLD, MODE_THRESHOLD_KEEP_LAST = 0, 1, 2
 PAGE_SIZE = 16
 
 

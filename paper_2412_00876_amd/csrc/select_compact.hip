@@ -162,6 +162,8 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectArgs a) {
           }
         } else {
           keep = keep_from_logits(D, i, a.threshold);
+          // decoding without KV cache: the last output token produces the next one and is always kept
+          if (a.mode == DLLAVA_MODE_THRESHOLD_KEEP_LAST && i == n - 1) keep = true;
         }
       }
       keep_bits |= (keep ? 1u : 0u) << e;
@@ -320,7 +322,8 @@ extern "C" int dllava_select_compact(const float* logits, int32_t B, const int32
   DLLAVA_REQUIRE(B >= 0 && sumN >= 0, DLLAVA_EINVAL, "select_compact: B = %d, sumN = %lld", B, (long long)sumN);
   DLLAVA_REQUIRE(sumN <= 0x7fffffffLL, DLLAVA_ESHAPE, "select_compact: sumN must fit in int32");
   DLLAVA_REQUIRE(dtype == DLLAVA_F32 || dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "select_compact: unknown dtype %d", dtype);
-  DLLAVA_REQUIRE(mode == DLLAVA_MODE_TOPK || mode == DLLAVA_MODE_THRESHOLD, DLLAVA_EINVAL,
+  DLLAVA_REQUIRE(mode == DLLAVA_MODE_TOPK || mode == DLLAVA_MODE_THRESHOLD || mode == DLLAVA_MODE_THRESHOLD_KEEP_LAST,
+                 DLLAVA_EINVAL,
                  "select_compact: unknown mode %d", mode);
   if (mode == DLLAVA_MODE_TOPK)
     DLLAVA_REQUIRE(keep_ratio >= 0.0 && keep_ratio <= 1.0, DLLAVA_EINVAL,

@@ -163,6 +163,33 @@ def test_prefill_block_numbering(B, Dh, lens, from_cache):
     _assert_out_close(h.as_f64(O), ref, w.dtype, f"prefill numbering B={B} Dh={Dh}")
 
 
+@pytest.mark.parametrize("theta", [0.0, 0.4, float("inf"), float("-inf")])
+def test_decode_step_without_kv_cache(theta):
+    """Decoding without KV cache (Sec. 3.3.2, Eq. 12): every sequence is its reduced prompt followed by all output
+    tokens so far; the output span is masked by the threshold rule with its last token always kept, compacted, and
+    attended causally.  Mask, indices and offsets bit-exact, attention rows within the output tolerance."""
+    h = _H()
+    import paper_2412_00876_amd as P
+    n_p, n_ot = [37, 0, 130, 5, 64], [9, 3, 1, 0, 150]      # a sequence without prompt, one without output tokens
+    w = W.make("nocache", "bf16", 256, 3, 128, 5, n_p, n_ot, 0, 1.0, 0)
+    pre = W.prefill_inputs(w)
+    g = h.GpuPath(w, pre, None)
+    D = rng.normal(w.seed, "ot.D", (int(sum(n_ot)), 2)).astype(np.float32)
+    out = g.select_compact(torch.from_numpy(D).to(h.DEV), mode=P.MODE_THRESHOLD_KEEP_LAST, theta=theta, with_hidden=False)
+    mask, idx, off = R.select(D, w.seq_off, w.vis_start, w.vis_len, R.THRESHOLD_KEEP_LAST, 0.0, theta)
+    total = int(off[-1])
+    assert np.array_equal(out["keep_mask"].cpu().numpy(), mask)
+    assert np.array_equal(out["out_off"].cpu().numpy(), off)
+    assert np.array_equal(out["kept_idx"].cpu().numpy()[:total], idx)
+    for b in range(w.B):                       # the last output token of every sequence that has one is kept
+        if n_ot[b]:
+            assert mask[w.seq_off[b + 1] - 1] == 1
+    src = np.concatenate([w.seq_off[b] + idx[off[b]:off[b + 1]] for b in range(w.B)])
+    O_ref = R.prefill_attn(pre["Q"][src], pre["K"][src], pre["V"][src], off, g.scale, w.dtype)
+    O = g.prefill(out["Q_out"].contiguous(), out["out_off"])
+    _assert_out_close(h.as_f64(O[:total]), O_ref, w.dtype, "attention over the reduced prompt and output tokens")
+
+
 def test_results_are_bit_reproducible():
     """Every reduction runs in a fixed order (or in integer arithmetic): repeating a call must not change a bit."""
     h = _H()

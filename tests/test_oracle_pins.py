@@ -440,3 +440,54 @@ def test_projecting_kept_rows_equals_compacting_the_full_projection():
         Kc, Vc = cache.rows(b)
         assert np.array_equal(Kc, R.narrow(K[off[b]:off[b + 1]], w.dtype))
         assert np.array_equal(Vc, R.narrow(V[off[b]:off[b + 1]], w.dtype))
+
+
+# ------------------------------------------------------------------ decoding without KV cache (Sec. 3.3.2, Eq. 12)
+
+def test_keep_last_mode_is_the_threshold_rule_with_the_last_entry_set():
+    D = rng.normal(11, "D", (40, 2)).astype(np.float32)
+    seq_off, v0, n = [0, 12, 12, 40], [2, 0, 5], [7, 0, 20]      # middle sequence empty
+    logits = np.concatenate([D[:7], D[7:27]])
+    m1, i1, o1 = R.select(logits, seq_off, v0, n, R.THRESHOLD, 0.0, 0.3)
+    m2, i2, o2 = R.select(logits, seq_off, v0, n, R.THRESHOLD_KEEP_LAST, 0.0, 0.3)
+    want = m1.copy()
+    want[0 + 2 + 7 - 1] = 1
+    want[12 + 5 + 20 - 1] = 1
+    assert np.array_equal(m2, want)
+    m3, _, _ = R.select(logits, seq_off, v0, n, R.THRESHOLD_KEEP_LAST, 0.0, float("inf"))
+    assert m3[2:9].tolist() == [0] * 6 + [1] and m3[17:37].tolist() == [0] * 19 + [1]   # nothing but the last one
+
+
+def test_decoding_without_cache_reproduces_decoding_with_cache():
+    """Two formulations of the same step.  With KV cache (Eq. 6): the new token attends over the cached kept
+    tokens plus itself, and enters the cache only if kept.  Without (Eq. 12 + Eq. 1): all output tokens are
+    re-masked with the last one forced to 1, compacted, and attended causally.  The last row of the second must
+    equal the output of the first at every step, for any keep history."""
+    w = W.make("nocache", "bf16", 64, 2, 16, 2, [1, 0], [6, 4], [2, 3], 0.5, 7, project_qkv=True)
+    pre, dec = W.prefill_inputs(w), W.decode_inputs(w)
+    D = rng.normal(w.seed, "D", (int(sum(w.n_vis)), 2)).astype(np.float32)
+    mask, idx, off = R.select(D, w.seq_off, w.vis_start, w.vis_len, R.TOPK, w.keep_ratio, 0.0)
+    bt, n_pages = W.block_table(w)
+    cache = R.PagedCache(n_pages, bt, w.H, w.Dh, w.dtype)
+    _, Qp = R.compact(idx, off, w.seq_off, Q=pre["Q"], K=pre["K"], V=pre["V"], cache=cache)
+    src = np.concatenate([w.seq_off[b] + idx[off[b]:off[b + 1]] for b in range(w.B)])
+    Kp, Vp = pre["K"][src], pre["V"][src]
+    scale = 1.0 / math.sqrt(w.Dh)
+    logits = rng.normal(w.seed, "ot.logits", (w.T, w.B, 2)).astype(np.float32)   # predictor logits of the output tokens
+    for t in range(w.T):
+        keep = R.decode_keep(logits[t], 0.0)
+        o_cache, err = R.decode_attn_append(dec["q"][t], dec["k"][t], dec["v"][t], keep, cache, scale)
+        assert not err.any()
+        # without cache: all output tokens 0..t of both sequences, sequence-major
+        n_ot = t + 1
+        seqmaj = lambda a: np.concatenate([a[:n_ot, b] for b in range(w.B)])
+        o_off = np.arange(w.B + 1) * n_ot
+        O, ooff, m = R.decode_nocache_step(Qp, Kp, Vp, off, seqmaj(dec["q"]), seqmaj(dec["k"]), seqmaj(dec["v"]),
+                                           o_off, seqmaj(logits), 0.0, scale, w.dtype)
+        for b in range(w.B):
+            assert np.allclose(O[ooff[b + 1] - 1], o_cache[b], rtol=0, atol=1e-12)
+            # kept output tokens = the history of keep decisions, plus the current token
+            hist = [int(R.decode_keep(logits[s], 0.0)[b]) for s in range(t)] + [1]
+            n_p = int(off[b + 1] - off[b])
+            assert ooff[b + 1] - ooff[b] == n_p + sum(hist)
+            assert int(cache.cache_len[b]) == n_p + sum(hist[:-1]) + int(keep[b])
