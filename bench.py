@@ -162,6 +162,47 @@ class Path:
             self.decode_attn(t)
 
 
+class NoCacheStep:
+    """One decoding step WITHOUT KV cache at the END of the generation (Sec. 3.3.2, Eq. 12): every sequence is its
+    reduced prompt (kept_len rows) followed by all T output tokens; the output span is re-masked by the threshold
+    rule with the last token kept, everything kept is compacted (Q, K/V into pages) and attended causally.
+    Q/K/V and the output-token logits are seeded random tensors of that shape (the cost is value-independent)."""
+
+    def __init__(self, path):
+        w, P, torch = path.w, path.P, path.torch
+        dev, td = "cuda:0", (torch.bfloat16 if w.dtype == "bf16" else torch.float32)
+        B, T, H, Dh = w.B, w.T, w.H, w.Dh
+        self.path = path
+        n_p = np.asarray(w.kept_len, np.int64)
+        self.seq_off_np = np.concatenate([[0], np.cumsum(n_p + T)]).astype(np.int32)
+        self.sumN = int(self.seq_off_np[-1])
+        i32 = lambda a: torch.from_numpy(np.asarray(a, np.int32)).to(dev)
+        self.seq_off, self.span_start, self.span_len = i32(self.seq_off_np), i32(n_p), i32([T] * B)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed + 77)
+        rnd = lambda *sh: torch.randn(*sh, generator=gen, device=dev, dtype=torch.float32)
+        self.Q, self.K, self.V = (rnd(self.sumN, H, Dh).to(td) for _ in range(3))
+        self.logits = rnd(B * T, 2)
+        mp = (int(n_p.max()) + T + 15) // 16
+        self.pages = torch.zeros((B * mp, 2, H, 16, Dh), dtype=td, device=dev)
+        self.cache_len = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.cache = P.KVCache(self.pages, i32(np.arange(B * mp).reshape(B, mp)), self.cache_len)
+        self.keep_mask = torch.zeros(self.sumN, dtype=torch.uint8, device=dev)
+        self.kept_idx = torch.zeros(self.sumN, dtype=torch.int32, device=dev)
+        self.out_off = torch.zeros(B + 1, dtype=torch.int32, device=dev)
+        self.Q_out = torch.zeros((self.sumN, H, Dh), dtype=td, device=dev)
+        self.O = torch.zeros((self.sumN, H, Dh), dtype=td, device=dev)
+        self.ws = torch.zeros(P.dllava_select_compact_workspace(B, self.sumN), dtype=torch.uint8, device=dev)
+
+    def run(self):
+        p, w, P = self.path, self.path.w, self.path.P
+        P.dllava_select_compact(self.logits, w.B, self.seq_off, self.span_start, self.span_len, self.sumN,
+                                P.MODE_THRESHOLD_KEEP_LAST, 0.0, 0.0, None, None, w.d, self.Q, self.Q_out, self.K, self.V,
+                                self.cache, self.keep_mask, self.kept_idx, self.out_off, p.err, p.code, self.ws)
+        P.dllava_prefill_attn(self.Q_out, None, None, self.cache, w.B, self.out_off, self.sumN, w.H, w.Dh, p.scale,
+                              self.O, p.code)
+
+
 def timed_events(torch, fn, n=1):
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
@@ -325,6 +366,9 @@ def main():
         path.qkv_project()                                              # (weights to the device, outside the graph)
         ms_qkv = stage_ms(lambda i: path.qkv_project(), 3)              # overwrites Q_out and the pages ...
         ms_select = stage_ms(lambda i: path.select_compact(), 5)       # ... which this restores
+        nc = NoCacheStep(path)
+        ms_nc = stage_ms(lambda i: nc.run(), 3)
+        nc_kept = [int(v) for v in (nc.out_off[1:] - nc.out_off[:-1]).tolist()]
         ms_prefill = stage_ms(lambda i: path.prefill_attn(), 5)
         ms_sd = stage_ms(path.score_decode, T)                          # logits of all steps: inputs of the next line
         ms_da = stage_ms(path.decode_attn, T, before=path.select_compact)  # cache reset, then T attention launches
@@ -368,6 +412,12 @@ def main():
             "qkv_project": {"ms": ms_qkv, "tflops": flops_qkv / (ms_qkv * 1e-3) / 1e12,
                             "frac_mfma_peak": flops_qkv / (ms_qkv * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                             "flops_dense_counterfactual": 2.0 * w.sumN * w.d * 3 * H * Dh},
+            # the paper's other decoding mode, also outside the timed step: one step without KV cache at the end of
+            # the generation (re-mask all output tokens, compact, causal attention over prompt* + kept outputs)
+            "decode_step_without_cache": {"ms": ms_nc, "rows_in": nc.sumN, "rows_kept": int(sum(nc_kept)),
+                                          "attn_tflops": sum(4.0 * H * Dh * n * (n + 1) / 2 for n in nc_kept) / (ms_nc * 1e-3) / 1e12,
+                                          "attn_flops_dense_counterfactual": float(sum(4.0 * H * Dh * n * (n + 1) / 2
+                                                                                       for n in (np.asarray(w.seq_len) + T)))},
             "decode_score": {"avg_us": float(ms_sd * 1e3)},
             "decode_attn": {"avg_us": avg_ms * 1e3, "gbs": achieved,
                             "kv_mb_first_step": float(kv_bytes_t[0] / 1e6), "kv_mb_last_step": float(kv_bytes_t[-1] / 1e6)},
