@@ -31,6 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # HBM bytes moved per algorithmic byte by the decode kernel, from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE, each
 # scaled by its reading for a 256 MiB copy): profiles/decode_attn_c3_hbm_counters.txt
 DECODE_TRAFFIC_PER_ALGORITHMIC_BYTE = 1.027
+STEP_TRAFFIC_PER_ALGORITHMIC_BYTE = None   # dllava_decode_step: not yet read from the counters
 
 
 def parse():
@@ -41,6 +42,9 @@ def parse():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--decode-steps", type=int, default=None, help="override T (for quick runs)")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--two-launch-decode", action="store_true",
+                    help="decode with dllava_score + dllava_decode_attn_append (two dependent launches per step) "
+                         "instead of dllava_decode_step (one launch, append deferred by one step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--pmc-probe", type=int, default=0, metavar="L",
@@ -96,6 +100,8 @@ class Path:
         self.ws_score_dec = z(P.dllava_score_workspace(B, w.d, w.dh, self.code))
         self.ws_select = z(P.dllava_select_compact_workspace(B, sumN))
         self.ws_decode = z(P.dllava_decode_workspace(B, w.H, w.Dh, self.cache.max_pages_per_seq))
+        self.ws_step = z(P.dllava_decode_step_workspace(B, w.H, w.Dh, self.cache.max_pages_per_seq, w.d, w.dh, self.code))
+        self.two_launch = False
         self.scale = 1.0 / math.sqrt(w.Dh)
 
     def calibrate_theta(self):
@@ -153,13 +159,34 @@ class Path:
                                          self.cache, self.scale, self.o_dec[t], self.keep_dec[t], self.err,
                                          self.ws_decode)
 
+    def decode_step(self, t):
+        """Scoring + attention of step t in one launch; the append of token t-1 happens here (deferred form)."""
+        w, d, p = self.w, self.dec, self.pred
+        prev = t > 0
+        self.P.dllava_decode_step(d["x"][t], w.d, w.d, w.dh, p["W1"], p["b1"], p["W2"], p["b2"],
+                                  d["q"][t], d["k"][t], d["v"][t],
+                                  d["k"][t - 1] if prev else None, d["v"][t - 1] if prev else None,
+                                  self.logits_dec[t - 1] if prev else None, None, w.B, w.theta, self.cache, self.scale,
+                                  self.o_dec[t], self.logits_dec[t], self.keep_dec[t - 1] if prev else None, self.err,
+                                  self.ws_step)
+
+    def decode_commit(self):
+        w, d, T = self.w, self.dec, self.w.T
+        self.P.dllava_decode_commit(d["k"][T - 1], d["v"][T - 1], self.logits_dec[T - 1], None, w.B, w.theta, self.cache,
+                                    self.keep_dec[T - 1], self.err)
+
     def step(self):
         self.score_vision()
         self.select_compact()
         self.prefill_attn()
-        for t in range(self.w.T):
-            self.score_decode(t)
-            self.decode_attn(t)
+        if self.two_launch:
+            for t in range(self.w.T):
+                self.score_decode(t)
+                self.decode_attn(t)
+        else:
+            for t in range(self.w.T):
+                self.decode_step(t)
+            self.decode_commit()
 
 
 class NoCacheStep:
@@ -277,11 +304,19 @@ def pmc_probe(path, torch, L):
                                          path.cache, path.scale, path.o_dec[0], path.keep_dec[0], path.err,
                                          path.ws_decode)
     torch.cuda.synchronize()
+    for _ in range(3):                               # the one-launch step at the same length (no previous token)
+        path.cache_len.fill_(L)
+        path.P.dllava_decode_step(path.dec["x"][0], w.d, w.d, w.dh, path.pred["W1"], path.pred["b1"], path.pred["W2"],
+                                  path.pred["b2"], path.dec["q"][0], path.dec["k"][0], path.dec["v"][0], None, None, None,
+                                  None, w.B, 0.0, path.cache, path.scale, path.o_dec[0], path.logits_dec[0], None,
+                                  path.err, path.ws_step)
+    torch.cuda.synchronize()
     es = 2 if w.dtype == "bf16" else 4
     rows = int(path.out_off[-1].item())
     n_kept = [int(v) for v in (path.out_off[1:] - path.out_off[:-1]).tolist()]
     print(json.dumps({"pmc_probe": True, "copy_bytes_read": n, "copy_bytes_written": n, "cache_len": L,
                       "decode_algorithmic_bytes_per_launch": w.B * L * 2 * w.H * w.Dh * es,
+                      "decode_step_algorithmic_bytes_per_launch": w.B * L * 2 * w.H * w.Dh * es + (w.d * w.dh + w.B * w.d) * es,
                       "score_vision_flops": 2.0 * path.M_vis * w.d * w.dh,
                       "prefill_attn_flops": float(sum(4.0 * w.H * w.Dh * m * (m + 1) / 2 for m in n_kept)),
                       "compact_algorithmic_bytes": 2 * rows * (2 * w.d + 6 * w.H * w.Dh) * es // 2}))
@@ -306,6 +341,7 @@ def main():
         w.T = args.decode_steps
     torch.cuda.set_device(0)
     path = Path(w, torch, P, W)
+    path.two_launch = args.two_launch_decode
     B, T, H, Dh = w.B, w.T, w.H, w.Dh
     es = 2 if w.dtype == "bf16" else 4
 
@@ -373,11 +409,19 @@ def main():
         ms_sd = stage_ms(path.score_decode, T)                          # logits of all steps: inputs of the next line
         ms_da = stage_ms(path.decode_attn, T, before=path.select_compact)  # cache reset, then T attention launches
         assert np.array_equal(path.keep_dec.cpu().numpy(), keep), "decode replay diverged from the timed run"
+        ms_ds = stage_ms(path.decode_step, T, before=path.select_compact)  # cache reset, then T one-launch steps
 
     tokens = B * T
     value = tokens / (ms_per_step * 1e-3)
-    # dominant kernel: decode attention.  Algorithmic bytes per launch: the cached K+V of every sequence.
-    kernel_name, avg_ms, avg_bytes = "decode_attn_kernel (dllava_decode_attn_append)", float(ms_da), float(kv_bytes_t.mean())
+    # dominant kernel: the decode launch.  Algorithmic bytes per launch: the cached K+V of every sequence, and for the
+    # one-launch step also what its scoring half must read once (W1 and the B hidden rows).
+    pred_bytes = (w.d * w.dh + B * w.d) * es
+    if args.two_launch_decode:
+        kernel_name, avg_ms, avg_bytes = "decode_attn_kernel (dllava_decode_attn_append)", float(ms_da), float(kv_bytes_t.mean())
+        traffic_factor = DECODE_TRAFFIC_PER_ALGORITHMIC_BYTE
+    else:
+        kernel_name, avg_ms, avg_bytes = "decode_step_kernel (dllava_decode_step)", float(ms_ds), float(kv_bytes_t.mean()) + pred_bytes
+        traffic_factor = STEP_TRAFFIC_PER_ALGORITHMIC_BYTE
     achieved = avg_bytes / (avg_ms * 1e-3) / 1e9
     M_vis = path.M_vis
     flops_score = 2.0 * M_vis * w.d * w.dh + 4.0 * M_vis * w.dh
@@ -398,7 +442,7 @@ def main():
                    "text_keep_fraction": float(keep.mean()), "theta": w.theta},
         "roofline": {"kernel": kernel_name, "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": DECODE_TRAFFIC_PER_ALGORITHMIC_BYTE * avg_bytes if ci == 2 else None,
+                     "traffic": traffic_factor * avg_bytes if (ci == 2 and traffic_factor) else None,
                      "avg_launch_us": avg_ms * 1e3, "avg_bytes_per_launch": avg_bytes},
         "stages": {
             "score_vision": {"ms": ms_score, "tflops": flops_score / (ms_score * 1e-3) / 1e12,
@@ -418,8 +462,10 @@ def main():
                                           "attn_tflops": sum(4.0 * H * Dh * n * (n + 1) / 2 for n in nc_kept) / (ms_nc * 1e-3) / 1e12,
                                           "attn_flops_dense_counterfactual": float(sum(4.0 * H * Dh * n * (n + 1) / 2
                                                                                        for n in (np.asarray(w.seq_len) + T)))},
+            "decode_step": {"avg_us": float(ms_ds * 1e3), "gbs": (float(kv_bytes_t.mean()) + pred_bytes) / (ms_ds * 1e-3) / 1e9,
+                            "note": "one launch per step: scoring + attention, append deferred by one step"},
             "decode_score": {"avg_us": float(ms_sd * 1e3)},
-            "decode_attn": {"avg_us": avg_ms * 1e3, "gbs": achieved,
+            "decode_attn": {"avg_us": float(ms_da * 1e3), "gbs": float(kv_bytes_t.mean()) / (ms_da * 1e-3) / 1e9,
                             "kv_mb_first_step": float(kv_bytes_t[0] / 1e6), "kv_mb_last_step": float(kv_bytes_t[-1] / 1e6)},
             "kv_bytes_total": float(kv_bytes_t.sum()), "kv_bytes_dense_counterfactual": float(dense_L.sum()),
         },

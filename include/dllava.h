@@ -8,6 +8,7 @@
  *   dllava_select_compact      keep decisions + reduced token set / cache  (Eq. 5 lines 2-3, Eq. 11 lines 2-3)
  *   dllava_prefill_attn        Attention over the reduced prefill set      (Eq. 1 with S^{P*}, Sec. 3.3.2)
  *   dllava_decode_attn_append  decode step with online KV-cache reduction  (Eq. 6)
+ *   dllava_decode_step         the same step, scoring + attention in one launch, append deferred by one step
  *   dllava_qkv_project         Q, K, V of the reduced set, K/V into the cache (Eq. 3 line 1 with S^{P*})
  *
  * General conventions
@@ -199,6 +200,50 @@ int dllava_decode_attn_append(const void* q, const void* k_new, const void* v_ne
                               void* o, uint8_t* keep_out, int32_t* err_flag,
                               void* workspace, size_t workspace_bytes, void* stream);
 size_t dllava_decode_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pages_per_seq);
+
+/*
+ * The same decode step (Eq. 6) in DEFERRED form: scoring and attention of the current tokens in ONE launch.
+ *
+ * In dllava_decode_attn_append the append waits for the keep decision, so the predictor must run before the
+ * attention kernel (two dependent launches per step).  Nothing else in the step needs the decision: the current
+ * token takes part in its own attention whatever it is.  Here the decision of the token of step t is therefore
+ * applied by the call of step t+1:
+ *   logits[b]  = predictor logits of x[b]                          (as dllava_score, one row per sequence)
+ *   keep_prev[b] = keep_prev_override[b] != 0                      if keep_prev_override != NULL
+ *                = logits_prev[b,1] - logits_prev[b,0] > threshold if logits_prev != NULL   (float32, strict)
+ *                = 0                                               otherwise (first step: nothing outstanding)
+ *   if keep_prev[b]: k_prev[b], v_prev[b] are stored at position cache_len[b] and cache_len[b] += 1
+ *   o[b,h] = softmax(scale * [K_cache(b,h); k_new[b,h]] q[b,h]) [V_cache(b,h); v_new[b,h]]   over the cache INCLUDING
+ *            the previous token if it was kept -- exactly the o of dllava_decode_attn_append at the same step.
+ * The current tokens are NOT in the cache when the call returns: pass their k_new, v_new and `logits` as k_prev,
+ * v_prev, logits_prev of the next call (the buffers must stay untouched until then), and finish a generation
+ * with dllava_decode_commit.  After that the cache equals the one dllava_decode_attn_append leaves, bit for bit.
+ *
+ *   x [B, d] dtype (row stride ldx), W1 [dh, d], W2 [2, dh] dtype, b1 [dh], b2 [2] float32 or NULL: as dllava_score
+ *   q, k_new, v_new, k_prev, v_prev  [B, H, Dh] cache->dtype
+ *   logits       [B, 2] float32 out;  logits_prev [B, 2] float32 in (a different buffer) or NULL
+ *   keep_prev_out [B] uint8 out, may be NULL: keep_prev, written only when a previous token is given
+ *   err_flag     as in dllava_decode_attn_append (a kept previous token that finds its sequence at capacity is
+ *                neither stored nor attended)
+ *   workspace    dllava_decode_step_workspace(...) bytes, zero-filled once, private to this entry point
+ */
+int dllava_decode_step(const void* x, int64_t ldx, int64_t d, int64_t dh,
+                       const void* W1, const float* b1, const void* W2, const float* b2,
+                       const void* q, const void* k_new, const void* v_new,
+                       const void* k_prev, const void* v_prev, const float* logits_prev,
+                       const uint8_t* keep_prev_override,
+                       int32_t B, float threshold, const dllava_kv_cache* cache, float scale,
+                       void* o, float* logits, uint8_t* keep_prev_out, int32_t* err_flag,
+                       void* workspace, size_t workspace_bytes, void* stream);
+size_t dllava_decode_step_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pages_per_seq,
+                                    int64_t d, int64_t dh, int dtype);
+
+/* Applies the decision that the last dllava_decode_step left outstanding: if keep (from logits_prev and threshold, or
+ * keep_prev_override), k_prev[b], v_prev[b] are stored at position cache_len[b] and cache_len[b] += 1.
+ * keep_out [B] uint8 may be NULL; err_flag as above. */
+int dllava_decode_commit(const void* k_prev, const void* v_prev, const float* logits_prev,
+                         const uint8_t* keep_prev_override, int32_t B, float threshold,
+                         const dllava_kv_cache* cache, uint8_t* keep_out, int32_t* err_flag, void* stream);
 
 /*
  * Projections of the reduced prefill set (Eq. 3 line 1 applied to S^{P*}; Sec. 3.2: the linear layers carry

@@ -58,6 +58,13 @@ def _load() -> C.CDLL:
                                               vp, sz, vp]
     lib.dllava_decode_workspace.restype = sz
     lib.dllava_decode_workspace.argtypes = [i32, i32, i32, i32]
+    lib.dllava_decode_step.restype = C.c_int
+    lib.dllava_decode_step.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32,
+                                       C.POINTER(_KvCache), f32, vp, vp, vp, vp, vp, sz, vp]
+    lib.dllava_decode_step_workspace.restype = sz
+    lib.dllava_decode_step_workspace.argtypes = [i32, i32, i32, i32, i64, i64, C.c_int]
+    lib.dllava_decode_commit.restype = C.c_int
+    lib.dllava_decode_commit.argtypes = [vp, vp, vp, vp, i32, f32, C.POINTER(_KvCache), vp, vp, vp]
     lib.dllava_qkv_project.restype = C.c_int
     lib.dllava_qkv_project.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, vp, vp, f32, vp, C.POINTER(_KvCache), vp,
                                        C.c_int, vp]
@@ -67,7 +74,8 @@ def _load() -> C.CDLL:
 _lib = _load()
 EXPORTS = ("dllava_version", "dllava_last_error", "dllava_score", "dllava_score_workspace",
            "dllava_select_compact", "dllava_select_compact_workspace", "dllava_prefill_attn",
-           "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_qkv_project")
+           "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_qkv_project",
+           "dllava_decode_step", "dllava_decode_step_workspace", "dllava_decode_commit")
 
 
 def lib() -> C.CDLL:
@@ -160,6 +168,26 @@ def dllava_prefill_attn(Q, K, V, cache: Optional[KVCache], B, off, rows, H, Dh, 
                         stream=None) -> None:
     _check(_lib.dllava_prefill_attn(_p(Q), _p(K), _p(V), cache.ref if cache is not None else None, B, _p(off),
                                     rows, H, Dh, scale, _p(O), dtype, _stream(stream)))
+
+
+def dllava_decode_step_workspace(B: int, H: int, Dh: int, max_pages_per_seq: int, d: int, dh: int, dtype: int) -> int:
+    return int(_lib.dllava_decode_step_workspace(B, H, Dh, max_pages_per_seq, d, dh, dtype))
+
+
+def dllava_decode_step(x, ldx, d, dh, W1, b1, W2, b2, q, k_new, v_new, k_prev, v_prev, logits_prev,
+                       keep_prev_override, B, threshold, cache: KVCache, scale, o, logits, keep_prev_out, err_flag,
+                       workspace, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(_lib.dllava_decode_step(_p(x), ldx, d, dh, _p(W1), _p(b1), _p(W2), _p(b2), _p(q), _p(k_new), _p(v_new),
+                                   _p(k_prev), _p(v_prev), _p(logits_prev), _p(keep_prev_override), B, threshold,
+                                   cache.ref, scale, _p(o), _p(logits), _p(keep_prev_out), _p(err_flag), wp, wb,
+                                   _stream(stream)))
+
+
+def dllava_decode_commit(k_prev, v_prev, logits_prev, keep_prev_override, B, threshold, cache: KVCache, keep_out,
+                         err_flag, stream=None) -> None:
+    _check(_lib.dllava_decode_commit(_p(k_prev), _p(v_prev), _p(logits_prev), _p(keep_prev_override), B, threshold,
+                                     cache.ref, _p(keep_out), _p(err_flag), _stream(stream)))
 
 
 def dllava_qkv_project(x, ldx, rows, d, B, off, pos, Wq, Wk, Wv, rope_base, Q_out, cache: KVCache, err_flag, dtype,

@@ -25,6 +25,7 @@
 #include <limits.h>
 
 #include "attend.h"
+#include "score_splitk.h"
 
 namespace dllava {
 namespace {
@@ -56,6 +57,11 @@ struct DecodeArgs {
   void* o;
   uint8_t* keep_out;
   int32_t* err_flag;
+  // deferred form (dllava_decode_step): the tokens of the PREVIOUS step, whose keep decision is applied now
+  const void* k_prev;
+  const void* v_prev;
+  const float* logits_prev;
+  const uint8_t* keep_prev_override;
 };
 
 // ---- one 16-token page held in registers -------------------------------------------------------
@@ -199,8 +205,30 @@ __device__ __forceinline__ void commit_sequence(const DecodeArgs& a, int b) {
   if (tid == 0) a.cache_len[b] = L + 1;
 }
 
-// The work of block (s, h, b).
-template <typename T, int DH, int NW>
+// Keep decision of the previous step's token of sequence b (deferred form); false when there is none.
+__device__ __forceinline__ bool keep_prev_token(const DecodeArgs& a, int b) {
+  if (a.keep_prev_override) return a.keep_prev_override[b] != 0;
+  if (a.logits_prev) return keep_from_logits(a.logits_prev, b, a.threshold);
+  return false;
+}
+
+// Deferred form: every (b, h) block has appended its own head's slice of the previous token, so the block that
+// knows that all blocks of b have read cache_len[b] only moves the length (and reports decision and overflow).
+__device__ __forceinline__ void commit_length(const DecodeArgs& a, int b, bool keep_prev) {
+  if (threadIdx.x != 0) return;
+  if (a.keep_out && (a.logits_prev || a.keep_prev_override)) a.keep_out[b] = keep_prev ? 1 : 0;
+  if (!keep_prev) return;
+  const int L = a.cache_len[b];
+  if (L < 0 || L >= a.max_pages * kPage) {
+    if (a.err_flag) *a.err_flag = 1;
+    return;
+  }
+  a.cache_len[b] = L + 1;
+}
+
+// The work of block (s, h, b).  DEFER: the current token is not appended; instead the previous step's token is
+// (its decision is known by now), by every block for its own head, and attended as a second in-register key.
+template <typename T, int DH, int NW, bool DEFER>
 __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, int b) {
   using C = AttendCfg<T, DH>;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
@@ -223,6 +251,7 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
   int p = s * NW + w;
   int pg = bt[p < a.max_pages ? p : a.max_pages - 1];
   int L = a.cache_len[b];
+  const bool keep_prev = DEFER ? keep_prev_token(a, b) : false;  // block-uniform
   PageRegs<T, DH> cur;
   const bool spec = (S == 1);
   if (spec) {
@@ -233,6 +262,7 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
   // it cannot be issued before the load has returned; its own latency hides behind the page stream.
   int ticket = 0;
   if (tid == 0) ticket = add_agent(S == 1 ? &a.cnt_b[b * kCnt] : &a.cnt_bh[bh * kCnt], 1 + (L == INT32_MIN));
+  const bool append_prev = DEFER && keep_prev && L >= 0 && L < cap;  // the previous token goes to slot L
   L = L < 0 ? 0 : (L > cap ? cap : L);
   const int P = (L + kPage - 1) / kPage;
   if (!spec && p < P) {
@@ -253,7 +283,10 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
       sm_commit = commit;
     }
     __syncthreads();
-    if (sm_commit) commit_sequence<T, DH>(a, b);
+    if (sm_commit) {
+      if (DEFER) commit_length(a, b, keep_prev);
+      else commit_sequence<T, DH>(a, b);
+    }
   }
 
   LaneDot<T> qd;
@@ -269,6 +302,29 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
       st.m = d;
       st.l = 1.f;
       Elem<T>::unpack(vr, st.acc);
+    }
+    if (append_prev) {  // block-uniform
+      const T* kp = static_cast<const T*>(a.k_prev) + bh * DH;
+      const T* vp = static_cast<const T*>(a.v_prev) + bh * DH;
+      const uint4 kr2 = *reinterpret_cast<const uint4*>(kp + (lane % C::G) * C::E);
+      const uint4 vr2 = *reinterpret_cast<const uint4*>(vp + (lane % C::G) * C::E);
+      const int pgL = bt[L / kPage];  // L is the unclamped length here (append_prev implies 0 <= L < cap)
+      T* dstk = const_cast<T*>(pages) + (static_cast<size_t>(pgL) * 2 * H + h) * tile + static_cast<size_t>(L % kPage) * DH;
+      if (lane < C::G) {
+        *reinterpret_cast<uint4*>(dstk + lane * C::E) = kr2;
+        *reinterpret_cast<uint4*>(dstk + vofs + lane * C::E) = vr2;
+      }
+      const float d2 = row_group_sum<C::G>(qd.dot(kr2));
+      if (lane < C::G) {  // online-softmax fold of a second single key into lane group 0
+        float v2[C::E];
+        Elem<T>::unpack(vr2, v2);
+        const float m_new = fmaxf(st.m, d2);
+        const float a0 = __builtin_amdgcn_exp2f(st.m - m_new), p2 = __builtin_amdgcn_exp2f(d2 - m_new);
+        st.l = st.l * a0 + p2;
+#pragma unroll
+        for (int e = 0; e < C::E; ++e) st.acc[e] = st.acc[e] * a0 + p2 * v2[e];
+        st.m = m_new;
+      }
     }
   }
 
@@ -371,12 +427,43 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
 
   // The block that drew the last ticket of sequence b knows every block of b has read cache_len[b]: it alone
   // appends and advances the length.
-  if (S > 1 && sm_commit) commit_sequence<T, DH>(a, b);
+  if (S > 1 && sm_commit) {
+    if (DEFER) commit_length(a, b, keep_prev);
+    else commit_sequence<T, DH>(a, b);
+  }
 }
 
 template <typename T, int DH, int NW>
 __global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
-  attn_block<T, DH, NW>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+  attn_block<T, DH, NW, false>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// dllava_decode_step: one launch = the predictor scoring of the current tokens (first n_score blocks, split-K form of
+// score_splitk.h; NT = 0: no scoring blocks in this launch) + the deferred-append attention.  The two halves do
+// not depend on each other: the logits written here are read by the NEXT launch.
+// (Register budget: with at most 96 registers five waves fit a SIMD -- one scoring wave beside the two 8-wave
+// attention blocks of a compute unit -- so that the attention half starts at full occupancy; the scoring code for
+// up to 32 rows needs 122 registers: four waves.  For more rows it would leave two waves per SIMD, which costs the
+// attention half more than the second launch does: those sizes score in a launch of their own.)
+template <typename T, int DH, int NW, int NT>
+__global__ __launch_bounds__(NW * kWave, NT == 1 ? 5 : (NT == 2 ? 4 : 1)) void decode_step_kernel(DecodeArgs a, ScoreArgs sa, int G, int KS, int ppb,
+                                                                   int n_score) {
+  if constexpr (NT > 0) {
+    if (static_cast<int>(blockIdx.x) < n_score) {
+      // the scoring code runs on four waves and contains block barriers; the other waves end here (a barrier waits
+      // for the surviving waves of a block only)
+      if (threadIdx.x < kSpThreads) score_splitk_block<NT>(sa, G, KS, ppb, blockIdx.x);
+      return;
+    }
+  }
+  const int id = static_cast<int>(blockIdx.x) - n_score, S = a.n_split;
+  attn_block<T, DH, NW, true>(a, id % S, (id / S) % a.H, id / (S * a.H));
+}
+
+// appends the tokens of the last step whose decision is still outstanding (dllava_decode_commit)
+template <typename T, int DH>
+__global__ __launch_bounds__(256) void decode_commit_kernel(DecodeArgs a) {
+  commit_sequence<T, DH>(a, blockIdx.x);
 }
 
 struct DecodeShape {
@@ -461,6 +548,30 @@ int prepare(const char* who, const void* q, const void* k_new, const void* v_new
   return DLLAVA_OK;
 }
 
+template <typename T, int DH, int NW, int NT>
+int launch_step3(const DecodeArgs& a, const ScoreArgs& sa, const SplitPlan& p, hipStream_t st) {
+  const int n_score = NT > 0 ? p.G * p.KS : 0;
+  const int64_t blocks = static_cast<int64_t>(n_score) + static_cast<int64_t>(a.n_split) * a.H * a.B;
+  if (blocks > 0x7fffffffLL) DLLAVA_FAIL(DLLAVA_ESHAPE, "decode_step: too many blocks");
+  hipLaunchKernelGGL((decode_step_kernel<T, DH, NW, NT>), dim3(static_cast<unsigned>(blocks)), dim3(NW * kWave), 0, st, a,
+                     sa, p.G, p.KS, p.ppb, n_score);
+  DLLAVA_CHECK_LAUNCH("decode_step_kernel");
+  return DLLAVA_OK;
+}
+template <typename T, int DH, int NW>
+int launch_step2(const DecodeArgs& a, const ScoreArgs& sa, const SplitPlan& p, int nt, hipStream_t st) {
+  if constexpr (sizeof(T) == 2) {
+    if (nt == 1) return launch_step3<T, DH, NW, 1>(a, sa, p, st);
+    if (nt == 2) return launch_step3<T, DH, NW, 2>(a, sa, p, st);
+  }
+  return launch_step3<T, DH, NW, 0>(a, sa, p, st);
+}
+template <typename T, int DH>
+int launch_step(const DecodeArgs& a, const DecodeShape& sh, const ScoreArgs& sa, const SplitPlan& p, int nt,
+                hipStream_t st) {
+  return sh.nw == 8 ? launch_step2<T, DH, 8>(a, sa, p, nt, st) : launch_step2<T, DH, 4>(a, sa, p, nt, st);
+}
+
 }  // namespace
 }  // namespace dllava
 
@@ -481,7 +592,7 @@ extern "C" int dllava_decode_attn_append(const void* q, const void* k_new, const
   if (int rc = check_cache(cache, "decode")) return rc;
   if (B == 0) return DLLAVA_OK;
   DLLAVA_REQUIRE(logits || keep_override, DLLAVA_ENULL, "decode: need logits or keep_override");
-  DecodeArgs a;
+  DecodeArgs a{};
   DecodeShape sh;
   const size_t need = dllava_decode_workspace(B, cache->H, cache->Dh, cache->max_pages_per_seq);
   if (int rc = prepare("decode", q, k_new, v_new, B, logits, threshold, keep_override, cache, scale, o, keep_out,
@@ -491,4 +602,100 @@ extern "C" int dllava_decode_attn_append(const void* q, const void* k_new, const
   const bool bf = cache->dtype == DLLAVA_BF16;
   if (cache->Dh == 128) return bf ? launch<bf16_t, 128>(a, sh, st) : launch<float, 128>(a, sh, st);
   return bf ? launch<bf16_t, 64>(a, sh, st) : launch<float, 64>(a, sh, st);
+}
+
+extern "C" size_t dllava_decode_step_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pages_per_seq, int64_t d,
+                                               int64_t dh, int dtype) {
+  return round_up(dllava_decode_workspace(B, H, Dh, max_pages_per_seq), 256) +
+         round_up(dllava_score_workspace(B > 0 ? B : 1, d, dh, dtype), 256);
+}
+
+extern "C" int dllava_decode_step(const void* x, int64_t ldx, int64_t d, int64_t dh, const void* W1, const float* b1,
+                                  const void* W2, const float* b2, const void* q, const void* k_new,
+                                  const void* v_new, const void* k_prev, const void* v_prev,
+                                  const float* logits_prev, const uint8_t* keep_prev_override, int32_t B,
+                                  float threshold, const dllava_kv_cache* cache, float scale, void* o, float* logits,
+                                  uint8_t* keep_prev_out, int32_t* err_flag, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  DLLAVA_REQUIRE(B >= 0, DLLAVA_EINVAL, "decode_step: B = %d < 0", B);
+  if (int rc = check_cache(cache, "decode_step")) return rc;
+  if (B == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(x && W1 && W2 && logits, DLLAVA_ENULL, "decode_step: x, W1, W2 and logits are required");
+  const bool have_prev = logits_prev || keep_prev_override;
+  DLLAVA_REQUIRE(!have_prev || (k_prev && v_prev), DLLAVA_ENULL,
+                 "decode_step: k_prev and v_prev go with logits_prev / keep_prev_override");
+  DLLAVA_REQUIRE(aligned(k_prev, 16) && aligned(v_prev, 16), DLLAVA_EINVAL, "decode_step: k_prev, v_prev must be 16-byte aligned");
+  DLLAVA_REQUIRE(logits_prev != logits, DLLAVA_EINVAL, "decode_step: logits and logits_prev must be different buffers");
+  const int dtype = cache->dtype;
+  const size_t need_dec = round_up(dllava_decode_workspace(B, cache->H, cache->Dh, cache->max_pages_per_seq), 256);
+  const size_t need_score = round_up(dllava_score_workspace(B, d, dh, dtype), 256);
+  DecodeArgs a{};
+  DecodeShape sh;
+  if (int rc = prepare("decode_step", q, k_new, v_new, B, nullptr, threshold, nullptr, cache, scale, o, keep_prev_out,
+                       err_flag, workspace, workspace_bytes, need_dec + need_score, a, sh))
+    return rc;
+  a.k_prev = have_prev ? k_prev : nullptr;
+  a.v_prev = have_prev ? v_prev : nullptr;
+  a.logits_prev = logits_prev;
+  a.keep_prev_override = keep_prev_override;
+  void* ws_score = static_cast<char*>(workspace) + need_dec;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  // the scoring half rides in the same launch when the split-K form covers the shape; otherwise it is a launch of its own
+  ScoreArgs sa{x, ldx, B, d, dh, B, nullptr, nullptr, nullptr, W1, b1, W2, b2, logits, ws_score};
+  SplitPlan p = split_plan(d > 0 ? d : 64, dh > 0 ? dh : 1);
+  int nt = 0;
+  const bool bf = dtype == DLLAVA_BF16;
+  if (bf && B <= 64 && d > 0 && d % 64 == 0 && ldx >= d && ldx % 8 == 0 && dh >= 1 && p.G <= kSpMaxGroups && d <= 16384 &&
+      aligned(x, 16) && aligned(W1, 16))
+    nt = B <= 16 ? 1 : (B <= 32 ? 2 : 0);
+  if (nt > 0) {
+    // Inside the attention launch the scoring half is not latency-critical (it only has to finish before the
+    // attention does) but every one of its dependent trips to memory queues behind the K/V stream: fewer, longer
+    // slices of d (about 128 blocks instead of one per compute unit) were measured faster here.
+    const int npairs = static_cast<int>(d / 64);
+    int ks = 128 / p.G;
+    ks = ks < 1 ? 1 : (ks > kSpMaxSplit ? kSpMaxSplit : ks);
+    if (ks < p.KS) {
+      p.ppb = (npairs + ks - 1) / ks;
+      p.KS = (npairs + p.ppb - 1) / p.ppb;
+    }
+  }
+  if (nt == 0) {
+    if (int rc = dllava_score(x, ldx, B, 0, nullptr, nullptr, nullptr, d, dh, W1, b1, W2, b2, dtype, logits, ws_score,
+                              need_score, stream))
+      return rc;
+  }
+  if (cache->Dh == 128) return bf ? launch_step<bf16_t, 128>(a, sh, sa, p, nt, st) : launch_step<float, 128>(a, sh, sa, p, nt, st);
+  return bf ? launch_step<bf16_t, 64>(a, sh, sa, p, nt, st) : launch_step<float, 64>(a, sh, sa, p, nt, st);
+}
+
+extern "C" int dllava_decode_commit(const void* k_prev, const void* v_prev, const float* logits_prev,
+                                    const uint8_t* keep_prev_override, int32_t B, float threshold,
+                                    const dllava_kv_cache* cache, uint8_t* keep_out, int32_t* err_flag, void* stream) {
+  DLLAVA_REQUIRE(B >= 0, DLLAVA_EINVAL, "decode_commit: B = %d < 0", B);
+  if (int rc = check_cache(cache, "decode_commit")) return rc;
+  if (B == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(k_prev && v_prev && (logits_prev || keep_prev_override), DLLAVA_ENULL,
+                 "decode_commit: k_prev, v_prev and logits_prev or keep_prev_override are required");
+  DLLAVA_REQUIRE(threshold == threshold, DLLAVA_EINVAL, "decode_commit: threshold is NaN");
+  DLLAVA_REQUIRE(aligned(k_prev, 16) && aligned(v_prev, 16), DLLAVA_EINVAL, "decode_commit: k_prev, v_prev must be 16-byte aligned");
+  DecodeArgs a{};
+  a.k_new = k_prev; a.v_new = v_prev; a.logits = logits_prev; a.keep_override = keep_prev_override;
+  a.threshold = threshold;
+  a.pages = cache->pages; a.block_table = cache->block_table; a.cache_len = cache->cache_len;
+  a.max_pages = cache->max_pages_per_seq; a.H = cache->H; a.B = B;
+  a.keep_out = keep_out; a.err_flag = err_flag;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool bf = cache->dtype == DLLAVA_BF16;
+  const dim3 grid(static_cast<unsigned>(B)), block(256);
+  if (cache->Dh == 128) {
+    if (bf) hipLaunchKernelGGL((decode_commit_kernel<bf16_t, 128>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((decode_commit_kernel<float, 128>), grid, block, 0, st, a);
+  } else {
+    if (bf) hipLaunchKernelGGL((decode_commit_kernel<bf16_t, 64>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((decode_commit_kernel<float, 64>), grid, block, 0, st, a);
+  }
+  DLLAVA_CHECK_LAUNCH("decode_commit_kernel");
+  return DLLAVA_OK;
 }

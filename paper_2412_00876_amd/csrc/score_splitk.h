@@ -70,15 +70,16 @@ __device__ __forceinline__ sp_bf16x8 sp_frag(const uint4& v) {
   return c.f;
 }
 
+// The work of block `bid` of the G*KS blocks (threads 0..kSpThreads-1 of the calling block; the function contains
+// block barriers, so the block's other waves, if any, must have ended).
 // NT = 16-token column tiles (M <= 16*NT).  workspace = [accumulators | counters | partial tiles].
 template <int NT>
-__global__ __launch_bounds__(kSpThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void score_splitk_kernel(ScoreArgs a, int G, int KS,
-                                                                                                      int ppb) {
+__device__ __forceinline__ void score_splitk_block(const ScoreArgs& a, int G, int KS, int ppb, int bid) {
   constexpr int MP = 16 * NT;  // padded token count
   __shared__ float sm_p[kSpWaves][MP][2];
   __shared__ int sm_last;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-  const int g = blockIdx.x / KS, ks = blockIdx.x % KS;
+  const int g = bid / KS, ks = bid % KS;
   const int M = static_cast<int>(a.M);
   const int64_t d = a.d, dh = a.dh;
   const bf16_t* W1 = static_cast<const bf16_t*>(a.W1);
@@ -218,6 +219,12 @@ __global__ __launch_bounds__(kSpThreads) __attribute__((amdgpu_waves_per_eu(1, 2
       }
     }
   }
+}
+
+template <int NT>
+__global__ __launch_bounds__(kSpThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void score_splitk_kernel(ScoreArgs a, int G, int KS,
+                                                                                                      int ppb) {
+  score_splitk_block<NT>(a, G, KS, ppb, blockIdx.x);
 }
 
 }  // namespace dllava
