@@ -90,3 +90,38 @@ def test_deferred_step_decides_on_its_own_logits():
 def test_deferred_step_float32():
     w = W.make("stepf32", "f32", 128, 2, 64, 3, [4, 0, 19], 0, 0, 1.0, 5, project_qkv=True)
     _run(w, 5, 0.0, use_override=True)
+
+
+def test_deferred_step_at_cache_capacity():
+    """A kept token that finds its sequence full is neither stored nor attended by later steps, the flag is raised,
+    the length stays at the capacity: the same as the plain step."""
+    h = _H()
+    B, T = 3, 5
+    w = W.make("stepcap", "bf16", 256, 2, 128, B, [14, 16, 3], 0, 0, 1.0, T, project_qkv=True)
+    pre, dec, pred = W.prefill_inputs(w), W.decode_inputs(w, T), W.predictor(w)
+    bt = np.array([[2], [0], [1]], np.int32)        # one page = 16 slots per sequence
+    g = h.GpuPath(w, pre, pred, n_pages=3, bt=bt)
+    D0 = np.zeros((1, 2), np.float32)
+    g.select_compact(torch.from_numpy(D0).to(h.DEV), with_hidden=False)
+    mask, idx, off = R.select(D0, w.seq_off, w.vis_start, w.vis_len, R.TOPK, w.keep_ratio, 0.0)
+    cache = R.PagedCache(3, bt, w.H, w.Dh, w.dtype)
+    R.compact(idx, off, w.seq_off, Q=pre["Q"], K=pre["K"], V=pre["V"], cache=cache)
+    ws = torch.zeros(P.dllava_decode_step_workspace(B, w.H, w.Dh, 1, w.d, w.dh, g.code), dtype=torch.uint8, device=h.DEV)
+    dev = {n: h.to_dev(dec[n], w.dtype) for n in ("x", "q", "k", "v")}
+    logits = torch.zeros((T, B, 2), dtype=torch.float32, device=h.DEV)
+    ones = torch.ones(B, dtype=torch.uint8, device=h.DEV)     # every token is kept
+    p = g.pred
+    any_err = False
+    for t in range(T):
+        o = torch.zeros((B, w.H, w.Dh), dtype=torch.bfloat16, device=h.DEV)
+        prev = t > 0
+        P.dllava_decode_step(dev["x"][t], w.d, w.d, w.dh, p["W1"], p["b1"], p["W2"], p["b2"], dev["q"][t], dev["k"][t],
+                             dev["v"][t], dev["k"][t - 1] if prev else None, dev["v"][t - 1] if prev else None, None,
+                             ones if prev else None, B, 0.0, g.cache, g.scale, o, logits[t], None, g.err, ws)
+        o_ref, err = R.decode_attn_append(dec["q"][t], dec["k"][t], dec["v"][t], np.ones(B, np.uint8), cache, g.scale)
+        any_err = any_err or bool(err.any())
+        _assert_out_close(h.as_f64(o), o_ref, w.dtype, f"step {t}")
+    P.dllava_decode_commit(dev["k"][T - 1], dev["v"][T - 1], None, ones, B, 0.0, g.cache, None, g.err)
+    assert any_err and int(g.err.item()) == 1
+    assert g.cache_len.cpu().numpy().tolist() == [16, 16, 8] and cache.cache_len.tolist() == [16, 16, 8]
+    assert np.array_equal(h.bits(g.pages), cache.pages)

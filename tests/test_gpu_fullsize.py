@@ -127,3 +127,57 @@ def test_decode_step_at_final_context_length(ci):
     for b, hd in pairs:
         _assert_out_close(oh[b, hd], o_ref[b, hd], w.dtype, f"b={b} h={hd}")
     assert np.array_equal(h.bits(g.pages), cache.pages)
+
+
+@pytest.mark.parametrize("ci", [2, 3, 4])
+def test_deferred_decode_steps_at_final_context_length(ci):
+    """dllava_decode_step in the benchmark's launch configuration (scoring blocks + attention blocks in one launch), at
+    the cache length the configuration reaches at its end: three steps and the final commit, outputs of sampled
+    (sequence, head) pairs and all logits against the oracle's plain Eq. 6 loop, the cache bit for bit."""
+    import paper_2412_00876_amd as P
+    h = _H()
+    w = W.config(ci)
+    rs = np.random.RandomState(300 + ci)
+    T = 3
+    L_end = w.kept_len[0] + w.T // 2
+    lens = np.array([L_end - int(rs.randint(0, 40)) for _ in range(w.B)], np.int32)
+    bt, n_pages = W.block_table(w)
+    pred = W.predictor(w)
+    g = h.GpuPath(w, None, pred, n_pages=n_pages, bt=bt)
+    pages_np = W.store(rng.normal(w.seed, "final.pages", (n_pages, 2, w.H, 16, w.Dh)), w.dtype)
+    g.pages.copy_(h.to_dev(pages_np, w.dtype))
+    g.cache_len.copy_(torch.from_numpy(lens))
+    cache = R.PagedCache(n_pages, bt, w.H, w.Dh, w.dtype)
+    cache.pages[...] = pages_np
+    cache.cache_len[...] = lens
+    dec = W.decode_inputs(w, T)
+    dev = {n: h.to_dev(dec[n], w.dtype) for n in ("x", "q", "k", "v")}
+    ws = torch.zeros(P.dllava_decode_step_workspace(w.B, w.H, w.Dh, g.cache.max_pages_per_seq, w.d, w.dh, g.code),
+                     dtype=torch.uint8, device=h.DEV)
+    logits = torch.zeros((T, w.B, 2), dtype=torch.float32, device=h.DEV)
+    keep_out = torch.full((T, w.B), 255, dtype=torch.uint8, device=h.DEV)
+    pairs = [(int(rs.randint(w.B)), int(rs.randint(w.H))) for _ in range(8)] + [(0, 0), (w.B - 1, w.H - 1)]
+    p = g.pred
+    theta = 0.0
+    for t in range(T):
+        o = torch.zeros((w.B, w.H, w.Dh), dtype=h.tdtype(w.dtype), device=h.DEV)
+        prev = t > 0
+        P.dllava_decode_step(dev["x"][t], w.d, w.d, w.dh, p["W1"], p["b1"], p["W2"], p["b2"], dev["q"][t], dev["k"][t],
+                             dev["v"][t], dev["k"][t - 1] if prev else None, dev["v"][t - 1] if prev else None,
+                             logits[t - 1] if prev else None, None, w.B, theta, g.cache, g.scale, o, logits[t],
+                             keep_out[t - 1] if prev else None, g.err, ws)
+        Dg = logits[t].cpu().numpy()
+        Dr = R.score(dec["x"][t], pred["W1"], pred["b1"], pred["W2"], pred["b2"], w.dtype)
+        assert np.abs(Dg - Dr).max() <= TOL
+        keep_ref = R.decode_keep(Dg, theta)          # decisions from the GPU's logits on both sides
+        o_ref, err = R.decode_attn_append(dec["q"][t], dec["k"][t], dec["v"][t], keep_ref, cache, g.scale, only=pairs)
+        assert not err.any()
+        oh = h.as_f64(o)
+        for b, hd in pairs:
+            _assert_out_close(oh[b, hd], o_ref[b, hd], w.dtype, f"deferred t={t} b={b} h={hd}")
+        if prev:
+            assert np.array_equal(keep_out[t - 1].cpu().numpy(), R.decode_keep(logits[t - 1].cpu().numpy(), theta))
+    P.dllava_decode_commit(dev["k"][T - 1], dev["v"][T - 1], logits[T - 1], None, w.B, theta, g.cache, keep_out[T - 1], g.err)
+    assert int(g.err.item()) == 0
+    assert np.array_equal(g.cache_len.cpu().numpy(), cache.cache_len)
+    assert np.array_equal(h.bits(g.pages), cache.pages)
