@@ -38,12 +38,15 @@ def test_every_declared_symbol_is_exported(lib):
 def test_version_and_workspace_queries(lib):
     assert lib.dllava_version() >= 100
     for q in (lib.dllava_score_workspace(16, 4096, 1024, lib.BF16), lib.dllava_score_workspace(9216, 4096, 1024, lib.BF16),
-              lib.dllava_select_compact_workspace(16, 10800), lib.dllava_decode_workspace(16, 32, 128, 78)):
+              lib.dllava_select_compact_workspace(16, 10800), lib.dllava_decode_workspace(16, 32, 128, 78),
+              lib.dllava_decode_step_workspace(16, 32, 128, 78, 4096, 1024, lib.BF16)):
         assert q > 0 and q % 256 == 0
     # monotone in the problem size
     assert lib.dllava_select_compact_workspace(16, 20000) > lib.dllava_select_compact_workspace(16, 10000)
     assert lib.dllava_decode_workspace(32, 40, 128, 50) > lib.dllava_decode_workspace(16, 32, 128, 50)
     assert lib.dllava_score_workspace(0, 4096, 1024, lib.BF16) >= 256
+    assert lib.dllava_decode_step_workspace(16, 32, 128, 78, 4096, 1024, lib.BF16) >= \
+        lib.dllava_decode_workspace(16, 32, 128, 78) + lib.dllava_score_workspace(16, 4096, 1024, lib.BF16)
 
 
 def _expect(lib, status, fn, *args):
@@ -83,6 +86,30 @@ def test_argument_errors_are_reported_on_the_host(lib):
     _expect(lib, EWORKSPACE, L.dllava_decode_attn_append, fake, fake, fake, 2, fake, 0.0, None, C.byref(cache), 0.1, fake, None, None, fake, 64, None)
     _expect(lib, ENULL, L.dllava_decode_attn_append, fake, fake, fake, 2, fake, 0.0, None, None, 0.1, fake, None, None, fake, 1 << 24, None)
     _expect(lib, EINVAL, L.dllava_decode_attn_append, fake, fake, fake, 2, fake, float("nan"), None, C.byref(cache), 0.1, fake, None, None, fake, 1 << 24, None)
+    # decode, one-launch form: (x, ldx, d, dh, W1, b1, W2, b2, q, k, v, k_prev, v_prev, logits_prev, keep_prev_override, B, threshold,
+    #                           cache, scale, o, logits, keep_prev_out, err_flag, workspace, bytes, stream)
+    step = lambda **kw: tuple({**dict(x=fake, ldx=64, d=64, dh=16, W1=fake, b1=None, W2=fake, b2=None, q=fake, k=fake, v=fake,
+                                      kp=None, vp=None, lp=None, ov=None, B=2, thr=0.0, cache=C.byref(cache), scale=0.1, o=fake,
+                                      logits=fake, ko=None, err=None, ws=fake, wsb=1 << 24, st=None), **kw}.values())
+    _expect(lib, ENULL, L.dllava_decode_step, *step(x=None))
+    _expect(lib, ENULL, L.dllava_decode_step, *step(logits=None))
+    _expect(lib, ENULL, L.dllava_decode_step, *step(lp=C.c_void_p(0x2000)))                 # previous logits without previous K/V
+    _expect(lib, EINVAL, L.dllava_decode_step, *step(kp=fake, vp=fake, lp=fake))            # logits_prev == logits
+    _expect(lib, EWORKSPACE, L.dllava_decode_step, *step(wsb=64))
+    _expect(lib, ENULL, L.dllava_decode_step, *step(cache=None))
+    _expect(lib, EINVAL, L.dllava_decode_step, *step(scale=0.0))
+    _expect(lib, ENULL, L.dllava_decode_commit, fake, fake, None, None, 2, 0.0, C.byref(cache), None, None, None)
+    _expect(lib, EINVAL, L.dllava_decode_commit, fake, fake, fake, None, 2, float("nan"), C.byref(cache), None, None, None)
+    # projection: (x, ldx, rows, d, B, off, pos, Wq, Wk, Wv, rope_base, Q_out, cache, err_flag, dtype, stream)
+    proj = lambda **kw: tuple({**dict(x=fake, ldx=64, rows=8, d=64, B=2, off=fake, pos=fake, Wq=fake, Wk=fake, Wv=fake, base=10000.0,
+                                      Q=fake, cache=C.byref(cache), err=None, dtype=1, st=None), **kw}.values())
+    _expect(lib, ENULL, L.dllava_qkv_project, *proj(Wk=None))
+    _expect(lib, ENULL, L.dllava_qkv_project, *proj(pos=None))                              # rotation asked for, no positions
+    _expect(lib, EDTYPE, L.dllava_qkv_project, *proj(dtype=0))                              # cache is bfloat16
+    _expect(lib, ESHAPE, L.dllava_qkv_project, *proj(d=60, ldx=60))
+    _expect(lib, EINVAL, L.dllava_qkv_project, *proj(ldx=32))
+    _expect(lib, EINVAL, L.dllava_qkv_project, *proj(base=float("nan")))
+    _expect(lib, ENULL, L.dllava_qkv_project, *proj(cache=None))
 
 
 def test_noop_sizes_return_ok_without_a_gpu(lib):
@@ -92,6 +119,8 @@ def test_noop_sizes_return_ok_without_a_gpu(lib):
     cache = lib._KvCache(0x1000, 0x1000, 0x1000, 4, 2, 16, 2, 64, 1)
     assert L.dllava_decode_attn_append(fake, fake, fake, 0, fake, 0.0, None, C.byref(cache), 0.1, fake, None, None, None, 0, None) == 0
     assert L.dllava_prefill_attn(fake, fake, fake, None, 0, fake, 0, 2, 64, 0.1, fake, 1, None) == 0
+    assert L.dllava_qkv_project(fake, 64, 0, 64, 2, fake, fake, fake, fake, fake, 10000.0, fake, C.byref(cache), None, 1, None) == 0
+    assert L.dllava_decode_commit(fake, fake, fake, None, 0, 0.0, C.byref(cache), None, None, None) == 0
 
 
 def test_product_path_has_no_cpu_fallback():
