@@ -359,6 +359,9 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
   for (int t = 0; t < n_tiles; ++t) {
     // This wave's own loads of tile t are waited for (those of tile t+1, issued later, may stay in flight), then
     // the barrier makes every wave's part of the tile visible and says that all waves have left tile t-1.
+    // The count assumes that the tile loads are the only vector-memory operations issued inside the loop: the
+    // kernel must not spill registers (scratch traffic would be counted too); the build's resource report is
+    // checked for that by the tests.
     if (t + 1 < n_tiles)
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * D::kLoads) : "memory");
     else

@@ -141,3 +141,24 @@ def test_build_module_imports_without_loading_the_library():
             "assert 'paper_2412_00876_amd.binding' not in sys.modules; assert callable(b.build); print('ok')")
     out = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True)
     assert out.returncode == 0 and out.stdout.strip() == "ok", out.stderr
+
+
+def test_prefill_kernel_does_not_spill():
+    """The matrix-core prefill kernel waits for its asynchronous tile loads with explicit counts of outstanding
+    vector-memory operations; register spills inside its loop would add scratch traffic to that count.  The
+    compiler's resource report must show no scratch memory for any variant of the kernel."""
+    import subprocess
+    from paper_2412_00876_amd import build
+    src = os.path.join(build.CSRC, "prefill_mfma.hip")
+    cmd = [build.HIPCC, "-O3", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", build.CSRC, "--offload-arch=gfx950",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Rpass-analysis=kernel-resource-usage",
+           "--cuda-device-only", "-c", src, "-o", os.devnull]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    names = re.findall(r"Function Name: (\S*prefill_mfma_kernel\S*)", r.stderr)
+    scratch = re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", r.stderr)
+    assert len(names) >= 6 and len(scratch) == len(re.findall(r"Function Name:", r.stderr))
+    blocks = r.stderr.split("Function Name: ")[1:]
+    for b in blocks:
+        if "prefill_mfma_kernel" in b.split()[0]:
+            assert re.search(r"ScratchSize \[bytes/lane\]: 0\b", b), b[:400]
