@@ -226,6 +226,8 @@ size_t dllava_decode_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pag
  *   err_flag     as in dllava_decode_attn_append (a kept previous token that finds its sequence at capacity is
  *                neither stored nor attended)
  *   workspace    dllava_decode_step_workspace(...) bytes, zero-filled once, private to this entry point
+ * The single launch covers bfloat16 with B <= 64 and d % 64 == 0; other shapes run the predictor as a launch of its
+ * own in front (same results).
  */
 int dllava_decode_step(const void* x, int64_t ldx, int64_t d, int64_t dh,
                        const void* W1, const float* b1, const void* W2, const float* b2,

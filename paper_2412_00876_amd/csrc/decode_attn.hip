@@ -443,16 +443,26 @@ __global__ __launch_bounds__(NW * kWave) void decode_attn_kernel(DecodeArgs a) {
 // not depend on each other: the logits written here are read by the NEXT launch.
 // (Register budget: with at most 96 registers five waves fit a SIMD -- one scoring wave beside the two 8-wave
 // attention blocks of a compute unit -- so that the attention half starts at full occupancy; the scoring code for
-// up to 32 rows needs 122 registers: four waves.  For more rows it would leave two waves per SIMD, which costs the
-// attention half more than the second launch does: those sizes score in a launch of their own.)
+// up to 32 rows needs 122 registers: four waves.  The code for 64 rows would leave two waves per SIMD, which costs the
+// attention half more than reading W1 twice does: 33..64 rows are scored as two groups of blocks.)
 template <typename T, int DH, int NW, int NT>
 __global__ __launch_bounds__(NW * kWave, NT == 1 ? 5 : (NT == 2 ? 4 : 1)) void decode_step_kernel(DecodeArgs a, ScoreArgs sa, int G, int KS, int ppb,
-                                                                   int n_score) {
+                                                                   int n_score, size_t ws_group_stride) {
   if constexpr (NT > 0) {
     if (static_cast<int>(blockIdx.x) < n_score) {
       // the scoring code runs on four waves and contains block barriers; the other waves end here (a barrier waits
       // for the surviving waves of a block only)
-      if (threadIdx.x < kSpThreads) score_splitk_block<NT>(sa, G, KS, ppb, blockIdx.x);
+      if (threadIdx.x >= kSpThreads) return;
+      // Rows are scored in groups of 16*NT (more rows per block would cost registers, see above): group gi has its own
+      // blocks, its own slice of x and of the logits, and its own workspace region.
+      const int per_group = G * KS, gi = static_cast<int>(blockIdx.x) / per_group;
+      const int64_t r0 = static_cast<int64_t>(gi) * 16 * NT;
+      ScoreArgs sg = sa;
+      sg.x = static_cast<const char*>(sa.x) + r0 * sa.ldx * static_cast<int64_t>(sizeof(bf16_t));
+      sg.logits = sa.logits + 2 * r0;
+      sg.M = sa.M - r0 < 16 * NT ? sa.M - r0 : 16 * NT;
+      sg.workspace = static_cast<char*>(sa.workspace) + static_cast<size_t>(gi) * ws_group_stride;
+      score_splitk_block<NT>(sg, G, KS, ppb, static_cast<int>(blockIdx.x) % per_group);
       return;
     }
   }
@@ -550,11 +560,12 @@ int prepare(const char* who, const void* q, const void* k_new, const void* v_new
 
 template <typename T, int DH, int NW, int NT>
 int launch_step3(const DecodeArgs& a, const ScoreArgs& sa, const SplitPlan& p, hipStream_t st) {
-  const int n_score = NT > 0 ? p.G * p.KS : 0;
+  const int n_groups = NT > 0 ? static_cast<int>(ceil_div(a.B, 16 * NT)) : 0;  // row groups of the scoring half
+  const int n_score = n_groups * p.G * p.KS;
   const int64_t blocks = static_cast<int64_t>(n_score) + static_cast<int64_t>(a.n_split) * a.H * a.B;
   if (blocks > 0x7fffffffLL) DLLAVA_FAIL(DLLAVA_ESHAPE, "decode_step: too many blocks");
   hipLaunchKernelGGL((decode_step_kernel<T, DH, NW, NT>), dim3(static_cast<unsigned>(blocks)), dim3(NW * kWave), 0, st, a,
-                     sa, p.G, p.KS, p.ppb, n_score);
+                     sa, p.G, p.KS, p.ppb, n_score, NT > 0 ? round_up(split_workspace(16 * NT, sa.d, sa.dh), 256) : size_t{0});
   DLLAVA_CHECK_LAUNCH("decode_step_kernel");
   return DLLAVA_OK;
 }
@@ -606,8 +617,10 @@ extern "C" int dllava_decode_attn_append(const void* q, const void* k_new, const
 
 extern "C" size_t dllava_decode_step_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pages_per_seq, int64_t d,
                                                int64_t dh, int dtype) {
-  return round_up(dllava_decode_workspace(B, H, Dh, max_pages_per_seq), 256) +
-         round_up(dllava_score_workspace(B > 0 ? B : 1, d, dh, dtype), 256);
+  // the scoring half may run as two row groups with a workspace region each
+  const size_t two_groups = (dtype == DLLAVA_BF16 && d > 0 && dh > 0) ? 2 * round_up(split_workspace(32, d, dh), 256) : 0;
+  const size_t score = round_up(dllava_score_workspace(B > 0 ? B : 1, d, dh, dtype), 256);
+  return round_up(dllava_decode_workspace(B, H, Dh, max_pages_per_seq), 256) + (score > two_groups ? score : two_groups);
 }
 
 extern "C" int dllava_decode_step(const void* x, int64_t ldx, int64_t d, int64_t dh, const void* W1, const float* b1,
@@ -628,7 +641,7 @@ extern "C" int dllava_decode_step(const void* x, int64_t ldx, int64_t d, int64_t
   DLLAVA_REQUIRE(logits_prev != logits, DLLAVA_EINVAL, "decode_step: logits and logits_prev must be different buffers");
   const int dtype = cache->dtype;
   const size_t need_dec = round_up(dllava_decode_workspace(B, cache->H, cache->Dh, cache->max_pages_per_seq), 256);
-  const size_t need_score = round_up(dllava_score_workspace(B, d, dh, dtype), 256);
+  const size_t need_score = dllava_decode_step_workspace(B, cache->H, cache->Dh, cache->max_pages_per_seq, d, dh, dtype) - need_dec;
   DecodeArgs a{};
   DecodeShape sh;
   if (int rc = prepare("decode_step", q, k_new, v_new, B, nullptr, threshold, nullptr, cache, scale, o, keep_prev_out,
@@ -648,7 +661,7 @@ extern "C" int dllava_decode_step(const void* x, int64_t ldx, int64_t d, int64_t
   const bool bf = dtype == DLLAVA_BF16;
   if (bf && B <= 64 && d > 0 && d % 64 == 0 && ldx >= d && ldx % 8 == 0 && dh >= 1 && p.G <= kSpMaxGroups && d <= 16384 &&
       aligned(x, 16) && aligned(W1, 16))
-    nt = B <= 16 ? 1 : (B <= 32 ? 2 : 0);
+    nt = B <= 16 ? 1 : 2;  // up to 64 rows: one or two groups of at most 32
   if (nt > 0) {
     // Inside the attention launch the scoring half is not latency-critical (it only has to finish before the
     // attention does) but every one of its dependent trips to memory queues behind the K/V stream: fewer, longer

@@ -76,6 +76,8 @@ def _run(w, T, theta, use_override, extra_tokens=None):
 @pytest.mark.parametrize("B,H,Dh,d", [(16, 4, 128, 512),     # fused launch, one column tile of tokens
                                       (20, 2, 128, 256),     # two column tiles
                                       (3, 5, 64, 192),       # the smaller head size, odd head count
+                                      (40, 2, 128, 256),     # two row groups of scoring blocks (32 + 8 rows)
+                                      (64, 1, 128, 128),     # two full row groups
                                       (70, 2, 128, 256)])    # more rows than the fused scoring takes: two launches
 def test_deferred_step_matches_eq6_with_forced_decisions(B, H, Dh, d):
     w = W.make("step", "bf16", d, H, Dh, B, [5 + (7 * b) % 40 for b in range(B)], 0, 0, 1.0, 6, project_qkv=True)
