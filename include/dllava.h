@@ -105,6 +105,8 @@ const char* dllava_last_error(void);
  *   W1 [dh, d] dtype, W2 [2, dh] dtype;  b1 [dh], b2 [2] float32, either may be NULL (= 0)
  *   logits   [M, 2] float32, out
  * Sizes: d % 8 == 0, 1 <= dh, M >= 0 (M == 0 is a no-op).
+ * dllava_score_workspace is non-decreasing in M: a workspace sized for the largest row count
+ * serves every smaller one (same d, dh, dtype).
  */
 int dllava_score(const void* x, int64_t ldx, int64_t M,
                  int32_t B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_len,

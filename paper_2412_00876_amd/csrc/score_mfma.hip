@@ -149,11 +149,13 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
 }  // namespace
 
 size_t score_mfma_workspace(int64_t M, int64_t d, int64_t dh) {
-  (void)d;
-  size_t part;
-  if (M <= 64) return round_up(split_workspace(M, d, dh), 256);
-  part = static_cast<size_t>(ceil_div(dh, kTU)) * M * 2 * sizeof(float);
-  return kCounterBytes + round_up(part, 256);
+  // Non-decreasing in M, so a workspace sized for the largest row count serves every smaller one: the split-K form
+  // of at most 64 rows needs more than the GEMM form of a few hundred.
+  const size_t small = round_up(split_workspace(M < 64 ? M : 64, d, dh), 256);
+  if (M <= 64) return small;
+  const size_t part = static_cast<size_t>(ceil_div(dh, kTU)) * M * 2 * sizeof(float);
+  const size_t gemm = kCounterBytes + round_up(part, 256);
+  return gemm > small ? gemm : small;
 }
 
 // returns 1 if the shape is not handled here

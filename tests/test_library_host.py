@@ -162,3 +162,10 @@ def test_prefill_kernel_does_not_spill():
     for b in blocks:
         if "prefill_mfma_kernel" in b.split()[0]:
             assert re.search(r"ScratchSize \[bytes/lane\]: 0\b", b), b[:400]
+
+
+def test_score_workspace_is_monotonic_in_rows(lib):
+    """A workspace sized for the largest row count must serve every smaller one."""
+    for d, dh in ((4096, 1024), (256, 64), (64, 1)):
+        sizes = [lib.dllava_score_workspace(m, d, dh, lib.BF16) for m in (1, 16, 17, 64, 65, 200, 5000, 100000)]
+        assert sizes == sorted(sizes), (d, dh, sizes)
