@@ -172,6 +172,33 @@ def predictor(w: Workload, random_bias: bool = False) -> Dict[str, np.ndarray]:
     return {"W1": store(W1, w.dtype), "b1": b1, "W2": store(W2, w.dtype), "b2": b2}
 
 
+def paper_predictor(w: Workload, n_blocks: int, name: str = "ppred") -> Dict:
+    """Weights of a predictor in the appendix's form (Appendix A.4.1): d -> 512, n_blocks transformer blocks
+    (width 512, MLP 2048), head 512 -> 256 -> 128 -> 2.  Xavier-uniform matrices in storage dtype; float32
+    biases in [-0.1, 0.1], LayerNorm scales in [0.9, 1.1] and shifts in [-0.1, 0.1] (all seeded)."""
+    def mat(tag, fo, fi):
+        return store(_xavier(w.seed, f"{name}.{tag}", fo, fi), w.dtype)
+
+    def vec(tag, n, lo=-0.1, hi=0.1):
+        return rng.uniform(w.seed, f"{name}.{tag}", (n,), lo, hi).astype(np.float32)
+
+    P = {"W_in": mat("W_in", 512, w.d), "b_in": vec("b_in", 512), "blocks": []}
+    for i in range(n_blocks):
+        t = f"blk{i}."
+        P["blocks"].append({
+            "ln1_g": vec(t + "ln1_g", 512, 0.9, 1.1), "ln1_b": vec(t + "ln1_b", 512),
+            "Wqkv": mat(t + "Wqkv", 1536, 512), "bqkv": vec(t + "bqkv", 1536),
+            "Wo": mat(t + "Wo", 512, 512), "bo": vec(t + "bo", 512),
+            "ln2_g": vec(t + "ln2_g", 512, 0.9, 1.1), "ln2_b": vec(t + "ln2_b", 512),
+            "Wfc1": mat(t + "Wfc1", 2048, 512), "bfc1": vec(t + "bfc1", 2048),
+            "Wfc2": mat(t + "Wfc2", 512, 2048), "bfc2": vec(t + "bfc2", 512),
+        })
+    P["W_h1"], P["b_h1"] = mat("W_h1", 256, 512), vec("b_h1", 256)
+    P["W_h2"], P["b_h2"] = mat("W_h2", 128, 256), vec("b_h2", 128)
+    P["W_h3"], P["b_h3"] = mat("W_h3", 2, 128), vec("b_h3", 2)
+    return P
+
+
 def _hidden(w: Workload, name: str, rows: int, unit_scale: bool) -> np.ndarray:
     g = _normal_big(w.seed, name, (rows, w.d))
     if not unit_scale:
