@@ -10,6 +10,7 @@
  *   dllava_decode_attn_append  decode step with online KV-cache reduction  (Eq. 6)
  *   dllava_decode_step         the same step, scoring + attention in one launch, append deferred by one step
  *   dllava_qkv_project         Q, K, V of the reduced set, K/V into the cache (Eq. 3 line 1 with S^{P*})
+ *   dllava_predict             predictor logits with the predictors of Appendix A.4.1 (in place of dllava_score)
  *
  * General conventions
  *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller
@@ -279,6 +280,85 @@ int dllava_qkv_project(const void* x, int64_t ldx, int64_t rows, int64_t d,
                        const void* Wq, const void* Wk, const void* Wv, float rope_base,
                        void* Q_out, const dllava_kv_cache* cache, int32_t* err_flag,
                        int dtype, void* stream);
+
+/*
+ * Predictors in the form of the paper's appendix (Appendix A.4.1, "Details of Predictor Architecture"):
+ * one linear layer reduces the decoder width d to 512; the IMAGE predictor then runs n_blocks = 2
+ * vision-transformer blocks over the image tokens of each sequence, the OUTPUT-TEXT predictor none
+ * (n_blocks = 0: every row on its own); both end in the MLP 512 -> 256 -> 128 -> 2.  dllava_score is the
+ * simplified two-layer form of the same step; the logits have the same meaning (column 1 = keep) and feed
+ * dllava_select_compact / the decode steps unchanged.
+ *
+ * What the appendix leaves open is read as follows (all widths fixed):
+ *   z   = x W_in^T + b_in                                          [M, 512], no activation
+ *   per block (pre-norm):   z += MHA(LN1(z)) Wo^T + bo ,   z += GELU(LN2(z) Wfc1^T + bfc1) Wfc2^T + bfc2
+ *       LN: per row, biased variance, eps 1e-6, scale g and shift b;  MHA: q|k|v = y Wqkv^T + bqkv (q first),
+ *       8 heads of 64, softmax(q k^T / 8) v over ALL image tokens of the same sequence, no causal mask,
+ *       no tokens of other sequences, no position term;  MLP width 2048;  exact (erf) GELU
+ *   D   = GELU(GELU(z W_h1^T + b_h1) W_h2^T + b_h2) W_h3^T + b_h3   [M, 2]
+ * Every tensor written between two layers (z, LN outputs, q/k/v, attention output, hidden activations) is
+ * stored in dtype (rounded to nearest even); sums are float32; logits are float32.
+ *
+ * All matrices are [out, in] row-major in dtype, 16-byte aligned; vectors are float32 and may be NULL (= 0
+ * for biases and LayerNorm shifts, = 1 for LayerNorm scales).
+ */
+typedef struct dllava_vit_block {
+  const float* ln1_g; const float* ln1_b;   /* [512] */
+  const void* Wqkv; const float* bqkv;      /* [1536, 512], [1536]: rows 0..511 q, 512..1023 k, 1024..1535 v */
+  const void* Wo; const float* bo;          /* [512, 512], [512] */
+  const float* ln2_g; const float* ln2_b;   /* [512] */
+  const void* Wfc1; const float* bfc1;      /* [2048, 512], [2048] */
+  const void* Wfc2; const float* bfc2;      /* [512, 2048], [512] */
+} dllava_vit_block;
+
+#define DLLAVA_PREDICTOR_MAX_BLOCKS 4
+typedef struct dllava_predictor {
+  int64_t d;                                 /* input width; d % 64 == 0 */
+  int32_t n_blocks;                          /* 0 .. DLLAVA_PREDICTOR_MAX_BLOCKS */
+  const void* W_in; const float* b_in;       /* [512, d], [512] */
+  dllava_vit_block blocks[DLLAVA_PREDICTOR_MAX_BLOCKS];
+  const void* W_h1; const float* b_h1;       /* [256, 512], [256] */
+  const void* W_h2; const float* b_h2;       /* [128, 256], [128] */
+  const void* W_h3; const float* b_h3;       /* [2, 128], [2] */
+} dllava_predictor;
+
+/*
+ *   x, ldx, M, B, seq_off, vis_start, vis_len, logits
+ *            as in dllava_score: with seq_off the vision spans are scored (M = sum_b vis_len[b]) and, when
+ *            n_blocks > 0, the rows of one span attend to one another; with seq_off == NULL rows 0..M-1 of x
+ *            are scored and, when n_blocks > 0, form ONE span.
+ *   p        host struct (device pointers inside), read during the call only
+ *   dtype    DLLAVA_BF16 only (DLLAVA_EDTYPE otherwise)
+ *   workspace  device, 256-byte aligned, dllava_predict_workspace(M, B, n_blocks) bytes; contents need not
+ *            be initialised and are scratch (about 9.3 KB per row)
+ * Sizes: ldx % 8 == 0, M < 2^31.  M == 0 is a no-op.
+ */
+int dllava_predict(const void* x, int64_t ldx, int64_t M,
+                   int32_t B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_len,
+                   const dllava_predictor* p, int dtype, float* logits,
+                   void* workspace, size_t workspace_bytes, void* stream);
+size_t dllava_predict_workspace(int64_t M, int32_t B, int32_t n_blocks);
+
+/*
+ * The layers dllava_predict is made of, as calls of their own (Appendix A.4.1 names the layers; the formulas are
+ * the ones stated above).  DLLAVA_BF16 only; float32 sums; each output element is rounded once.
+ *
+ * dllava_linear:        y = act(x W^T + bias) + residual
+ *   x [M, K] row stride ldx;  W [N, K];  bias [N] float32 or NULL;  act 0 = none, 1 = exact GELU;
+ *   residual [M, N] with y's row stride, or NULL, may be y itself;  y [M, N] row stride ldy, out.
+ *   Sizes: K % 64 == 0, N % 8 == 0, ldx % 8 == 0, ldy % 8 == 0; pointers 16-byte aligned.
+ * dllava_layer_norm: y = (z - mean) / sqrt(var + 1e-6) * gamma + beta per row of 512 (biased variance);
+ *   z, y [M, 512] contiguous;  gamma, beta [512] float32 or NULL (1 and 0).
+ * dllava_span_attn:     O_i = softmax_j(scale * q_i . k_j) V over ALL rows j of the span of row i (no causal
+ *   mask);  Q, K, V, O [rows, H, Dh] contiguous;  off [B+1] row offsets of the spans;  rows = host upper bound on
+ *   off[B];  Dh in {64, 128}.
+ */
+int dllava_linear(const void* x, int64_t ldx, int64_t M, int64_t K, const void* W, const float* bias, int64_t N,
+                  int act, const void* residual, void* y, int64_t ldy, int dtype, void* stream);
+int dllava_layer_norm(const void* z, int64_t M, const float* gamma, const float* beta, void* y, int dtype,
+                         void* stream);
+int dllava_span_attn(const void* Q, const void* K, const void* V, int32_t B, const int32_t* off, int64_t rows,
+                     int32_t H, int32_t Dh, float scale, void* O, int dtype, void* stream);
 
 #ifdef __cplusplus
 }

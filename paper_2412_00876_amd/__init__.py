@@ -7,7 +7,8 @@ use raises ImportError.
 _BINDING_NAMES = ("BF16", "F32", "MODE_THRESHOLD", "MODE_THRESHOLD_KEEP_LAST", "MODE_TOPK", "PAGE_SIZE", "DllavaError", "KVCache", "EXPORTS",
                   "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_prefill_attn", "dllava_score",
                   "dllava_score_workspace", "dllava_qkv_project", "dllava_decode_step", "dllava_decode_step_workspace",
-                  "dllava_decode_commit",
+                  "dllava_decode_commit", "dllava_predict", "dllava_predict_workspace", "Predictor", "dllava_linear", "dllava_layer_norm",
+                  "dllava_span_attn",
                   "dllava_select_compact", "dllava_select_compact_workspace", "dllava_version", "lib")
 
 

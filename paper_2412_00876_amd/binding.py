@@ -32,6 +32,21 @@ class _KvCache(C.Structure):
                 ("H", C.c_int32), ("Dh", C.c_int32), ("dtype", C.c_int32)]
 
 
+class _VitBlock(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("ln1_g", "ln1_b", "Wqkv", "bqkv", "Wo", "bo", "ln2_g", "ln2_b",
+                                          "Wfc1", "bfc1", "Wfc2", "bfc2")]
+
+
+PREDICTOR_MAX_BLOCKS = 4
+
+
+class _Predictor(C.Structure):
+    _fields_ = [("d", C.c_int64), ("n_blocks", C.c_int32), ("W_in", C.c_void_p), ("b_in", C.c_void_p),
+                ("blocks", _VitBlock * PREDICTOR_MAX_BLOCKS),
+                ("W_h1", C.c_void_p), ("b_h1", C.c_void_p), ("W_h2", C.c_void_p), ("b_h2", C.c_void_p),
+                ("W_h3", C.c_void_p), ("b_h3", C.c_void_p)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2412_00876_amd.build` "
@@ -68,6 +83,16 @@ def _load() -> C.CDLL:
     lib.dllava_qkv_project.restype = C.c_int
     lib.dllava_qkv_project.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, vp, vp, f32, vp, C.POINTER(_KvCache), vp,
                                        C.c_int, vp]
+    lib.dllava_predict.restype = C.c_int
+    lib.dllava_predict.argtypes = [vp, i64, i64, i32, vp, vp, vp, C.POINTER(_Predictor), C.c_int, vp, vp, sz, vp]
+    lib.dllava_predict_workspace.restype = sz
+    lib.dllava_predict_workspace.argtypes = [i64, i32, i32]
+    lib.dllava_linear.restype = C.c_int
+    lib.dllava_linear.argtypes = [vp, i64, i64, i64, vp, vp, i64, C.c_int, vp, vp, i64, C.c_int, vp]
+    lib.dllava_layer_norm.restype = C.c_int
+    lib.dllava_layer_norm.argtypes = [vp, i64, vp, vp, vp, C.c_int, vp]
+    lib.dllava_span_attn.restype = C.c_int
+    lib.dllava_span_attn.argtypes = [vp, vp, vp, i32, vp, i64, i32, i32, f32, vp, C.c_int, vp]
     return lib
 
 
@@ -75,7 +100,8 @@ _lib = _load()
 EXPORTS = ("dllava_version", "dllava_last_error", "dllava_score", "dllava_score_workspace",
            "dllava_select_compact", "dllava_select_compact_workspace", "dllava_prefill_attn",
            "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_qkv_project",
-           "dllava_decode_step", "dllava_decode_step_workspace", "dllava_decode_commit")
+           "dllava_decode_step", "dllava_decode_step_workspace", "dllava_decode_commit",
+           "dllava_predict", "dllava_predict_workspace", "dllava_linear", "dllava_layer_norm", "dllava_span_attn")
 
 
 def lib() -> C.CDLL:
@@ -129,6 +155,52 @@ class KVCache:
     @property
     def ref(self):
         return C.byref(self.c)
+
+
+class Predictor:
+    """Host-side descriptor (dllava_predictor) over caller-owned device tensors.
+
+    `weights` maps the struct's field names to tensors (or None for an optional vector); `blocks` is a list of such
+    maps, one per transformer block.  The tensors are kept alive by this object.
+    """
+
+    def __init__(self, d: int, weights: dict, blocks: list):
+        assert len(blocks) <= PREDICTOR_MAX_BLOCKS
+        self._keep = (weights, blocks)
+        self.n_blocks = len(blocks)
+        self.c = _Predictor()
+        self.c.d, self.c.n_blocks = d, len(blocks)
+        for name in ("W_in", "b_in", "W_h1", "b_h1", "W_h2", "b_h2", "W_h3", "b_h3"):
+            setattr(self.c, name, _p(weights.get(name)))
+        for i, blk in enumerate(blocks):
+            for name, _ in _VitBlock._fields_:
+                setattr(self.c.blocks[i], name, _p(blk.get(name)))
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+
+def dllava_predict_workspace(M: int, B: int, n_blocks: int) -> int:
+    return _lib.dllava_predict_workspace(M, B, n_blocks)
+
+
+def dllava_predict(x, ldx, M, B, seq_off, vis_start, vis_len, p: Predictor, dtype, logits, workspace, stream=None):
+    ws, nbytes = _ws(workspace)
+    _check(_lib.dllava_predict(_p(x), ldx, M, B, _p(seq_off), _p(vis_start), _p(vis_len), p.ref, dtype, _p(logits),
+                               ws, nbytes, _stream(stream)))
+
+
+def dllava_linear(x, ldx, M, K, W, bias, N, act, residual, y, ldy, dtype, stream=None):
+    _check(_lib.dllava_linear(_p(x), ldx, M, K, _p(W), _p(bias), N, act, _p(residual), _p(y), ldy, dtype, _stream(stream)))
+
+
+def dllava_layer_norm(z, M, gamma, beta, y, dtype, stream=None):
+    _check(_lib.dllava_layer_norm(_p(z), M, _p(gamma), _p(beta), _p(y), dtype, _stream(stream)))
+
+
+def dllava_span_attn(Q, K, V, B, off, rows, H, Dh, scale, O, dtype, stream=None):
+    _check(_lib.dllava_span_attn(_p(Q), _p(K), _p(V), B, _p(off), rows, H, Dh, scale, _p(O), dtype, _stream(stream)))
 
 
 def dllava_version() -> int:

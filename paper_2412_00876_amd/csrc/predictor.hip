@@ -1,0 +1,406 @@
+// Predictors in the form of the paper's appendix (Appendix A.4.1): a linear layer that reduces the decoder width to
+// 512, for the image predictor two pre-norm transformer blocks over the image tokens of each sequence, and the MLP
+// head 512 -> 256 -> 128 -> 2.  bfloat16 storage, float32 sums.
+//
+//  * lin_gemm_kernel   Y = act(X W^T + b) (+ R): the 128 x 128 matrix-core tile product of gemm_tile.h (transposed
+//                      product W . X^T, so a lane holds many output features of ONE token), bias / GELU / residual in
+//                      registers, then a transposition through LDS so that every token leaves as whole 16-byte
+//                      pieces of a 256-byte run.  The first layer gathers its rows from the vision spans.
+//  * ln_kernel         LayerNorm of 512-wide rows, one wave per row, the row held in registers.
+//  * attention         prefill_mfma_kernel without the causal mask, 8 heads of 64, one "sequence" per span.
+//  * head_out_kernel   the last layer 128 -> 2, one wave per row.
+// Nothing here reduces across blocks: every output element is produced by one thread in a fixed order, so the
+// results are bit-reproducible.
+#include <cmath>
+
+#include "gemm_tile.h"
+#include "prefill_args.h"
+#include "score_args.h"
+
+namespace dllava {
+
+namespace {
+
+constexpr int kPW = 512;       // predictor width (Appendix A.4.1)
+constexpr int kPHeads = 8;     // heads of 64
+constexpr int kPMlp = 2048;    // hidden width of a block's MLP
+constexpr int kPH1 = 256, kPH2 = 128;  // head: 512 -> 256 -> 128 -> 2
+constexpr float kLnEps = 1e-6f;
+constexpr int kXcds = 8;
+
+struct LinArgs {
+  const bf16_t* X;   // [*, K], row stride ldx
+  int64_t ldx, M;
+  int K, N;
+  const bf16_t* W;   // [N, K]
+  const float* bias; // [N] or null
+  // feature f of row m goes to Y[(f / group) * group_stride + m * ldy + f % group]  (group = N: one plain matrix)
+  bf16_t* Y;
+  int64_t ldy, group_stride;
+  int group;
+  const bf16_t* R;   // residual, indexed like Y (may be Y itself), or null
+  int act;           // 1: GELU
+  // rows of X: the vision spans back to back when seq_off is given, else rows 0..M-1
+  int32_t B;
+  const int32_t* seq_off;
+  const int32_t* vis_start;
+  const int32_t* vis_len;
+};
+
+__global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4))) void lin_gemm_kernel(LinArgs a,
+                                                                                                         int n_ut) {
+  __shared__ __align__(16) bf16_t sAB[2 * kTileElems];  // W tile | X tile during the product, output tile afterwards
+  bf16_t* sA = sAB;
+  bf16_t* sB = sAB + kTileElems;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+  // XCD x takes the token tiles x, x+8, ... and, for each, all feature tiles (see score_gemm_kernel)
+  const int xcd = blockIdx.x % kXcds, jb = blockIdx.x / kXcds;
+  const int ut = jb % n_ut, mt = (jb / n_ut) * kXcds + xcd;
+  const int64_t M = a.M;
+  const int N = a.N, K = a.K;
+  if (static_cast<int64_t>(mt) * 128 >= M) return;
+
+  const int lc = tid & 7, lr = tid >> 3;
+  const bf16_t *ga[4], *gb[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int u = ut * 128 + lr + 32 * j;
+    if (u >= N) u = N - 1;  // such features are computed and dropped
+    ga[j] = a.W + static_cast<int64_t>(u) * K + lc * 8;
+    int64_t m = static_cast<int64_t>(mt) * 128 + lr + 32 * j;
+    if (m >= M) m = M - 1;
+    int64_t sr = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m);
+    if (sr < 0) sr = 0;
+    gb[j] = a.X + sr * a.ldx + lc * 8;
+  }
+  const int wu = (w >> 1) * 64, wm = (w & 1) * 64;  // this wave's 64 features x 64 tokens
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  gemm_tile_128x128<32>(ga[0], ga[1], ga[2], ga[3], gb[0], gb[1], gb[2], gb[3], K / kBK, sA, sB, wu, wm, acc);
+
+  // lane: token column wm + 32*j + lane%32; register r of fragment i: feature wu + 32*i + 8*(r/4) + 4*(lane/32) + r%4
+  const int g = lane >> 5;
+  bf16_t* sO = sAB;  // [128 tokens][16 chunks of 8 features], chunk c of token t at chunk position c ^ (t % 16)
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int fl = wu + 32 * i + 8 * q4 + 4 * g;  // this lane's four features of the tile
+      const int f0 = ut * 128 + fl;
+      const bool ok = f0 < N;
+      const float4 bs = *reinterpret_cast<const float4*>((ok && a.bias) ? a.bias + f0 : kZeroWords);
+      const int fs = ok ? f0 : 0;  // features past N: any valid address, the result is dropped
+      const int64_t col = static_cast<int64_t>(fs / a.group) * a.group_stride + fs % a.group;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int t = wm + 32 * j + (lane & 31);
+        int64_t m = static_cast<int64_t>(mt) * 128 + t;
+        if (m >= M) m = M - 1;
+        float v0 = acc[i][j][4 * q4] + bs.x, v1 = acc[i][j][4 * q4 + 1] + bs.y;
+        float v2 = acc[i][j][4 * q4 + 2] + bs.z, v3 = acc[i][j][4 * q4 + 3] + bs.w;
+        if (a.act) {
+          v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3);
+        }
+        if (a.R) {  // block-uniform; the sum is rounded once, after the addition
+          const uint2 rr = *reinterpret_cast<const uint2*>(a.R + col + m * a.ldy);
+          v0 += bf16lo_to_f32(rr.x); v1 += bf16hi_to_f32(rr.x);
+          v2 += bf16lo_to_f32(rr.y); v3 += bf16hi_to_f32(rr.y);
+        }
+        uint2 v;
+        v.x = pack_bf16x2(v0, v1);
+        v.y = pack_bf16x2(v2, v3);
+        *reinterpret_cast<uint2*>(sO + t * 128 + (((fl >> 3) ^ (t & 15)) * 8) + g * 4) = v;
+      }
+    }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int idx = tid + kGThreads * k, t = idx >> 4, c = idx & 15;
+    const int64_t m = static_cast<int64_t>(mt) * 128 + t;
+    const int f = ut * 128 + c * 8;
+    if (m < M && f < N)
+      *reinterpret_cast<uint4*>(a.Y + static_cast<int64_t>(f / a.group) * a.group_stride + m * a.ldy + f % a.group) =
+          *reinterpret_cast<const uint4*>(sO + t * 128 + ((c ^ (t & 15)) * 8));
+  }
+}
+
+int launch_lin(const LinArgs& a, hipStream_t st) {
+  const int n_ut = static_cast<int>(ceil_div(a.N, 128));
+  const int64_t n_mt = ceil_div(a.M, 128);
+  const int64_t blocks = ceil_div(n_mt, kXcds) * kXcds * n_ut;
+  if (blocks > 0x7fffffffLL) DLLAVA_FAIL(DLLAVA_ESHAPE, "predict: too many rows");
+  hipLaunchKernelGGL(lin_gemm_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kGThreads), 0, st, a, n_ut);
+  DLLAVA_CHECK_LAUNCH("lin_gemm_kernel");
+  return DLLAVA_OK;
+}
+
+// LayerNorm over rows of 512: lane holds 8 consecutive elements; mean and biased variance in two passes over the
+// registers.
+__global__ __launch_bounds__(256) void ln_kernel(const bf16_t* __restrict__ Z, bf16_t* __restrict__ Y,
+                                                 const float* __restrict__ gam, const float* __restrict__ bet,
+                                                 int64_t M) {
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + w;
+  if (row >= M) return;
+  const uint4 raw = *reinterpret_cast<const uint4*>(Z + row * kPW + lane * 8);
+  float v[8];
+  Elem<bf16_t>::unpack(raw, v);
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s += v[e];
+  const float mean = wave_sum(s) * (1.f / kPW);
+  float ss = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    v[e] -= mean;
+    ss = fmaf(v[e], v[e], ss);
+  }
+  const float rstd = 1.f / sqrtf(wave_sum(ss) * (1.f / kPW) + kLnEps);
+  float y[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float gm = gam ? gam[lane * 8 + e] : 1.f;
+    const float bt = bet ? bet[lane * 8 + e] : 0.f;
+    y[e] = fmaf(v[e] * rstd, gm, bt);
+  }
+  uint4 o;
+  o.x = pack_bf16x2(y[0], y[1]);
+  o.y = pack_bf16x2(y[2], y[3]);
+  o.z = pack_bf16x2(y[4], y[5]);
+  o.w = pack_bf16x2(y[6], y[7]);
+  *reinterpret_cast<uint4*>(Y + row * kPW + lane * 8) = o;
+}
+
+// last layer of the head: D[m] = h[m] W^T + b, h [M, 128], W [2, 128]; one wave per row, lane holds two inputs
+__global__ __launch_bounds__(256) void head_out_kernel(const bf16_t* __restrict__ Hd, const bf16_t* __restrict__ W,
+                                                       const float* __restrict__ b, float* __restrict__ logits,
+                                                       int64_t M, const int32_t* __restrict__ span_off, int32_t B) {
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + w;
+  const int64_t total = span_off ? span_off[B] : M;  // rows beyond the spans are left untouched
+  if (row >= M || row >= total) return;
+  const uint32_t x = *reinterpret_cast<const uint32_t*>(Hd + row * kPH2 + lane * 2);
+  const uint32_t w0 = *reinterpret_cast<const uint32_t*>(W + lane * 2);
+  const uint32_t w1 = *reinterpret_cast<const uint32_t*>(W + kPH2 + lane * 2);
+  const float x0 = bf16lo_to_f32(x), x1 = bf16hi_to_f32(x);
+  float p0 = fmaf(x1, bf16hi_to_f32(w0), x0 * bf16lo_to_f32(w0));
+  float p1 = fmaf(x1, bf16hi_to_f32(w1), x0 * bf16lo_to_f32(w1));
+  p0 = wave_sum(p0);
+  p1 = wave_sum(p1);
+  if (lane == 0) {
+    logits[2 * row] = p0 + (b ? b[0] : 0.f);
+    logits[2 * row + 1] = p1 + (b ? b[1] : 0.f);
+  }
+}
+
+// span_off[b] = sum of the span lengths before b (one wave; B+1 entries); without spans: {0, M}
+__global__ __launch_bounds__(kWave) void span_offsets_kernel(const int32_t* __restrict__ vis_len, int32_t B, int64_t M,
+                                                             int32_t* __restrict__ span_off) {
+  const int lane = threadIdx.x;
+  if (!vis_len) {
+    if (lane == 0) {
+      span_off[0] = 0;
+      span_off[1] = static_cast<int32_t>(M);
+    }
+    return;
+  }
+  int carry = 0;
+  if (lane == 0) span_off[0] = 0;
+  for (int base = 0; base < B; base += kWave) {
+    const int i = base + lane;
+    int n = i < B ? vis_len[i] : 0;
+    if (n < 0) n = 0;
+    const int incl = wave_incl_scan(n);
+    if (i < B) span_off[i + 1] = carry + incl;
+    carry += __shfl(incl, kWave - 1, kWave);
+  }
+}
+
+struct Regions {
+  int32_t* span_off;
+  bf16_t *Z, *Y, *QKV, *Hb;
+  size_t bytes;
+};
+
+Regions carve(void* ws, int64_t M, int32_t B, int32_t n_blocks) {
+  Regions r{};
+  size_t o = 0;
+  auto take = [&](size_t n) {
+    char* p = ws ? static_cast<char*>(ws) + o : nullptr;
+    o += round_up(n, 256);
+    return p;
+  };
+  const size_t rows = static_cast<size_t>(M > 0 ? M : 0);
+  r.span_off = reinterpret_cast<int32_t*>(take((static_cast<size_t>(B > 0 ? B : 0) + 2) * sizeof(int32_t)));
+  r.Z = reinterpret_cast<bf16_t*>(take(rows * kPW * 2));
+  r.Y = reinterpret_cast<bf16_t*>(take(rows * kPW * 2));
+  r.QKV = reinterpret_cast<bf16_t*>(take(n_blocks > 0 ? rows * 3 * kPW * 2 : 0));
+  r.Hb = reinterpret_cast<bf16_t*>(take(rows * (n_blocks > 0 ? kPMlp : kPH1) * 2));
+  r.bytes = o;
+  return r;
+}
+
+}  // namespace
+
+}  // namespace dllava
+
+using namespace dllava;
+
+extern "C" size_t dllava_predict_workspace(int64_t M, int32_t B, int32_t n_blocks) {
+  return carve(nullptr, M, B, n_blocks).bytes;
+}
+
+extern "C" int dllava_predict(const void* x, int64_t ldx, int64_t M, int32_t B, const int32_t* seq_off,
+                              const int32_t* vis_start, const int32_t* vis_len, const dllava_predictor* p, int dtype,
+                              float* logits, void* workspace, size_t workspace_bytes, void* stream) {
+  DLLAVA_REQUIRE(p, DLLAVA_ENULL, "predict: the predictor struct is required");
+  DLLAVA_REQUIRE(dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "predict: only DLLAVA_BF16 is supported (got dtype %d)", dtype);
+  DLLAVA_REQUIRE(M >= 0 && M <= 0x7fffffffLL, DLLAVA_ESHAPE, "predict: bad M = %lld", (long long)M);
+  DLLAVA_REQUIRE(B >= 0, DLLAVA_EINVAL, "predict: B = %d < 0", B);
+  DLLAVA_REQUIRE(p->n_blocks >= 0 && p->n_blocks <= DLLAVA_PREDICTOR_MAX_BLOCKS, DLLAVA_EINVAL,
+                 "predict: n_blocks = %d outside 0..%d", p->n_blocks, DLLAVA_PREDICTOR_MAX_BLOCKS);
+  DLLAVA_REQUIRE(p->d > 0 && p->d % 64 == 0 && p->d <= 0x7fffffffLL, DLLAVA_ESHAPE,
+                 "predict: d must be a positive multiple of 64 (got %lld)", (long long)p->d);
+  DLLAVA_REQUIRE(ldx >= p->d && ldx % 8 == 0, DLLAVA_ESHAPE,
+                 "predict: ldx must be >= d and a multiple of 8 (got %lld)", (long long)ldx);
+  if (M == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(x && logits, DLLAVA_ENULL, "predict: x and logits are required");
+  DLLAVA_REQUIRE(!seq_off || (vis_start && vis_len), DLLAVA_ENULL, "predict: vis_start and vis_len go with seq_off");
+  DLLAVA_REQUIRE(p->W_in && p->W_h1 && p->W_h2 && p->W_h3, DLLAVA_ENULL, "predict: W_in, W_h1, W_h2, W_h3 are required");
+  DLLAVA_REQUIRE(aligned(x, 16) && aligned(p->W_in, 16) && aligned(p->W_h1, 16) && aligned(p->W_h2, 16) &&
+                     aligned(p->W_h3, 4),
+                 DLLAVA_EINVAL, "predict: x and the matrices must be 16-byte aligned");
+  DLLAVA_REQUIRE(aligned(p->b_in, 16) && aligned(p->b_h1, 16) && aligned(p->b_h2, 16), DLLAVA_EINVAL,
+                 "predict: bias vectors must be 16-byte aligned");
+  for (int i = 0; i < p->n_blocks; ++i) {
+    const dllava_vit_block& k = p->blocks[i];
+    DLLAVA_REQUIRE(k.Wqkv && k.Wo && k.Wfc1 && k.Wfc2, DLLAVA_ENULL, "predict: block %d lacks a matrix", i);
+    DLLAVA_REQUIRE(aligned(k.Wqkv, 16) && aligned(k.Wo, 16) && aligned(k.Wfc1, 16) && aligned(k.Wfc2, 16) &&
+                       aligned(k.bqkv, 16) && aligned(k.bo, 16) && aligned(k.bfc1, 16) && aligned(k.bfc2, 16),
+                   DLLAVA_EINVAL, "predict: block %d: matrices and bias vectors must be 16-byte aligned", i);
+  }
+  const int nb = p->n_blocks;
+  const Regions r = carve(workspace, M, B, nb);
+  DLLAVA_REQUIRE(workspace && aligned(workspace, 256) && workspace_bytes >= r.bytes, DLLAVA_EWORKSPACE,
+                 "predict: workspace needs %zu bytes, 256-byte aligned (got %zu)", r.bytes, workspace_bytes);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bf16_t* X = static_cast<const bf16_t*>(x);
+  const int32_t n_spans = seq_off ? B : 1;
+
+  auto lin = [&](const bf16_t* in, int64_t ldin, int K, const void* W, const float* bias, int N, bf16_t* out,
+                 int64_t ldout, int act, const bf16_t* res) {
+    LinArgs a{};
+    a.X = in; a.ldx = ldin; a.M = M; a.K = K; a.N = N;
+    a.W = static_cast<const bf16_t*>(W); a.bias = bias;
+    a.Y = out; a.ldy = ldout; a.group = N; a.group_stride = 0;
+    a.R = res; a.act = act;
+    return a;
+  };
+
+  if (nb > 0 || seq_off) {
+    hipLaunchKernelGGL(span_offsets_kernel, dim3(1), dim3(kWave), 0, st, seq_off ? vis_len : nullptr, B, M, r.span_off);
+    DLLAVA_CHECK_LAUNCH("span_offsets_kernel");
+  }
+  {  // z = x W_in^T + b_in over the rows of the spans
+    LinArgs a = lin(X, ldx, static_cast<int>(p->d), p->W_in, p->b_in, kPW, r.Z, kPW, 0, nullptr);
+    a.B = B; a.seq_off = seq_off; a.vis_start = vis_start; a.vis_len = vis_len;
+    if (int rc = launch_lin(a, st)) return rc;
+  }
+  const unsigned row_blocks = static_cast<unsigned>(ceil_div(M, 4));
+  for (int i = 0; i < nb; ++i) {
+    const dllava_vit_block& k = p->blocks[i];
+    hipLaunchKernelGGL(ln_kernel, dim3(row_blocks), dim3(256), 0, st, r.Z, r.Y, k.ln1_g, k.ln1_b, M);
+    DLLAVA_CHECK_LAUNCH("ln_kernel");
+    {  // q | k | v into three [M, 512] matrices
+      LinArgs a = lin(r.Y, kPW, kPW, k.Wqkv, k.bqkv, 3 * kPW, r.QKV, kPW, 0, nullptr);
+      a.group = kPW;
+      a.group_stride = M * kPW;
+      if (int rc = launch_lin(a, st)) return rc;
+    }
+    {  // attention of every image token over all image tokens of its sequence, into Y
+      PrefillArgs pa{};
+      pa.Q = r.QKV; pa.K = r.QKV + M * kPW; pa.V = r.QKV + 2 * M * kPW; pa.O = r.Y;
+      pa.off = r.span_off; pa.B = n_spans; pa.H = kPHeads;
+      pa.scale_log2 = 0.125f * 1.44269504088896340736f;  // 1 / sqrt(64), in the base-2 exponent
+      pa.full = 1;
+      const int rc = prefill_mfma_launch(pa, M, kPW / kPHeads, st);
+      if (rc < 0) return rc;
+      if (rc > 0) DLLAVA_FAIL(DLLAVA_ESHAPE, "predict: too many rows or spans for the attention step");
+    }
+    if (int rc = launch_lin(lin(r.Y, kPW, kPW, k.Wo, k.bo, kPW, r.Z, kPW, 0, r.Z), st)) return rc;
+    hipLaunchKernelGGL(ln_kernel, dim3(row_blocks), dim3(256), 0, st, r.Z, r.Y, k.ln2_g, k.ln2_b, M);
+    DLLAVA_CHECK_LAUNCH("ln_kernel");
+    if (int rc = launch_lin(lin(r.Y, kPW, kPW, k.Wfc1, k.bfc1, kPMlp, r.Hb, kPMlp, 1, nullptr), st)) return rc;
+    if (int rc = launch_lin(lin(r.Hb, kPMlp, kPMlp, k.Wfc2, k.bfc2, kPW, r.Z, kPW, 0, r.Z), st)) return rc;
+  }
+  if (int rc = launch_lin(lin(r.Z, kPW, kPW, p->W_h1, p->b_h1, kPH1, r.Hb, kPH1, 1, nullptr), st)) return rc;
+  if (int rc = launch_lin(lin(r.Hb, kPH1, kPH1, p->W_h2, p->b_h2, kPH2, r.Y, kPH2, 1, nullptr), st)) return rc;
+  hipLaunchKernelGGL(head_out_kernel, dim3(row_blocks), dim3(256), 0, st, r.Y, static_cast<const bf16_t*>(p->W_h3),
+                     p->b_h3, logits, M, seq_off ? r.span_off : nullptr, B);
+  DLLAVA_CHECK_LAUNCH("head_out_kernel");
+  return DLLAVA_OK;
+}
+
+// ---- the layers of the predictor as calls of their own ---------------------------------------------------------
+
+extern "C" int dllava_linear(const void* x, int64_t ldx, int64_t M, int64_t K, const void* W, const float* bias,
+                             int64_t N, int act, const void* residual, void* y, int64_t ldy, int dtype, void* stream) {
+  DLLAVA_REQUIRE(dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "linear: only DLLAVA_BF16 is supported (got dtype %d)", dtype);
+  DLLAVA_REQUIRE(M >= 0 && M <= 0x7fffffffLL, DLLAVA_ESHAPE, "linear: bad M = %lld", (long long)M);
+  DLLAVA_REQUIRE(K > 0 && K % 64 == 0 && K <= 0x7fffffffLL, DLLAVA_ESHAPE,
+                 "linear: K must be a positive multiple of 64 (got %lld)", (long long)K);
+  DLLAVA_REQUIRE(N > 0 && N % 8 == 0 && N <= 0x7fffffffLL, DLLAVA_ESHAPE,
+                 "linear: N must be a positive multiple of 8 (got %lld)", (long long)N);
+  DLLAVA_REQUIRE(ldx >= K && ldx % 8 == 0 && ldy >= N && ldy % 8 == 0, DLLAVA_ESHAPE,
+                 "linear: ldx >= K, ldy >= N, both multiples of 8 (got %lld, %lld)", (long long)ldx, (long long)ldy);
+  DLLAVA_REQUIRE(act == 0 || act == 1, DLLAVA_EINVAL, "linear: act = %d (0: none, 1: GELU)", act);
+  if (M == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(x && W && y, DLLAVA_ENULL, "linear: x, W and y are required");
+  DLLAVA_REQUIRE(aligned(x, 16) && aligned(W, 16) && aligned(y, 16) && aligned(residual, 16) && aligned(bias, 16),
+                 DLLAVA_EINVAL, "linear: x, W, bias, residual, y must be 16-byte aligned");
+  LinArgs a{};
+  a.X = static_cast<const bf16_t*>(x); a.ldx = ldx; a.M = M; a.K = static_cast<int>(K); a.N = static_cast<int>(N);
+  a.W = static_cast<const bf16_t*>(W); a.bias = bias;
+  a.Y = static_cast<bf16_t*>(y); a.ldy = ldy; a.group = static_cast<int>(N); a.group_stride = 0;
+  a.R = static_cast<const bf16_t*>(residual); a.act = act;
+  return launch_lin(a, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int dllava_layer_norm(const void* z, int64_t M, const float* gamma, const float* beta, void* y, int dtype,
+                                    void* stream) {
+  DLLAVA_REQUIRE(dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "layer_norm: only DLLAVA_BF16 is supported (got dtype %d)", dtype);
+  DLLAVA_REQUIRE(M >= 0 && M <= 0x7fffffffLL, DLLAVA_ESHAPE, "layer_norm: bad M = %lld", (long long)M);
+  if (M == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(z && y, DLLAVA_ENULL, "layer_norm: z and y are required");
+  DLLAVA_REQUIRE(aligned(z, 16) && aligned(y, 16), DLLAVA_EINVAL, "layer_norm: z and y must be 16-byte aligned");
+  hipLaunchKernelGGL(ln_kernel, dim3(static_cast<unsigned>(ceil_div(M, 4))), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const bf16_t*>(z), static_cast<bf16_t*>(y), gamma,
+                     beta, M);
+  DLLAVA_CHECK_LAUNCH("ln_kernel");
+  return DLLAVA_OK;
+}
+
+extern "C" int dllava_span_attn(const void* Q, const void* K, const void* V, int32_t B, const int32_t* off, int64_t rows,
+                                int32_t H, int32_t Dh, float scale, void* O, int dtype, void* stream) {
+  DLLAVA_REQUIRE(dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "span_attn: only DLLAVA_BF16 is supported (got dtype %d)", dtype);
+  DLLAVA_REQUIRE(B >= 0 && rows >= 0 && rows <= 0x7fffffffLL, DLLAVA_EINVAL, "span_attn: B = %d, rows = %lld", B,
+                 (long long)rows);
+  DLLAVA_REQUIRE(H > 0 && (Dh == 64 || Dh == 128), DLLAVA_ESHAPE, "span_attn: H = %d, Dh = %d (Dh must be 64 or 128)", H, Dh);
+  DLLAVA_REQUIRE(scale == scale && scale < INFINITY && scale > -INFINITY, DLLAVA_EINVAL, "span_attn: bad scale");
+  if (B == 0 || rows == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(Q && K && V && O && off, DLLAVA_ENULL, "span_attn: Q, K, V, O and off are required");
+  DLLAVA_REQUIRE(aligned(Q, 16) && aligned(K, 16) && aligned(V, 16) && aligned(O, 16), DLLAVA_EINVAL,
+                 "span_attn: Q, K, V, O must be 16-byte aligned");
+  PrefillArgs pa{};
+  pa.Q = Q; pa.K = K; pa.V = V; pa.O = O; pa.off = off; pa.B = B; pa.H = H;
+  pa.scale_log2 = scale * 1.44269504088896340736f;
+  pa.full = 1;
+  const int rc = prefill_mfma_launch(pa, rows, Dh, static_cast<hipStream_t>(stream));
+  if (rc > 0) DLLAVA_FAIL(DLLAVA_ESHAPE, "span_attn: too many rows, spans or heads");
+  return rc;
+}

@@ -17,6 +17,8 @@ struct PrefillArgs {
   const void* pages;
   const int32_t* block_table;
   int32_t max_pages;
+  // 0: causal (query i sees keys 0..i of its sequence); 1: every query sees all keys of its sequence
+  int32_t full;
 };
 
 // matrix-core path (prefill_mfma.hip); returns 1 if it does not handle the shape

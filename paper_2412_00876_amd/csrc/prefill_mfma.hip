@@ -301,7 +301,8 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
     for (int r = 0; r < 16; ++r) o_acc[nb][r] = 0.f;
   float m_ref = -INFINITY, l_run = 0.f;
 
-  const int last_key = (i0 + kBM < n ? i0 + kBM : n) - 1;  // keys 0..last_key are needed by this block
+  const bool full = a.full != 0;  // no causal mask: all keys of the sequence (block-uniform)
+  const int last_key = (!full && i0 + kBM < n ? i0 + kBM : n) - 1;  // keys 0..last_key are needed by this block
   const int n_tiles = last_key / kBN + 1;
 
   // Fragment addresses (LDS bytes, stage 0).  K: row lq, logical chunk 2*ks + g, stored at chunk ^ (lq mod chunks):
@@ -373,10 +374,12 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
       PAGE_IDS(t + 3);
     }
     const int j0 = t * kBN;
-    if (j0 <= iw + 31 && iw < n) {  // else the tile lies entirely above this wave's diagonal, or the wave has no query (wave-uniform)
+    if ((full || j0 <= iw + 31) && iw < n) {  // else the tile lies entirely above this wave's diagonal, or the wave has no query (wave-uniform)
       const uint32_t kb = kb0 + cur * (kTileElems * 2), vb = vb0 + cur * (kTileElems * 2);
-      // diag: some key of the tile may exceed some query of the wave
-      tile_step<DH>(kb, vb, qf, o_acc, m_ref, l_run, a.scale_log2, j0, qi, g, j0 + kBN - 1 > iw);
+      // diag: some key of the tile may exceed some query of the wave (causal) or the end of the sequence (full);
+      // keys beyond the last visible one are masked
+      tile_step<DH>(kb, vb, qf, o_acc, m_ref, l_run, a.scale_log2, j0, full ? n - 1 : qi, g,
+                    j0 + kBN - 1 > (full ? n - 1 : iw));
     }
     cur = cur == kStages - 1 ? 0 : cur + 1;
   }
