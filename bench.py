@@ -231,6 +231,46 @@ class NoCacheStep:
                               self.O, p.code)
 
 
+class PaperPredictors:
+    """The predictors in the appendix's form (Appendix A.4.1) on this workload, outside the timed step, which
+    scores with the two-layer form the benchmark definition fixes: the image predictor (two transformer blocks)
+    over all vision spans, and the output-text predictor over the B rows of one decode step."""
+
+    def __init__(self, path, W):
+        w, P, torch = path.w, path.P, path.torch
+        dev = "cuda:0"
+        self.path = path
+
+        def desc(Pw):
+            up = lambda v: path.to_dev(v, "bf16") if v.dtype == np.uint16 else torch.from_numpy(v).to(dev)
+            return P.Predictor(w.d, {k: up(v) for k, v in Pw.items() if k != "blocks"},
+                               [{k: up(v) for k, v in blk.items()} for blk in Pw["blocks"]])
+
+        self.image = desc(W.paper_predictor(w, 2, "ppred.image"))
+        self.text = desc(W.paper_predictor(w, 0, "ppred.text"))
+        z = lambda n: torch.zeros(n, dtype=torch.uint8, device=dev)
+        self.ws_image = z(P.dllava_predict_workspace(path.M_vis, w.B, 2))
+        self.ws_text = z(P.dllava_predict_workspace(w.B, w.B, 0))
+        self.logits_image = torch.zeros((path.M_vis, 2), dtype=torch.float32, device=dev)
+        self.logits_text = torch.zeros((w.B, 2), dtype=torch.float32, device=dev)
+
+    def run_image(self):
+        p, w = self.path, self.path.w
+        p.P.dllava_predict(p.pre["hidden"], w.d, p.M_vis, w.B, p.seq_off, p.vis_start, p.vis_len, self.image, p.code,
+                           self.logits_image, self.ws_image)
+
+    def run_text(self, t):
+        p, w = self.path, self.path.w
+        p.P.dllava_predict(p.dec["x"][t], w.d, w.B, 0, None, None, None, self.text, p.code, self.logits_text,
+                           self.ws_text)
+
+    def flops_image(self):
+        w, M = self.path.w, self.path.M_vis
+        lin = 2.0 * M * (w.d * 512 + 512 * 256 + 256 * 128 + 256) + 2 * 2.0 * M * 12 * 512 * 512
+        att = 2 * sum(4.0 * n * n * 512 for n in w.n_vis)
+        return lin + att
+
+
 def timed_events(torch, fn, n=1):
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
@@ -406,6 +446,11 @@ def main():
         nc = NoCacheStep(path)
         ms_nc = stage_ms(lambda i: nc.run(), 3)
         nc_kept = [int(v) for v in (nc.out_off[1:] - nc.out_off[:-1]).tolist()]
+        ms_pp_image = ms_pp_text = None
+        if w.dtype == "bf16":
+            pp = PaperPredictors(path, W)
+            ms_pp_image = stage_ms(lambda i: pp.run_image(), 3)
+            ms_pp_text = stage_ms(pp.run_text, min(T, 64))
         ms_prefill = stage_ms(lambda i: path.prefill_attn(), 5)
         ms_sd = stage_ms(path.score_decode, T)                          # logits of all steps: inputs of the next line
         ms_da = stage_ms(path.decode_attn, T, before=path.select_compact)  # cache reset, then T attention launches
@@ -463,6 +508,12 @@ def main():
                                           "attn_tflops": sum(4.0 * H * Dh * n * (n + 1) / 2 for n in nc_kept) / (ms_nc * 1e-3) / 1e12,
                                           "attn_flops_dense_counterfactual": float(sum(4.0 * H * Dh * n * (n + 1) / 2
                                                                                        for n in (np.asarray(w.seq_len) + T)))},
+            # the predictors in the appendix's form (also outside the timed step): image predictor over all vision
+            # spans, output-text predictor over the B rows of a decode step
+            "predict_image": None if ms_pp_image is None else {
+                "ms": ms_pp_image, "rows": path.M_vis, "tflops": pp.flops_image() / (ms_pp_image * 1e-3) / 1e12,
+                "frac_mfma_peak": pp.flops_image() / (ms_pp_image * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+            "predict_text": None if ms_pp_text is None else {"avg_us": float(ms_pp_text * 1e3), "rows": B},
             "decode_step": {"avg_us": float(ms_ds * 1e3), "gbs": (float(kv_bytes_t.mean()) + pred_bytes) / (ms_ds * 1e-3) / 1e9,
                             "note": "one launch per step: scoring + attention, append deferred by one step"},
             "decode_score": {"avg_us": float(ms_sd * 1e3)},

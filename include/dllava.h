@@ -299,8 +299,8 @@ int dllava_qkv_project(const void* x, int64_t ldx, int64_t rows, int64_t d,
  * Every tensor written between two layers (z, LN outputs, q/k/v, attention output, hidden activations) is
  * stored in dtype (rounded to nearest even); sums are float32; logits are float32.
  *
- * All matrices are [out, in] row-major in dtype, 16-byte aligned; vectors are float32 and may be NULL (= 0
- * for biases and LayerNorm shifts, = 1 for LayerNorm scales).
+ * All matrices are [out, in] row-major in dtype; vectors are float32 and may be NULL (= 0 for biases and
+ * LayerNorm shifts, = 1 for LayerNorm scales); matrices and vectors are 16-byte aligned (b_h3 and W_h3: 4).
  */
 typedef struct dllava_vit_block {
   const float* ln1_g; const float* ln1_b;   /* [512] */
@@ -348,7 +348,7 @@ size_t dllava_predict_workspace(int64_t M, int32_t B, int32_t n_blocks);
  *   residual [M, N] with y's row stride, or NULL, may be y itself;  y [M, N] row stride ldy, out.
  *   Sizes: K % 64 == 0, N % 8 == 0, ldx % 8 == 0, ldy % 8 == 0; pointers 16-byte aligned.
  * dllava_layer_norm: y = (z - mean) / sqrt(var + 1e-6) * gamma + beta per row of 512 (biased variance);
- *   z, y [M, 512] contiguous;  gamma, beta [512] float32 or NULL (1 and 0).
+ *   z, y [M, 512] contiguous;  gamma, beta [512] float32, 16-byte aligned, or NULL (1 and 0).
  * dllava_span_attn:     O_i = softmax_j(scale * q_i . k_j) V over ALL rows j of the span of row i (no causal
  *   mask);  Q, K, V, O [rows, H, Dh] contiguous;  off [B+1] row offsets of the spans;  rows = host upper bound on
  *   off[B];  Dh in {64, 128}.

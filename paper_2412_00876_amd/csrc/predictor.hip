@@ -161,13 +161,26 @@ __global__ __launch_bounds__(256) void ln_kernel(const bf16_t* __restrict__ Z, b
     ss = fmaf(v[e], v[e], ss);
   }
   const float rstd = 1.f / sqrtf(wave_sum(ss) * (1.f / kPW) + kLnEps);
+  // scale and shift: two 16-byte loads each (eight scalar loads per vector would touch every cache line of the
+  // vector eight times per wave); a missing vector reads as ones / zeros
+  float gm[8], bt[8];
+  if (gam) {
+    *reinterpret_cast<float4*>(gm) = *reinterpret_cast<const float4*>(gam + lane * 8);
+    *reinterpret_cast<float4*>(gm + 4) = *reinterpret_cast<const float4*>(gam + lane * 8 + 4);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) gm[e] = 1.f;
+  }
+  if (bet) {
+    *reinterpret_cast<float4*>(bt) = *reinterpret_cast<const float4*>(bet + lane * 8);
+    *reinterpret_cast<float4*>(bt + 4) = *reinterpret_cast<const float4*>(bet + lane * 8 + 4);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bt[e] = 0.f;
+  }
   float y[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float gm = gam ? gam[lane * 8 + e] : 1.f;
-    const float bt = bet ? bet[lane * 8 + e] : 0.f;
-    y[e] = fmaf(v[e] * rstd, gm, bt);
-  }
+  for (int e = 0; e < 8; ++e) y[e] = fmaf(v[e] * rstd, gm[e], bt[e]);
   uint4 o;
   o.x = pack_bf16x2(y[0], y[1]);
   o.y = pack_bf16x2(y[2], y[3]);
@@ -221,9 +234,191 @@ __global__ __launch_bounds__(kWave) void span_offsets_kernel(const int32_t* __re
   }
 }
 
+
+// ---- the output-text predictor on a handful of rows (one per sequence and decode step) ---------------------------
+// With at most 64 rows the tile kernel above would pull the 2*512*d bytes of W_in through four compute units.
+// small_in_kernel spreads W_in over 64 blocks of 4 waves: block = 32 output features x a quarter of d, wave = a
+// sixteenth of d, fragments straight from global memory (every byte of W_in is read once, all loads of a wave in
+// flight together), the four waves summed through LDS in wave order, one partial per block.  small_head_kernel
+// (one block per 32 rows) adds the four partials and the bias in a fixed order, rounds the 512 features to the
+// storage type into LDS, and runs the head 512 -> 256 -> 128 -> 2 from there on the matrix cores, the weights of
+// both layers requested at its very start.
+constexpr int kSmallRows = 64;
+constexpr int kSmallSplit = 4;    // blocks along d
+constexpr int kZs = 520, kH1s = 264, kH2s = 136;  // LDS row strides (elements): 16-byte pieces of 16 rows fall in 16 bank groups
+
+template <int NT>  // tiles of 32 rows
+__global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict__ X, int64_t ldx, int M, int K,
+                                                       const bf16_t* __restrict__ W, float* __restrict__ partial,
+                                                       int32_t B, const int32_t* __restrict__ seq_off,
+                                                       const int32_t* __restrict__ vis_start,
+                                                       const int32_t* __restrict__ vis_len) {
+  __shared__ float red[3][NT][16][kWave];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+  const int fg = blockIdx.x & 15, kq = blockIdx.x >> 4;
+  const int r = lane & 31, g = lane >> 5;
+  const int total = K / 16;            // steps of 16 elements of d
+  const int per = (total + 15) / 16;   // steps of one wave (16 slices: 4 blocks x 4 waves)
+  const int sbeg = (kq * 4 + w) * per;
+  const int send = sbeg + per < total ? sbeg + per : total;
+  const bf16_t* wrow = W + static_cast<int64_t>(32 * fg + r) * K + 8 * g;
+  const bf16_t* xrow[NT];
+#pragma unroll
+  for (int tt = 0; tt < NT; ++tt) {
+    int64_t m = 32 * tt + r;
+    if (m >= M) m = M - 1;  // rows past M repeat the last one and are dropped later
+    int64_t sr = score_src_row(seq_off, vis_start, vis_len, B, m);
+    if (sr < 0) sr = 0;
+    xrow[tt] = X + sr * ldx + 8 * g;
+  }
+  f32x16 acc[NT];
+#pragma unroll
+  for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[tt][i] = 0.f;
+  for (int s0 = sbeg; s0 < send; s0 += 16) {
+    uint4 wf[16], xf[NT][16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {  // all loads of the batch first (past the end: the last step again, unused)
+      const int sidx = s0 + u < send ? s0 + u : send - 1;
+      wf[u] = *reinterpret_cast<const uint4*>(wrow + 16 * sidx);
+#pragma unroll
+      for (int tt = 0; tt < NT; ++tt) xf[tt][u] = *reinterpret_cast<const uint4*>(xrow[tt] + 16 * sidx);
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      if (s0 + u < send) {  // wave-uniform
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt)
+          acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(wf[u]), as_frag(xf[tt][u]), acc[tt], 0, 0, 0);
+      }
+  }
+  if (w > 0) {
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) red[w - 1][tt][i][lane] = acc[tt][i];
+  }
+  __syncthreads();
+  if (w != 0) return;
+  // lane: row 32*tt + r; register i: feature 32*fg + 8*(i/4) + 4*g + i%4
+#pragma unroll
+  for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      float4 v;
+      float* pv = &v.x;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = 4 * q4 + e;
+        pv[e] = ((acc[tt][i] + red[0][tt][i][lane]) + red[1][tt][i][lane]) + red[2][tt][i][lane];
+      }
+      *reinterpret_cast<float4*>(partial + (static_cast<int64_t>(kq * (32 * NT) + 32 * tt + r)) * kPW + 32 * fg +
+                                 8 * q4 + 4 * g) = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void small_head_kernel(const float* __restrict__ partial, int rows_pad, int M,
+                                                         const float* __restrict__ b_in,
+                                                         const bf16_t* __restrict__ W1, const float* __restrict__ b1,
+                                                         const bf16_t* __restrict__ W2, const float* __restrict__ b2,
+                                                         const bf16_t* __restrict__ W3, const float* __restrict__ b3,
+                                                         float* __restrict__ logits,
+                                                         const int32_t* __restrict__ span_off, int32_t B) {
+  __shared__ __align__(16) bf16_t zT[32 * kZs];
+  __shared__ __align__(16) bf16_t h1T[32 * kH1s];
+  __shared__ __align__(16) bf16_t h2T[32 * kH2s];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+  const int r = lane & 31, g = lane >> 5;
+  const int t0 = blockIdx.x * 32;
+  // the weights of both layers: wave w owns features 64w..64w+63 of the first and 32w..32w+31 of the second
+  uint4 f1a[32], f1b[32], f2[16];
+  {
+    const bf16_t* wa = W1 + static_cast<int64_t>(64 * w + r) * kPW + 8 * g;
+    const bf16_t* wb = wa + 32 * kPW;
+    const bf16_t* wc = W2 + static_cast<int64_t>(32 * w + r) * kPH1 + 8 * g;
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+      f1a[u] = *reinterpret_cast<const uint4*>(wa + 16 * u);
+      f1b[u] = *reinterpret_cast<const uint4*>(wb + 16 * u);
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) f2[u] = *reinterpret_cast<const uint4*>(wc + 16 * u);
+  }
+  // z = bias + the partial sums, in a fixed order, rounded to the storage type
+  for (int it = tid; it < 32 * (kPW / 4); it += 256) {
+    const int tok = it / (kPW / 4), f = (it % (kPW / 4)) * 4;
+    float4 sum = *reinterpret_cast<const float4*>(b_in ? b_in + f : kZeroWords);
+#pragma unroll
+    for (int q = 0; q < kSmallSplit; ++q) {
+      const float4 pq = *reinterpret_cast<const float4*>(partial + static_cast<int64_t>(q * rows_pad + t0 + tok) * kPW + f);
+      sum.x += pq.x; sum.y += pq.y; sum.z += pq.z; sum.w += pq.w;
+    }
+    uint2 v;
+    v.x = pack_bf16x2(sum.x, sum.y);
+    v.y = pack_bf16x2(sum.z, sum.w);
+    *reinterpret_cast<uint2*>(zT + tok * kZs + f) = v;
+  }
+  __syncthreads();
+  {  // h1 = GELU(W1 z + b1): two 32-feature tiles per wave
+    f32x16 a0, a1;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a0[i] = a1[i] = 0.f;
+    const bf16_t* zb = zT + r * kZs + 8 * g;
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+      const bf16x8 bz = as_frag(*reinterpret_cast<const uint4*>(zb + 16 * u));
+      a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(f1a[u]), bz, a0, 0, 0, 0);
+      a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(f1b[u]), bz, a1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int f = 64 * w + 32 * i + 8 * q4 + 4 * g;
+        const float4 bs = *reinterpret_cast<const float4*>(b1 ? b1 + f : kZeroWords);
+        const f32x16& a = i ? a1 : a0;
+        uint2 v;
+        v.x = pack_bf16x2(gelu_erf_fast(a[4 * q4] + bs.x), gelu_erf_fast(a[4 * q4 + 1] + bs.y));
+        v.y = pack_bf16x2(gelu_erf_fast(a[4 * q4 + 2] + bs.z), gelu_erf_fast(a[4 * q4 + 3] + bs.w));
+        *reinterpret_cast<uint2*>(h1T + r * kH1s + f) = v;
+      }
+  }
+  __syncthreads();
+  {  // h2 = GELU(W2 h1 + b2): one 32-feature tile per wave
+    f32x16 a;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a[i] = 0.f;
+    const bf16_t* hb = h1T + r * kH1s + 8 * g;
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(f2[u]), as_frag(*reinterpret_cast<const uint4*>(hb + 16 * u)), a,
+                                                  0, 0, 0);
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int f = 32 * w + 8 * q4 + 4 * g;
+      const float4 bs = *reinterpret_cast<const float4*>(b2 ? b2 + f : kZeroWords);
+      uint2 v;
+      v.x = pack_bf16x2(gelu_erf_fast(a[4 * q4] + bs.x), gelu_erf_fast(a[4 * q4 + 1] + bs.y));
+      v.y = pack_bf16x2(gelu_erf_fast(a[4 * q4 + 2] + bs.z), gelu_erf_fast(a[4 * q4 + 3] + bs.w));
+      *reinterpret_cast<uint2*>(h2T + r * kH2s + f) = v;
+    }
+  }
+  __syncthreads();
+  if (tid < 64) {  // the two logits of a row: a float32 sum over the 128 inputs in ascending order
+    const int tok = tid >> 1, c = tid & 1;
+    const int64_t m = t0 + tok;
+    const int64_t lim = span_off ? span_off[B] : M;
+    float sum = b3 ? b3[c] : 0.f;
+    for (int k = 0; k < kPH2; ++k) sum = fmaf(bf16_to_f32(h2T[tok * kH2s + k]), bf16_to_f32(W3[c * kPH2 + k]), sum);
+    if (m < M && m < lim) logits[2 * m + c] = sum;
+  }
+}
+
 struct Regions {
   int32_t* span_off;
   bf16_t *Z, *Y, *QKV, *Hb;
+  float* small;  // partial sums of the small-batch path
   size_t bytes;
 };
 
@@ -241,6 +436,7 @@ Regions carve(void* ws, int64_t M, int32_t B, int32_t n_blocks) {
   r.Y = reinterpret_cast<bf16_t*>(take(rows * kPW * 2));
   r.QKV = reinterpret_cast<bf16_t*>(take(n_blocks > 0 ? rows * 3 * kPW * 2 : 0));
   r.Hb = reinterpret_cast<bf16_t*>(take(rows * (n_blocks > 0 ? kPMlp : kPH1) * 2));
+  r.small = reinterpret_cast<float*>(take(n_blocks == 0 && M <= kSmallRows ? size_t(kSmallSplit) * kSmallRows * kPW * 4 : 0));
   r.bytes = o;
   return r;
 }
@@ -281,8 +477,9 @@ extern "C" int dllava_predict(const void* x, int64_t ldx, int64_t M, int32_t B, 
     const dllava_vit_block& k = p->blocks[i];
     DLLAVA_REQUIRE(k.Wqkv && k.Wo && k.Wfc1 && k.Wfc2, DLLAVA_ENULL, "predict: block %d lacks a matrix", i);
     DLLAVA_REQUIRE(aligned(k.Wqkv, 16) && aligned(k.Wo, 16) && aligned(k.Wfc1, 16) && aligned(k.Wfc2, 16) &&
-                       aligned(k.bqkv, 16) && aligned(k.bo, 16) && aligned(k.bfc1, 16) && aligned(k.bfc2, 16),
-                   DLLAVA_EINVAL, "predict: block %d: matrices and bias vectors must be 16-byte aligned", i);
+                       aligned(k.bqkv, 16) && aligned(k.bo, 16) && aligned(k.bfc1, 16) && aligned(k.bfc2, 16) &&
+                       aligned(k.ln1_g, 16) && aligned(k.ln1_b, 16) && aligned(k.ln2_g, 16) && aligned(k.ln2_b, 16),
+                   DLLAVA_EINVAL, "predict: block %d: matrices and vectors must be 16-byte aligned", i);
   }
   const int nb = p->n_blocks;
   const Regions r = carve(workspace, M, B, nb);
@@ -305,6 +502,23 @@ extern "C" int dllava_predict(const void* x, int64_t ldx, int64_t M, int32_t B, 
   if (nb > 0 || seq_off) {
     hipLaunchKernelGGL(span_offsets_kernel, dim3(1), dim3(kWave), 0, st, seq_off ? vis_len : nullptr, B, M, r.span_off);
     DLLAVA_CHECK_LAUNCH("span_offsets_kernel");
+  }
+  if (nb == 0 && M <= kSmallRows) {  // a handful of rows: the output-text predictor of a decode step
+    const int nt = M <= 32 ? 1 : 2;
+    const int Mi = static_cast<int>(M), Ki = static_cast<int>(p->d);
+    const bf16_t* Wi = static_cast<const bf16_t*>(p->W_in);
+    if (nt == 1)
+      hipLaunchKernelGGL(small_in_kernel<1>, dim3(16 * kSmallSplit), dim3(256), 0, st, X, ldx, Mi, Ki, Wi, r.small, B,
+                         seq_off, vis_start, vis_len);
+    else
+      hipLaunchKernelGGL(small_in_kernel<2>, dim3(16 * kSmallSplit), dim3(256), 0, st, X, ldx, Mi, Ki, Wi, r.small, B,
+                         seq_off, vis_start, vis_len);
+    DLLAVA_CHECK_LAUNCH("small_in_kernel");
+    hipLaunchKernelGGL(small_head_kernel, dim3(nt), dim3(256), 0, st, r.small, 32 * nt, Mi, p->b_in,
+                       static_cast<const bf16_t*>(p->W_h1), p->b_h1, static_cast<const bf16_t*>(p->W_h2), p->b_h2,
+                       static_cast<const bf16_t*>(p->W_h3), p->b_h3, logits, seq_off ? r.span_off : nullptr, B);
+    DLLAVA_CHECK_LAUNCH("small_head_kernel");
+    return DLLAVA_OK;
   }
   {  // z = x W_in^T + b_in over the rows of the spans
     LinArgs a = lin(X, ldx, static_cast<int>(p->d), p->W_in, p->b_in, kPW, r.Z, kPW, 0, nullptr);
@@ -377,7 +591,8 @@ extern "C" int dllava_layer_norm(const void* z, int64_t M, const float* gamma, c
   DLLAVA_REQUIRE(M >= 0 && M <= 0x7fffffffLL, DLLAVA_ESHAPE, "layer_norm: bad M = %lld", (long long)M);
   if (M == 0) return DLLAVA_OK;
   DLLAVA_REQUIRE(z && y, DLLAVA_ENULL, "layer_norm: z and y are required");
-  DLLAVA_REQUIRE(aligned(z, 16) && aligned(y, 16), DLLAVA_EINVAL, "layer_norm: z and y must be 16-byte aligned");
+  DLLAVA_REQUIRE(aligned(z, 16) && aligned(y, 16) && aligned(gamma, 16) && aligned(beta, 16), DLLAVA_EINVAL,
+                 "layer_norm: z, y, gamma, beta must be 16-byte aligned");
   hipLaunchKernelGGL(ln_kernel, dim3(static_cast<unsigned>(ceil_div(M, 4))), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const bf16_t*>(z), static_cast<bf16_t*>(y), gamma,
                      beta, M);

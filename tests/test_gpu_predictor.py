@@ -49,7 +49,7 @@ def _wl(d, n_sys, n_vis, n_prompt, seed):
     return W.make("pp", "bf16", d, 2, 64, B, n_sys, n_vis, n_prompt, 0.5, 1, seed=seed)
 
 
-@pytest.mark.parametrize("M,d", [(1, 64), (16, 256), (70, 128), (300, 64)])
+@pytest.mark.parametrize("M,d", [(1, 64), (16, 256), (33, 192), (64, 320), (65, 64), (70, 128), (300, 64)])
 def test_text_predictor_rows(M, d):
     h = _H()
     w = _wl(d, [0], [M], [0], 31 + M)
@@ -230,3 +230,39 @@ def test_span_attention_layer(lens, H, Dh):
     # the probabilities enter the second product with 16 significant bits: close to, not at, the output's rounding
     assert np.abs(got - ref).max() <= 2.0 ** -7 * max(1.0, np.abs(ref).max())
     assert (h.bits(o) != R.narrow(ref, "bf16")).mean() <= 0.05
+
+
+def test_image_predictor_at_the_benchmark_shape():
+    """8 sequences x 2880 image tokens, d = 4096 (the long-context workload), in the launch shapes the benchmark times.
+    The oracle evaluates one whole sequence (the spans do not interact) and the first rows of another."""
+    h = _H()
+    B, n, d = 8, 2880, 4096
+    w = _wl(d, [0] * B, [n] * B, [0] * B, 2024)
+    Pw = W.paper_predictor(w, 2)
+    hidden = W.store(W._normal_big(w.seed, "hid", (B * n, d)), "bf16")
+    M = B * n
+    off = (np.arange(B + 1) * n).astype(np.int32)
+    logits = torch.full((M, 2), float("nan"), dtype=torch.float32, device=h.DEV)
+    dev_i = lambda a: torch.from_numpy(np.asarray(a, np.int32)).to(h.DEV)
+    P.dllava_predict(h.to_dev(hidden, "bf16"), d, M, B, dev_i(off), dev_i([0] * B), dev_i([n] * B), upload(h, Pw, d),
+                     P.BF16, logits, _workspace(h, M, B, 2))
+    got = logits.cpu().numpy()
+    assert np.isfinite(got).all()
+    b = 5
+    ref = PR.predict(hidden[off[b]:off[b + 1]], np.array([0, n]), Pw, "bf16")
+    err = got[off[b]:off[b + 1]] - ref
+    assert np.abs(err).max() <= TOL_IMAGE, np.abs(err).max()
+    assert np.sqrt(np.mean(err ** 2)) <= RMS_IMAGE
+    # the sequences differ from one another (no span read another's rows by mistake)
+    assert np.abs(got[off[0]:off[1]] - got[off[b]:off[b + 1]]).max() > 0.1
+
+
+def test_text_predictor_at_the_benchmark_shape():
+    h = _H()
+    B, d = 16, 4096
+    w = _wl(d, [0], [B], [0], 2025)
+    Pw = W.paper_predictor(w, 0)
+    x = W.store(rng.normal(w.seed, "x", (B, d)) * 1.3, "bf16")
+    logits = torch.zeros((B, 2), dtype=torch.float32, device=h.DEV)
+    P.dllava_predict(h.to_dev(x, "bf16"), d, B, 0, None, None, None, upload(h, Pw, d), P.BF16, logits, _workspace(h, B, 0, 0))
+    assert np.abs(logits.cpu().numpy() - PR.predict(x, None, Pw, "bf16")).max() <= TOL

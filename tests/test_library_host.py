@@ -169,3 +169,48 @@ def test_score_workspace_is_monotonic_in_rows(lib):
     for d, dh in ((4096, 1024), (256, 64), (64, 1)):
         sizes = [lib.dllava_score_workspace(m, d, dh, lib.BF16) for m in (1, 16, 17, 64, 65, 200, 5000, 100000)]
         assert sizes == sorted(sizes), (d, dh, sizes)
+
+
+def test_predictor_entry_points_validate_on_the_host(lib):
+    L = lib.lib()
+    EINVAL, ENULL, ESHAPE, EDTYPE, EWORKSPACE = -1, -2, -3, -4, -6
+    fake = C.c_void_p(0x1000)       # never dereferenced: every call below must fail validation first
+    p = lib._Predictor()
+    p.d, p.n_blocks = 128, 0
+    p.W_in = p.W_h1 = p.W_h2 = p.W_h3 = 0x1000
+    big = 1 << 30
+    call = lambda pp, dtype, ldx, M, ws, wsb, x=fake: (x, ldx, M, 0, None, None, None, pp, dtype, fake, ws, wsb, None)
+    _expect(lib, ENULL, L.dllava_predict, *call(None, 1, 128, 4, fake, big))
+    _expect(lib, EDTYPE, L.dllava_predict, *call(C.byref(p), 0, 128, 4, fake, big))       # float32 is not offered
+    _expect(lib, ESHAPE, L.dllava_predict, *call(C.byref(p), 1, 120, 4, fake, big))       # ldx < d
+    _expect(lib, EWORKSPACE, L.dllava_predict, *call(C.byref(p), 1, 128, 4, None, 0))
+    _expect(lib, EWORKSPACE, L.dllava_predict, *call(C.byref(p), 1, 128, 4, fake, 64))
+    _expect(lib, ENULL, L.dllava_predict, *call(C.byref(p), 1, 128, 4, fake, big, x=None))
+    assert L.dllava_predict(*call(C.byref(p), 1, 128, 0, None, 0)) == 0                   # M == 0: nothing to do
+    q = lib._Predictor()
+    q.d, q.n_blocks = 100, 0
+    q.W_in = q.W_h1 = q.W_h2 = q.W_h3 = 0x1000
+    _expect(lib, ESHAPE, L.dllava_predict, *call(C.byref(q), 1, 128, 4, fake, big))       # d % 64
+    q.d, q.n_blocks = 128, 5
+    _expect(lib, EINVAL, L.dllava_predict, *call(C.byref(q), 1, 128, 4, fake, big))
+    q.n_blocks = 1                                                                       # a block without matrices
+    _expect(lib, ENULL, L.dllava_predict, *call(C.byref(q), 1, 128, 4, fake, big))
+    # spans need all three arrays
+    _expect(lib, ENULL, L.dllava_predict, fake, 128, 4, 1, fake, None, None, C.byref(p), 1, fake, fake, big, None)
+    # workspace query: grows with the rows, image form needs more than the text form
+    assert lib.dllava_predict_workspace(1000, 4, 2) > lib.dllava_predict_workspace(1000, 4, 0) > 0
+    assert lib.dllava_predict_workspace(2000, 4, 2) > lib.dllava_predict_workspace(1000, 4, 2)
+    assert lib.dllava_predict_workspace(1000, 4, 2) % 256 == 0
+    # the layers
+    _expect(lib, ESHAPE, L.dllava_linear, fake, 100, 4, 100, fake, None, 64, 0, None, fake, 64, 1, None)   # K % 64
+    _expect(lib, ESHAPE, L.dllava_linear, fake, 128, 4, 128, fake, None, 60, 0, None, fake, 64, 1, None)   # N % 8
+    _expect(lib, ESHAPE, L.dllava_linear, fake, 128, 4, 128, fake, None, 64, 0, None, fake, 56, 1, None)   # ldy < N
+    _expect(lib, EINVAL, L.dllava_linear, fake, 128, 4, 128, fake, None, 64, 2, None, fake, 64, 1, None)   # act
+    _expect(lib, EDTYPE, L.dllava_linear, fake, 128, 4, 128, fake, None, 64, 0, None, fake, 64, 0, None)
+    _expect(lib, ENULL, L.dllava_linear, fake, 128, 4, 128, None, None, 64, 0, None, fake, 64, 1, None)
+    _expect(lib, EINVAL, L.dllava_linear, C.c_void_p(0x1008), 128, 4, 128, fake, None, 64, 0, None, fake, 64, 1, None)
+    _expect(lib, ENULL, L.dllava_layer_norm, None, 4, None, None, fake, 1, None)
+    _expect(lib, EDTYPE, L.dllava_layer_norm, fake, 4, None, None, fake, 0, None)
+    _expect(lib, ESHAPE, L.dllava_span_attn, fake, fake, fake, 1, fake, 8, 8, 96, 0.1, fake, 1, None)
+    _expect(lib, ENULL, L.dllava_span_attn, fake, fake, fake, 1, None, 8, 8, 64, 0.1, fake, 1, None)
+    _expect(lib, EINVAL, L.dllava_span_attn, fake, fake, fake, 1, fake, 8, 8, 64, float("nan"), fake, 1, None)
