@@ -238,8 +238,8 @@ __global__ __launch_bounds__(kWave) void span_offsets_kernel(const int32_t* __re
 // ---- the output-text predictor on a handful of rows (one per sequence and decode step) ---------------------------
 // With at most 64 rows the tile kernel above would pull the 2*512*d bytes of W_in through four compute units.
 // small_in_kernel spreads W_in over 64 blocks of 4 waves: block = 32 output features x a quarter of d, wave = a
-// sixteenth of d, fragments straight from global memory (every byte of W_in is read once, all loads of a wave in
-// flight together), the four waves summed through LDS in wave order, one partial per block.  small_head_kernel
+// sixteenth of d (every byte of W_in is read once, all loads of a wave in flight together), the four waves summed
+// through LDS in wave order, one partial per block.  small_head_kernel
 // (one block per 32 rows) adds the four partials and the bias in a fixed order, rounds the 512 features to the
 // storage type into LDS, and runs the head 512 -> 256 -> 128 -> 2 from there on the matrix cores, the weights of
 // both layers requested at its very start.
@@ -247,6 +247,19 @@ constexpr int kSmallRows = 64;
 constexpr int kSmallSplit = 4;    // blocks along d
 constexpr int kZs = 520, kH1s = 264, kH2s = 136;  // LDS row strides (elements): 16-byte pieces of 16 rows fall in 16 bank groups
 
+// Register-to-LDS order inside ONE wave: the area written and read is private to the wave and the wave's LDS
+// instructions execute in order; the fences only keep the compiler from moving them across one another.
+__device__ __forceinline__ void wave_lds_order() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+__device__ __forceinline__ void want_now(const uint4& v) { asm volatile("" ::"v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
+
+// Operands are loaded 8 lanes per 128-byte line (a load instruction then touches 8 whole lines; a fragment-shaped
+// load, one row per lane, touches 32 lines for the same bytes and was measured 4x slower here) and turned into
+// matrix-core fragments through a wave-private LDS area in the swizzled row-major form of gemm_tile.h: chunk c of
+// row rr at chunk position c ^ ((rr / 2) % 8).
 template <int NT>  // tiles of 32 rows
 __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict__ X, int64_t ldx, int M, int K,
                                                        const bf16_t* __restrict__ W, float* __restrict__ partial,
@@ -254,43 +267,79 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
                                                        const int32_t* __restrict__ vis_start,
                                                        const int32_t* __restrict__ vis_len) {
   __shared__ float red[3][NT][16][kWave];
+  __shared__ __align__(16) bf16_t stage[4][(1 + NT) * 32 * 64];  // per wave: 32 weight rows and 32*NT input rows x 64 elements
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
   const int fg = blockIdx.x & 15, kq = blockIdx.x >> 4;
   const int r = lane & 31, g = lane >> 5;
-  const int total = K / 16;            // steps of 16 elements of d
-  const int per = (total + 15) / 16;   // steps of one wave (16 slices: 4 blocks x 4 waves)
-  const int sbeg = (kq * 4 + w) * per;
-  const int send = sbeg + per < total ? sbeg + per : total;
-  const bf16_t* wrow = W + static_cast<int64_t>(32 * fg + r) * K + 8 * g;
-  const bf16_t* xrow[NT];
+  const int lr8 = lane >> 3, lc = lane & 7;
+  const int total = K / 64;            // 128-byte lines per row
+  const int per = (total + 15) / 16;   // lines of one wave (16 slices of d: 4 blocks x 4 waves)
+  const int lbeg = (kq * 4 + w) * per;
+  const int lend = lbeg + per < total ? lbeg + per : total;
+  // this lane's rows: 8j + lane/8 of the 32 weight rows and of every 32-row input tile
+  const bf16_t* wrow[4];
+  const bf16_t* xrow[NT][4];
 #pragma unroll
-  for (int tt = 0; tt < NT; ++tt) {
-    int64_t m = 32 * tt + r;
-    if (m >= M) m = M - 1;  // rows past M repeat the last one and are dropped later
-    int64_t sr = score_src_row(seq_off, vis_start, vis_len, B, m);
-    if (sr < 0) sr = 0;
-    xrow[tt] = X + sr * ldx + 8 * g;
+  for (int j = 0; j < 4; ++j) {
+    wrow[j] = W + static_cast<int64_t>(32 * fg + 8 * j + lr8) * K + 8 * lc;
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt) {
+      int64_t m = 32 * tt + 8 * j + lr8;
+      if (m >= M) m = M - 1;  // rows past M repeat the last one and are dropped later
+      int64_t sr = score_src_row(seq_off, vis_start, vis_len, B, m);
+      if (sr < 0) sr = 0;
+      xrow[tt][j] = X + sr * ldx + 8 * lc;
+    }
   }
   f32x16 acc[NT];
 #pragma unroll
   for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[tt][i] = 0.f;
-  for (int s0 = sbeg; s0 < send; s0 += 16) {
-    uint4 wf[16], xf[NT][16];
+  bf16_t* sw = stage[w];
+  bf16_t* sx = sw + 32 * 64;
+  const int st_off = lr8 * 64 + ((lc ^ ((lr8 >> 1) & 3)) * 8);  // row 8j + lane/8: ((8j + lr8) / 2) % 8 = 4*(j%2) + lr8/2
+  const int fr_off = r * 64 + ((g ^ ((r >> 1) & 7)) * 8);       // row r, chunk 2*step + g
+  for (int l0 = lbeg; l0 < lend; l0 += 4) {
+    uint4 wf[4][4], xf[NT][4][4];  // [line of the batch][row group j]
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {  // all loads of the batch first (past the end: the last step again, unused)
-      const int sidx = s0 + u < send ? s0 + u : send - 1;
-      wf[u] = *reinterpret_cast<const uint4*>(wrow + 16 * sidx);
+    for (int c = 0; c < 4; ++c) {  // all loads of the batch first (past the end: the last line again, unused)
+      const int line = l0 + c < lend ? l0 + c : lend - 1;
 #pragma unroll
-      for (int tt = 0; tt < NT; ++tt) xf[tt][u] = *reinterpret_cast<const uint4*>(xrow[tt] + 16 * sidx);
+      for (int j = 0; j < 4; ++j) {
+        wf[c][j] = *reinterpret_cast<const uint4*>(wrow[j] + 64 * line);
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) xf[tt][c][j] = *reinterpret_cast<const uint4*>(xrow[tt][j] + 64 * line);
+      }
     }
 #pragma unroll
-    for (int u = 0; u < 16; ++u)
-      if (s0 + u < send) {  // wave-uniform
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int tt = 0; tt < NT; ++tt)
-          acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(wf[u]), as_frag(xf[tt][u]), acc[tt], 0, 0, 0);
+      for (int j = 0; j < 4; ++j) {
+        want_now(wf[c][j]);
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) want_now(xf[tt][c][j]);
+      }
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (l0 + c < lend) {  // wave-uniform
+        wave_lds_order();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int o = 8 * j * 64 + (st_off ^ ((j & 1) * 32));
+          *reinterpret_cast<uint4*>(sw + o) = wf[c][j];
+#pragma unroll
+          for (int tt = 0; tt < NT; ++tt) *reinterpret_cast<uint4*>(sx + tt * 32 * 64 + o) = xf[tt][c][j];
+        }
+        wave_lds_order();
+#pragma unroll
+        for (int sk = 0; sk < 4; ++sk) {
+          const bf16x8 fa = as_frag(*reinterpret_cast<const uint4*>(sw + (fr_off ^ (sk * 16))));
+#pragma unroll
+          for (int tt = 0; tt < NT; ++tt)
+            acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                fa, as_frag(*reinterpret_cast<const uint4*>(sx + tt * 32 * 64 + (fr_off ^ (sk * 16)))), acc[tt], 0, 0, 0);
+        }
       }
   }
   if (w > 0) {
@@ -328,48 +377,103 @@ __global__ __launch_bounds__(256) void small_head_kernel(const float* __restrict
   __shared__ __align__(16) bf16_t zT[32 * kZs];
   __shared__ __align__(16) bf16_t h1T[32 * kH1s];
   __shared__ __align__(16) bf16_t h2T[32 * kH2s];
+  __shared__ __align__(16) bf16_t stage[4][64 * 64];  // per wave: 64 weight rows x 64 elements
+  __shared__ float w3s[2 * kPH2];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
   const int r = lane & 31, g = lane >> 5;
+  const int lr8 = lane >> 3, lc = lane & 7;
   const int t0 = blockIdx.x * 32;
-  // the weights of both layers: wave w owns features 64w..64w+63 of the first and 32w..32w+31 of the second
-  uint4 f1a[32], f1b[32], f2[16];
-  {
-    const bf16_t* wa = W1 + static_cast<int64_t>(64 * w + r) * kPW + 8 * g;
-    const bf16_t* wb = wa + 32 * kPW;
-    const bf16_t* wc = W2 + static_cast<int64_t>(32 * w + r) * kPH1 + 8 * g;
+  const bf16_t w3v = W3[tid];  // last layer's 2 x 128 weights: one per thread, into LDS before the first barrier
+  // The weights of both layers, requested before anything else: wave w owns features 64w..64w+63 of the first layer
+  // and 32w..32w+31 of the second.  Register [j][c] of a lane: row 8j + lane/8 of the wave's rows, elements
+  // 64c + 8*(lane%8) .. +7.
+  uint4 w1r[8][8], w2r[4][4];
 #pragma unroll
-    for (int u = 0; u < 32; ++u) {
-      f1a[u] = *reinterpret_cast<const uint4*>(wa + 16 * u);
-      f1b[u] = *reinterpret_cast<const uint4*>(wb + 16 * u);
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+      w1r[j][c] = *reinterpret_cast<const uint4*>(W1 + static_cast<int64_t>(64 * w + 8 * j + lr8) * kPW + 64 * c + 8 * lc);
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      w2r[j][c] = *reinterpret_cast<const uint4*>(W2 + static_cast<int64_t>(32 * w + 8 * j + lr8) * kPH1 + 64 * c + 8 * lc);
+  // z = bias + the partial sums, in a fixed order, rounded to the storage type: rows of this tile that exist only
+  // (the others stay undefined in LDS: a row only ever influences its own outputs, which are dropped), four
+  // items per thread at a time; the loads of the first four are issued together with the weights.
+  const int n_valid = M - t0 < 32 ? M - t0 : 32;
+  const int items = n_valid * (kPW / 4);
+  float4 sum[4], pq[4][kSmallSplit];
+  auto z_load = [&](int base) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      int it = base + 256 * u + tid;
+      if (it >= items) it = items - 1;
+      const int tok = it / (kPW / 4), f = (it % (kPW / 4)) * 4;
+      sum[u] = *reinterpret_cast<const float4*>(b_in ? b_in + f : kZeroWords);
+#pragma unroll
+      for (int q = 0; q < kSmallSplit; ++q)
+        pq[u][q] = *reinterpret_cast<const float4*>(partial + static_cast<int64_t>(q * rows_pad + t0 + tok) * kPW + f);
     }
+  };
+  auto z_finish = [&](int base) {
 #pragma unroll
-    for (int u = 0; u < 16; ++u) f2[u] = *reinterpret_cast<const uint4*>(wc + 16 * u);
-  }
-  // z = bias + the partial sums, in a fixed order, rounded to the storage type
-  for (int it = tid; it < 32 * (kPW / 4); it += 256) {
-    const int tok = it / (kPW / 4), f = (it % (kPW / 4)) * 4;
-    float4 sum = *reinterpret_cast<const float4*>(b_in ? b_in + f : kZeroWords);
+    for (int u = 0; u < 4; ++u) {
+      const int it = base + 256 * u + tid;
+      if (it < items) {
+        const int tok = it / (kPW / 4), f = (it % (kPW / 4)) * 4;
 #pragma unroll
-    for (int q = 0; q < kSmallSplit; ++q) {
-      const float4 pq = *reinterpret_cast<const float4*>(partial + static_cast<int64_t>(q * rows_pad + t0 + tok) * kPW + f);
-      sum.x += pq.x; sum.y += pq.y; sum.z += pq.z; sum.w += pq.w;
+        for (int q = 0; q < kSmallSplit; ++q) {
+          sum[u].x += pq[u][q].x; sum[u].y += pq[u][q].y; sum[u].z += pq[u][q].z; sum[u].w += pq[u][q].w;
+        }
+        uint2 v;
+        v.x = pack_bf16x2(sum[u].x, sum[u].y);
+        v.y = pack_bf16x2(sum[u].z, sum[u].w);
+        *reinterpret_cast<uint2*>(zT + tok * kZs + f) = v;
+      }
     }
-    uint2 v;
-    v.x = pack_bf16x2(sum.x, sum.y);
-    v.y = pack_bf16x2(sum.z, sum.w);
-    *reinterpret_cast<uint2*>(zT + tok * kZs + f) = v;
+  };
+  z_load(0);
+  // The weights are wanted in registers HERE, all loads of a lane in flight together: without a use at this point
+  // the compiler moves each load down to its slice of the product, one memory round trip per slice.
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) want_now(w1r[j][c]);
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) want_now(w2r[j][c]);
+  w3s[tid] = bf16_to_f32(w3v);
+  z_finish(0);
+  for (int base = 4 * 256; base < items; base += 4 * 256) {
+    z_load(base);
+    z_finish(base);
   }
   __syncthreads();
+  bf16_t* st = stage[w];
+  const int st_off = lr8 * 64 + ((lc ^ ((lr8 >> 1) & 3)) * 8);  // row 8j + lane/8: ((8j + lr8) / 2) % 8 = 4*(j%2) + lr8/2
+  const int fr_off = r * 64 + ((g ^ ((r >> 1) & 7)) * 8);       // row r (+32), chunk 2s + g
   {  // h1 = GELU(W1 z + b1): two 32-feature tiles per wave
     f32x16 a0, a1;
 #pragma unroll
     for (int i = 0; i < 16; ++i) a0[i] = a1[i] = 0.f;
     const bf16_t* zb = zT + r * kZs + 8 * g;
 #pragma unroll
-    for (int u = 0; u < 32; ++u) {
-      const bf16x8 bz = as_frag(*reinterpret_cast<const uint4*>(zb + 16 * u));
-      a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(f1a[u]), bz, a0, 0, 0, 0);
-      a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(f1b[u]), bz, a1, 0, 0, 0);
+    for (int c = 0; c < 8; ++c) {
+      wave_lds_order();
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        *reinterpret_cast<uint4*>(st + 8 * j * 64 + (st_off ^ ((j & 1) * 32))) = w1r[j][c];
+      wave_lds_order();
+#pragma unroll
+      for (int sk = 0; sk < 4; ++sk) {
+        const bf16x8 bz = as_frag(*reinterpret_cast<const uint4*>(zb + 64 * c + 16 * sk));
+        const bf16x8 fa = as_frag(*reinterpret_cast<const uint4*>(st + (fr_off ^ (sk * 16))));
+        const bf16x8 fb = as_frag(*reinterpret_cast<const uint4*>(st + 32 * 64 + (fr_off ^ (sk * 16))));
+        a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, bz, a0, 0, 0, 0);
+        a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, bz, a1, 0, 0, 0);
+      }
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -391,9 +495,19 @@ __global__ __launch_bounds__(256) void small_head_kernel(const float* __restrict
     for (int i = 0; i < 16; ++i) a[i] = 0.f;
     const bf16_t* hb = h1T + r * kH1s + 8 * g;
 #pragma unroll
-    for (int u = 0; u < 16; ++u)
-      a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(f2[u]), as_frag(*reinterpret_cast<const uint4*>(hb + 16 * u)), a,
-                                                  0, 0, 0);
+    for (int c = 0; c < 4; ++c) {
+      wave_lds_order();
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        *reinterpret_cast<uint4*>(st + 8 * j * 64 + (st_off ^ ((j & 1) * 32))) = w2r[j][c];
+      wave_lds_order();
+#pragma unroll
+      for (int sk = 0; sk < 4; ++sk) {
+        const bf16x8 bh = as_frag(*reinterpret_cast<const uint4*>(hb + 64 * c + 16 * sk));
+        const bf16x8 fa = as_frag(*reinterpret_cast<const uint4*>(st + (fr_off ^ (sk * 16))));
+        a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, bh, a, 0, 0, 0);
+      }
+    }
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
       const int f = 32 * w + 8 * q4 + 4 * g;
@@ -405,13 +519,17 @@ __global__ __launch_bounds__(256) void small_head_kernel(const float* __restrict
     }
   }
   __syncthreads();
-  if (tid < 64) {  // the two logits of a row: a float32 sum over the 128 inputs in ascending order
-    const int tok = tid >> 1, c = tid & 1;
+  {  // the two logits of a row: four threads sum a quarter of the 128 inputs each, combined in a fixed order
+    const int out = tid >> 2, part = tid & 3, tok = out >> 1, c = out & 1;
     const int64_t m = t0 + tok;
     const int64_t lim = span_off ? span_off[B] : M;
-    float sum = b3 ? b3[c] : 0.f;
-    for (int k = 0; k < kPH2; ++k) sum = fmaf(bf16_to_f32(h2T[tok * kH2s + k]), bf16_to_f32(W3[c * kPH2 + k]), sum);
-    if (m < M && m < lim) logits[2 * m + c] = sum;
+    float ps = 0.f;
+#pragma unroll
+    for (int k = 32 * part; k < 32 * part + 32; ++k) ps = fmaf(bf16_to_f32(h2T[tok * kH2s + k]), w3s[c * kPH2 + k], ps);
+    const int l0 = lane & ~3;
+    const float p0 = __shfl(ps, l0, kWave), p1 = __shfl(ps, l0 + 1, kWave), p2 = __shfl(ps, l0 + 2, kWave),
+                p3 = __shfl(ps, l0 + 3, kWave);
+    if (part == 0 && m < M && m < lim) logits[2 * m + c] = ((((b3 ? b3[c] : 0.f) + p0) + p1) + p2) + p3;
   }
 }
 
