@@ -26,6 +26,9 @@ Conventions
   * Paged cache layout: pages[n_pages][2 (K,V)][H][page_size][Dh]; token t of
     sequence b lives in page block_table[b, t // page_size], slot t % page_size.
 
+  * Training form (Eq. 7): the same attention on the full token set with the mask inside the softmax;
+    ``masked_attn`` is that definition written out, every row (kept or not) gets an output.
+
   * Projection of the reduced set (Eq. 3, first line, applied to S^{P*}): Q, K, V
     of the kept rows only; queries and keys optionally rotated by the ORIGINAL
     position of each kept token (rotary embedding of the LLaMA decoder).
@@ -244,6 +247,30 @@ def prefill_attn(Q, K, V, off, scale: float, dtype: str) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------- Eq. 6
+
+def masked_attn(Q, K, V, off, keep, scale: float, dtype: str) -> np.ndarray:
+    """Attention of the end-to-end sparsification training (Sec. 3.3.3, Eq. 7) on the FULL token set.
+
+    Per sequence and head, with X = scale * Q K^T: weights exp(X_ij) G_ij / sum_k exp(X_ik) G_ik, where
+    G_ij = keep[j] for j < i, G_ii = 1 (the diagonal is set to one), and G_ij = 0 for j > i (the decoder's causal
+    order).  Every row gets an output, also the rows whose own mask entry is 0.  Returns O [rows, H, Dh] float64.
+    """
+    Qf, Kf, Vf = widen(Q, dtype), widen(K, dtype), widen(V, dtype)
+    keep = np.asarray(keep).astype(bool)
+    O = np.zeros(Qf.shape, dtype=np.float64)
+    for b in range(len(off) - 1):
+        r0, r1 = int(off[b]), int(off[b + 1])
+        n = r1 - r0
+        if n == 0:
+            continue
+        G = np.tril(np.broadcast_to(keep[r0:r1][None, :], (n, n)) | np.eye(n, dtype=bool))
+        for h in range(Qf.shape[1]):
+            x = (Qf[r0:r1, h] @ Kf[r0:r1, h].T) * scale
+            x = np.where(G, x, -np.inf)
+            e = np.exp(x - x.max(axis=1, keepdims=True)) * G
+            O[r0:r1, h] = (e @ Vf[r0:r1, h]) / e.sum(axis=1, keepdims=True)
+    return O
+
 
 def decode_keep(logits, theta, keep_override=None) -> np.ndarray:
     if keep_override is not None:

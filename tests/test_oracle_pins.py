@@ -281,6 +281,40 @@ def test_gather_form_equals_masked_softmax_form():
     assert list(cache.cache_len) == exp_len
 
 
+def test_masked_attn_matches_loops_and_its_special_cases():
+    """R.masked_attn (Eq. 7 on the full token set) against the loop form above, and: all-ones mask = causal attention,
+    all-zeros mask = every row returns its own value, kept rows = attention over the compacted sequence, a dropped
+    token influences no row but its own."""
+    w, pre, dec = _tiny("bf16", T=1, ratio=0.4)
+    f = lambda a: W.stored_to_f32(a, "bf16").astype(np.float64)
+    scale = 1.0 / math.sqrt(w.Dh)
+    r = np.random.RandomState(3)
+    keep = (r.rand(w.sumN) < 0.5).astype(np.uint8)
+    O = R.masked_attn(pre["Q"], pre["K"], pre["V"], w.seq_off, keep, scale, "bf16")
+    for b in range(w.B):
+        s0, s1 = int(w.seq_off[b]), int(w.seq_off[b + 1])
+        for h in range(w.H):
+            dense = _masked_softmax_attention(f(pre["Q"])[s0:s1, h], f(pre["K"])[s0:s1, h], f(pre["V"])[s0:s1, h],
+                                              list(keep[s0:s1]), scale)
+            assert np.allclose(O[s0:s1, h], dense, atol=1e-12)
+    ones = R.masked_attn(pre["Q"], pre["K"], pre["V"], w.seq_off, np.ones(w.sumN, np.uint8), scale, "bf16")
+    assert np.allclose(ones, R.prefill_attn(pre["Q"], pre["K"], pre["V"], w.seq_off, scale, "bf16"), atol=1e-12)
+    zeros = R.masked_attn(pre["Q"], pre["K"], pre["V"], w.seq_off, np.zeros(w.sumN, np.uint8), scale, "bf16")
+    assert np.allclose(zeros, f(pre["V"]), atol=1e-12)
+    # kept rows: the compacted sequence attended causally
+    idx = np.flatnonzero(keep)
+    off_c = np.concatenate([[0], np.cumsum([keep[w.seq_off[b]:w.seq_off[b + 1]].sum() for b in range(w.B)])])
+    Oc = R.prefill_attn(pre["Q"][idx], pre["K"][idx], pre["V"][idx], off_c, scale, "bf16")
+    assert np.allclose(O[idx], Oc, atol=1e-12)
+    # a dropped token's key and value matter to its own row only
+    j = int(np.flatnonzero(keep == 0)[1])
+    K2, V2 = pre["K"].copy(), pre["V"].copy()
+    K2[j], V2[j] = pre["K"][j - 1], pre["V"][j - 1]
+    O2 = R.masked_attn(pre["Q"], K2, V2, w.seq_off, keep, scale, "bf16")
+    others = np.arange(w.sumN) != j
+    assert np.array_equal(O2[others], O[others]) and not np.allclose(O2[j], O[j])
+
+
 def test_decode_closed_forms():
     H, Dh = 2, 8
     bt = np.array([[1, 0]], np.int32)
