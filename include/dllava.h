@@ -11,6 +11,7 @@
  *   dllava_decode_step         the same step, scoring + attention in one launch, append deferred by one step
  *   dllava_qkv_project         Q, K, V of the reduced set, K/V into the cache (Eq. 3 line 1 with S^{P*})
  *   dllava_predict             predictor logits with the predictors of Appendix A.4.1 (in place of dllava_score)
+ *   dllava_masked_attn         attention of the training form, mask inside the softmax (Eq. 7)
  *
  * General conventions
  *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller
@@ -353,6 +354,25 @@ size_t dllava_predict_workspace(int64_t M, int32_t B, int32_t n_blocks);
  *   mask);  Q, K, V, O [rows, H, Dh] contiguous;  off [B+1] row offsets of the spans;  rows = host upper bound on
  *   off[B];  Dh in {64, 128}.
  */
+/*
+ * Attention of the end-to-end sparsification training on the FULL token set (Sec. 3.3.3, Eq. 7): the keep mask acts
+ * inside the softmax instead of removing tokens.  For sequence b, head h and row i:
+ *     O_i = sum_{j<=i} w_ij V_j,   w_ij = exp(scale q_i.k_j) G_ij / sum_{k<=i} exp(scale q_i.k_k) G_ik,
+ *     G_ij = keep_mask[j] for j < i,  G_ii = 1
+ * (causal order of the decoder; the diagonal of the mask matrix is one).  Every row gets an output, also rows whose
+ * own mask entry is 0; on the rows with mask 1 the result equals dllava_prefill_attn over the compacted sequence.
+ *
+ *   Q, K, V, O  [rows, H, Dh] dtype (DLLAVA_BF16 only), all tokens of the batch, sequences back to back
+ *   off       [B+1] row offsets of the sequences;  rows = host upper bound on off[B]
+ *   keep_mask [rows] uint8, 0 = dropped, anything else = kept (keep_mask of dllava_select_compact)
+ *   workspace device, 256-byte aligned, dllava_masked_attn_workspace(rows, B) bytes, scratch (need not be initialised)
+ * Sizes: Dh in {64, 128}, scale > 0.
+ */
+int dllava_masked_attn(const void* Q, const void* K, const void* V, int32_t B, const int32_t* off, int64_t rows,
+                       int32_t H, int32_t Dh, float scale, const uint8_t* keep_mask, void* O, int dtype,
+                       void* workspace, size_t workspace_bytes, void* stream);
+size_t dllava_masked_attn_workspace(int64_t rows, int32_t B);
+
 int dllava_linear(const void* x, int64_t ldx, int64_t M, int64_t K, const void* W, const float* bias, int64_t N,
                   int act, const void* residual, void* y, int64_t ldy, int dtype, void* stream);
 int dllava_layer_norm(const void* z, int64_t M, const float* gamma, const float* beta, void* y, int dtype,

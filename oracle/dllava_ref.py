@@ -272,6 +272,25 @@ def masked_attn(Q, K, V, off, keep, scale: float, dtype: str) -> np.ndarray:
     return O
 
 
+def masked_attn_rows(Q, K, V, off, keep, scale: float, dtype: str, rows) -> np.ndarray:
+    """Rows `rows` (global row numbers) of masked_attn, one by one, for sequences too long for the dense form."""
+    off = np.asarray(off)
+    keep = np.asarray(keep).astype(bool)
+    out = np.zeros((len(rows),) + tuple(np.shape(Q)[1:]), dtype=np.float64)
+    for n_out, i in enumerate(rows):
+        b = int(np.searchsorted(off, i, side="right") - 1)
+        r0 = int(off[b])
+        q = widen(Q[i], dtype)
+        Kf, Vf = widen(K[r0:i + 1], dtype), widen(V[r0:i + 1], dtype)
+        g = keep[r0:i + 1].copy()
+        g[-1] = True                                   # diag(G) = 1
+        for h in range(q.shape[0]):
+            x = (Kf[:, h] @ q[h]) * scale
+            e = np.exp(x - x[g].max()) * g
+            out[n_out, h] = (e @ Vf[:, h]) / e.sum()
+    return out
+
+
 def decode_keep(logits, theta, keep_override=None) -> np.ndarray:
     if keep_override is not None:
         return (np.asarray(keep_override) != 0).astype(np.uint8)

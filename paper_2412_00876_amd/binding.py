@@ -87,6 +87,10 @@ def _load() -> C.CDLL:
     lib.dllava_predict.argtypes = [vp, i64, i64, i32, vp, vp, vp, C.POINTER(_Predictor), C.c_int, vp, vp, sz, vp]
     lib.dllava_predict_workspace.restype = sz
     lib.dllava_predict_workspace.argtypes = [i64, i32, i32]
+    lib.dllava_masked_attn.restype = C.c_int
+    lib.dllava_masked_attn.argtypes = [vp, vp, vp, i32, vp, i64, i32, i32, f32, vp, vp, C.c_int, vp, sz, vp]
+    lib.dllava_masked_attn_workspace.restype = sz
+    lib.dllava_masked_attn_workspace.argtypes = [i64, i32]
     lib.dllava_linear.restype = C.c_int
     lib.dllava_linear.argtypes = [vp, i64, i64, i64, vp, vp, i64, C.c_int, vp, vp, i64, C.c_int, vp]
     lib.dllava_layer_norm.restype = C.c_int
@@ -101,7 +105,8 @@ EXPORTS = ("dllava_version", "dllava_last_error", "dllava_score", "dllava_score_
            "dllava_select_compact", "dllava_select_compact_workspace", "dllava_prefill_attn",
            "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_qkv_project",
            "dllava_decode_step", "dllava_decode_step_workspace", "dllava_decode_commit",
-           "dllava_predict", "dllava_predict_workspace", "dllava_linear", "dllava_layer_norm", "dllava_span_attn")
+           "dllava_predict", "dllava_predict_workspace", "dllava_linear", "dllava_layer_norm", "dllava_span_attn",
+           "dllava_masked_attn", "dllava_masked_attn_workspace")
 
 
 def lib() -> C.CDLL:
@@ -189,6 +194,16 @@ def dllava_predict(x, ldx, M, B, seq_off, vis_start, vis_len, p: Predictor, dtyp
     ws, nbytes = _ws(workspace)
     _check(_lib.dllava_predict(_p(x), ldx, M, B, _p(seq_off), _p(vis_start), _p(vis_len), p.ref, dtype, _p(logits),
                                ws, nbytes, _stream(stream)))
+
+
+def dllava_masked_attn_workspace(rows: int, B: int) -> int:
+    return _lib.dllava_masked_attn_workspace(rows, B)
+
+
+def dllava_masked_attn(Q, K, V, B, off, rows, H, Dh, scale, keep_mask, O, dtype, workspace, stream=None):
+    ws, nbytes = _ws(workspace)
+    _check(_lib.dllava_masked_attn(_p(Q), _p(K), _p(V), B, _p(off), rows, H, Dh, scale, _p(keep_mask), _p(O), dtype,
+                                   ws, nbytes, _stream(stream)))
 
 
 def dllava_linear(x, ldx, M, K, W, bias, N, act, residual, y, ldy, dtype, stream=None):

@@ -724,7 +724,7 @@ extern "C" int dllava_span_attn(const void* Q, const void* K, const void* V, int
   DLLAVA_REQUIRE(B >= 0 && rows >= 0 && rows <= 0x7fffffffLL, DLLAVA_EINVAL, "span_attn: B = %d, rows = %lld", B,
                  (long long)rows);
   DLLAVA_REQUIRE(H > 0 && (Dh == 64 || Dh == 128), DLLAVA_ESHAPE, "span_attn: H = %d, Dh = %d (Dh must be 64 or 128)", H, Dh);
-  DLLAVA_REQUIRE(scale == scale && scale < INFINITY && scale > -INFINITY, DLLAVA_EINVAL, "span_attn: bad scale");
+  DLLAVA_REQUIRE(scale == scale && scale > 0.f && scale < INFINITY, DLLAVA_EINVAL, "span_attn: bad scale");
   if (B == 0 || rows == 0) return DLLAVA_OK;
   DLLAVA_REQUIRE(Q && K && V && O && off, DLLAVA_ENULL, "span_attn: Q, K, V, O and off are required");
   DLLAVA_REQUIRE(aligned(Q, 16) && aligned(K, 16) && aligned(V, 16) && aligned(O, 16), DLLAVA_EINVAL,

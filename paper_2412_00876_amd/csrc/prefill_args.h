@@ -19,6 +19,9 @@ struct PrefillArgs {
   int32_t max_pages;
   // 0: causal (query i sees keys 0..i of its sequence); 1: every query sees all keys of its sequence
   int32_t full;
+  // Key masks (Eq. 7), or null: bit i of word t of sequence b says whether key 32t + i may be seen by LATER queries
+  // (a query always sees itself); the words of sequence b start at key_words[off[b] / 32 + b].  Causal form only.
+  const uint32_t* key_words;
 };
 
 // matrix-core path (prefill_mfma.hip); returns 1 if it does not handle the shape

@@ -72,11 +72,69 @@ int launch_generic(const PrefillArgs& a, int64_t rows, hipStream_t st) {
   return DLLAVA_OK;
 }
 
+// Packs the per-token mask of Eq. 7 into one 32-bit word per key tile: thread = word slot; the words of sequence b
+// start at slot off[b] / 32 + b (disjoint for any offsets, since ceil(n / 32) <= (off + n) / 32 - off / 32 + 1).
+__global__ __launch_bounds__(256) void key_words_kernel(const uint8_t* __restrict__ keep, const int32_t* __restrict__ off,
+                                                        int32_t B, int64_t n_slots, uint32_t* __restrict__ words) {
+  const int64_t slot = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (slot >= n_slots) return;
+  int lo = 0, hi = B;  // the last sequence whose first slot is <= slot
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if ((off[mid] >> 5) + mid <= slot) lo = mid; else hi = mid;
+  }
+  const int b = lo, r0 = off[b], n = off[b + 1] - r0;
+  const int64_t t = slot - ((r0 >> 5) + b);
+  if (t < 0 || 32 * t >= n) return;  // a slot no tile uses
+  uint32_t wd = 0;
+#pragma unroll 8
+  for (int i = 0; i < 32; ++i) {
+    const int64_t j = 32 * t + i;
+    if (j < n && keep[r0 + j] != 0) wd |= 1u << i;
+  }
+  words[slot] = wd;
+}
+
 }  // namespace
 
 }  // namespace dllava
 
 using namespace dllava;
+
+extern "C" size_t dllava_masked_attn_workspace(int64_t rows, int32_t B) {
+  return round_up((static_cast<size_t>(rows > 0 ? rows : 0) / 32 + static_cast<size_t>(B > 0 ? B : 0) + 2) * 4, 256);
+}
+
+extern "C" int dllava_masked_attn(const void* Q, const void* K, const void* V, int32_t B, const int32_t* off,
+                                  int64_t rows, int32_t H, int32_t Dh, float scale, const uint8_t* keep_mask, void* O,
+                                  int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  DLLAVA_REQUIRE(dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "masked_attn: only DLLAVA_BF16 is supported (got dtype %d)", dtype);
+  DLLAVA_REQUIRE(B >= 0 && rows >= 0 && rows <= 0x7fffffffLL, DLLAVA_EINVAL, "masked_attn: B = %d, rows = %lld", B,
+                 (long long)rows);
+  DLLAVA_REQUIRE(Dh == 64 || Dh == 128, DLLAVA_ESHAPE, "masked_attn: Dh must be 64 or 128 (got %d)", Dh);
+  DLLAVA_REQUIRE(H > 0 && H <= 65535, DLLAVA_ESHAPE, "masked_attn: bad H = %d", H);
+  DLLAVA_REQUIRE(scale == scale && scale > 0.f && scale < INFINITY, DLLAVA_EINVAL, "masked_attn: bad scale");
+  if (B == 0 || rows == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(Q && K && V && O && off && keep_mask, DLLAVA_ENULL, "masked_attn: Q, K, V, O, off and keep_mask are required");
+  DLLAVA_REQUIRE(aligned(Q, 16) && aligned(O, 16) && aligned(K, 16) && aligned(V, 16), DLLAVA_EINVAL,
+                 "masked_attn: Q, K, V, O must be 16-byte aligned");
+  const size_t need = dllava_masked_attn_workspace(rows, B);
+  DLLAVA_REQUIRE(workspace && aligned(workspace, 256) && workspace_bytes >= need, DLLAVA_EWORKSPACE,
+                 "masked_attn: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint32_t* words = static_cast<uint32_t*>(workspace);
+  const int64_t n_slots = rows / 32 + B + 1;
+  hipLaunchKernelGGL(key_words_kernel, dim3(static_cast<unsigned>(ceil_div(n_slots, 256))), dim3(256), 0, st, keep_mask,
+                     off, B, n_slots, words);
+  DLLAVA_CHECK_LAUNCH("key_words_kernel");
+  PrefillArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.O = O; a.off = off; a.B = B; a.H = H;
+  a.scale_log2 = scale * 1.44269504088896340736f;
+  a.key_words = words;
+  const int rc = prefill_mfma_launch(a, rows, Dh, st);
+  if (rc > 0) DLLAVA_FAIL(DLLAVA_ESHAPE, "masked_attn: too many rows or sequences");
+  return rc;
+}
 
 extern "C" int dllava_prefill_attn(const void* Q, const void* K, const void* V, const dllava_kv_cache* cache,
                                    int32_t B, const int32_t* off, int64_t rows, int32_t H, int32_t Dh,

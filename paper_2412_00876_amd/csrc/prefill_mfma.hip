@@ -99,12 +99,14 @@ __device__ __forceinline__ u32x2 lds_read8_tr16(uint32_t addr) {
   return v;
 }
 
-// One key tile for one wave.  diag: the tile reaches above the diagonal of some query of the wave.
+// One key tile for one wave.  diag: some score of the tile has to be masked: the tile reaches above the diagonal of
+// some query of the wave (keys > qi), or kmask (bit i: key j0 + i may be seen by other queries than itself) has a
+// zero bit.
 // kb / vb: LDS byte addresses of this lane's first K and V fragment pieces in the tile (see the kernel).
-template <int DH>
+template <int DH, bool MASKED>
 __device__ __forceinline__ void tile_step(uint32_t kb, uint32_t vb_in, const uint4 (&qf)[DH / 16],
                                           f32x16 (&o_acc)[DH / 32], float& m_ref, float& l_run, float scale_log2,
-                                          int j0, int qi, int g, bool diag) {
+                                          int j0, int qi, int g, bool diag, uint32_t kmask, int q_self) {
   constexpr int kDB = DH / 32;
   constexpr int kRowBytes = DH * 2;
   uint32_t vb = vb_in;
@@ -155,14 +157,17 @@ __device__ __forceinline__ void tile_step(uint32_t kb, uint32_t vb_in, const uin
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int key = j0 + 8 * (r >> 2) + 4 * g + (r & 3);
-      if (key > qi) s[r] = -INFINITY;
+      const bool open = !MASKED || ((kmask >> (8 * (r >> 2) + (r & 3) + 4 * g)) & 1u);
+      if (key > qi || (!open && key != q_self)) s[r] = -INFINITY;
     }
   }
   float tmax = -INFINITY;
 #pragma unroll
   for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[r]);
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-  const float m_t = tmax * scale_log2;  // scale > 0: the maximum of the scaled scores; finite (key j0 <= qi is never masked)
+  // scale > 0: the maximum of the scaled scores; -inf for a query that sees no key of this tile (possible with key
+  // masks only).  m_ref starts at a finite floor, so such a tile leaves the query's state as it is (alpha = 1, p = 0).
+  const float m_t = tmax * scale_log2;
   if (__any(m_t > m_ref + kSlack)) {
     const float m_new = fmaxf(m_ref, m_t);
     const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
@@ -217,7 +222,8 @@ __device__ __forceinline__ void tile_step(uint32_t kb, uint32_t vb_in, const uin
   }
 }
 
-template <int DH, int NWQ>
+// MASKED: the variant with key masks (a.key_words); the plain kernel carries none of its registers.
+template <int DH, int NWQ, bool MASKED>
 __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_kernel(PrefillArgs a, int tiles_cap) {
   constexpr int kBM = NWQ * 32;
   constexpr int kChunks = DH / 8;  // 16-byte chunks per row
@@ -294,12 +300,21 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
     for (int ks = 0; ks < DH / 16; ++ks) qf[ks] = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
   }
 
+  // key-mask words of this sequence: word t in lane t % 64 of register t / 64 (requested with the queries)
+  const uint32_t* kw = MASKED ? a.key_words + (r0 >> 5) + b : nullptr;  // block-uniform
+  uint32_t kwr[4] = {~0u, ~0u, ~0u, ~0u};
+  if (MASKED) {
+    const int nw = (n + 31) >> 5;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) kwr[k] = kw[64 * k + lane < nw ? 64 * k + lane : nw - 1];
+  }
+
   f32x16 o_acc[kDB];
 #pragma unroll
   for (int nb = 0; nb < kDB; ++nb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o_acc[nb][r] = 0.f;
-  float m_ref = -INFINITY, l_run = 0.f;
+  float m_ref = -1e30f, l_run = 0.f;  // finite floor, not -inf: see tile_step
 
   const bool full = a.full != 0;  // no causal mask: all keys of the sequence (block-uniform)
   const int last_key = (!full && i0 + kBM < n ? i0 + kBM : n) - 1;  // keys 0..last_key are needed by this block
@@ -355,6 +370,7 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
   // the query fragments have arrived before the loop starts (the tiles requested after them may still be on their way)
 #pragma unroll
   for (int ks = 0; ks < DH / 16; ++ks) asm volatile("" ::"v"(qf[ks].x), "v"(qf[ks].y), "v"(qf[ks].z), "v"(qf[ks].w));
+  if (MASKED) asm volatile("" ::"v"(kwr[0]), "v"(kwr[1]), "v"(kwr[2]), "v"(kwr[3]));  // and so have the mask words
 
   int cur = 0;  // stage of tile t
   for (int t = 0; t < n_tiles; ++t) {
@@ -374,12 +390,19 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
       PAGE_IDS(t + 3);
     }
     const int j0 = t * kBN;
-    if ((full || j0 <= iw + 31) && iw < n) {  // else the tile lies entirely above this wave's diagonal, or the wave has no query (wave-uniform)
+    uint32_t kmask = ~0u;  // wave-uniform
+    if (MASKED) {
+      const uint32_t sel = t < 64 ? kwr[0] : (t < 128 ? kwr[1] : (t < 192 ? kwr[2] : kwr[3]));
+      kmask = t < 256 ? static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(sel), t & 63)) : kw[t];
+    }
+    // skipped (wave-uniform): the tile lies entirely above this wave's diagonal, the wave has no query, or every key
+    // of the tile is masked and none of them is a query of this wave
+    if ((full || j0 <= iw + 31) && iw < n && !(kmask == 0u && j0 + kBN - 1 < iw)) {
       const uint32_t kb = kb0 + cur * (kTileElems * 2), vb = vb0 + cur * (kTileElems * 2);
-      // diag: some key of the tile may exceed some query of the wave (causal) or the end of the sequence (full);
-      // keys beyond the last visible one are masked
-      tile_step<DH>(kb, vb, qf, o_acc, m_ref, l_run, a.scale_log2, j0, full ? n - 1 : qi, g,
-                    j0 + kBN - 1 > (full ? n - 1 : iw));
+      // masking needed: some key of the tile may exceed some query of the wave (causal) or the end of the sequence
+      // (full), or is hidden by its mask bit
+      tile_step<DH, MASKED>(kb, vb, qf, o_acc, m_ref, l_run, a.scale_log2, j0, full ? n - 1 : qi, g,
+                            j0 + kBN - 1 > (full ? n - 1 : iw) || kmask != ~0u, kmask, qi);
     }
     cur = cur == kStages - 1 ? 0 : cur + 1;
   }
@@ -409,7 +432,10 @@ int launch(const PrefillArgs& a, int64_t rows, hipStream_t st) {
   if (tiles > 0x7fffffffLL) return 1;
   if (tiles > 65535) return 1;
   dim3 grid(static_cast<unsigned>(a.H), static_cast<unsigned>(tiles));
-  hipLaunchKernelGGL((prefill_mfma_kernel<DH, NWQ>), grid, dim3(NWQ * kWave), 0, st, a, static_cast<int>(tiles));
+  if (a.key_words)
+    hipLaunchKernelGGL((prefill_mfma_kernel<DH, NWQ, true>), grid, dim3(NWQ * kWave), 0, st, a, static_cast<int>(tiles));
+  else
+    hipLaunchKernelGGL((prefill_mfma_kernel<DH, NWQ, false>), grid, dim3(NWQ * kWave), 0, st, a, static_cast<int>(tiles));
   DLLAVA_CHECK_LAUNCH("prefill_mfma_kernel");
   return DLLAVA_OK;
 }

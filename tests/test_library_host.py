@@ -214,3 +214,19 @@ def test_predictor_entry_points_validate_on_the_host(lib):
     _expect(lib, ESHAPE, L.dllava_span_attn, fake, fake, fake, 1, fake, 8, 8, 96, 0.1, fake, 1, None)
     _expect(lib, ENULL, L.dllava_span_attn, fake, fake, fake, 1, None, 8, 8, 64, 0.1, fake, 1, None)
     _expect(lib, EINVAL, L.dllava_span_attn, fake, fake, fake, 1, fake, 8, 8, 64, float("nan"), fake, 1, None)
+
+
+def test_masked_attn_validates_on_the_host(lib):
+    L = lib.lib()
+    EINVAL, ENULL, ESHAPE, EDTYPE, EWORKSPACE = -1, -2, -3, -4, -6
+    fake = C.c_void_p(0x1000)
+    big = 1 << 20
+    call = lambda Dh, scale, keep, dtype, ws, wsb: (fake, fake, fake, 2, fake, 64, 4, Dh, scale, keep, fake, dtype, ws, wsb, None)
+    _expect(lib, EDTYPE, L.dllava_masked_attn, *call(64, 0.1, fake, 0, fake, big))
+    _expect(lib, ESHAPE, L.dllava_masked_attn, *call(96, 0.1, fake, 1, fake, big))
+    _expect(lib, EINVAL, L.dllava_masked_attn, *call(64, 0.0, fake, 1, fake, big))
+    _expect(lib, ENULL, L.dllava_masked_attn, *call(64, 0.1, None, 1, fake, big))
+    _expect(lib, EWORKSPACE, L.dllava_masked_attn, *call(64, 0.1, fake, 1, None, 0))
+    _expect(lib, EWORKSPACE, L.dllava_masked_attn, *call(64, 0.1, fake, 1, fake, 8))
+    assert lib.dllava_masked_attn_workspace(64, 2) % 256 == 0
+    assert lib.dllava_masked_attn_workspace(1 << 20, 16) >= (1 << 20) // 32 * 4

@@ -306,6 +306,10 @@ def test_masked_attn_matches_loops_and_its_special_cases():
     off_c = np.concatenate([[0], np.cumsum([keep[w.seq_off[b]:w.seq_off[b + 1]].sum() for b in range(w.B)])])
     Oc = R.prefill_attn(pre["Q"][idx], pre["K"][idx], pre["V"][idx], off_c, scale, "bf16")
     assert np.allclose(O[idx], Oc, atol=1e-12)
+    # the row-by-row form used for long sequences
+    some = [0, 1, int(w.seq_off[1]) - 1, int(w.seq_off[1]), w.sumN - 1]
+    assert np.allclose(R.masked_attn_rows(pre["Q"], pre["K"], pre["V"], w.seq_off, keep, scale, "bf16", some), O[some],
+                       atol=1e-12)
     # a dropped token's key and value matter to its own row only
     j = int(np.flatnonzero(keep == 0)[1])
     K2, V2 = pre["K"].copy(), pre["V"].copy()
