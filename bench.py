@@ -514,6 +514,14 @@ def main():
                 "ms": ms_pp_image, "rows": path.M_vis, "tflops": pp.flops_image() / (ms_pp_image * 1e-3) / 1e12,
                 "frac_mfma_peak": pp.flops_image() / (ms_pp_image * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
             "predict_text": None if ms_pp_text is None else {"avg_us": float(ms_pp_text * 1e3), "rows": B},
+            # K/V held by a 32-layer decoder with the decisions taken once after layer l = 2 (Sec. 3.3) and shared by
+            # the later layers: layers 1..2 keep every token, layers 3..32 the reduced prompt and the kept outputs
+            # (this run's decisions); arithmetic on the cache lengths, checked against real caches by the tests
+            "kv_memory_gb_32_layers_l2": (lambda per_tok, full0, red0, fullT, redT: {
+                "after_prefill": {"dense": 32 * full0 * per_tok / 1e9, "sparsified": (2 * full0 + 30 * red0) * per_tok / 1e9},
+                "after_decode": {"dense": 32 * fullT * per_tok / 1e9, "sparsified": (2 * fullT + 30 * redT) * per_tok / 1e9}})(
+                2 * H * Dh * es, int(np.sum(w.seq_len)), int(np.sum(w.kept_len)), int(np.sum(w.seq_len)) + B * T,
+                int(np.sum(w.kept_len)) + int(keep.sum())),
             "decode_step": {"avg_us": float(ms_ds * 1e3), "gbs": (float(kv_bytes_t.mean()) + pred_bytes) / (ms_ds * 1e-3) / 1e9,
                             "note": "one launch per step: scoring + attention, append deferred by one step"},
             "decode_score": {"avg_us": float(ms_sd * 1e3)},

@@ -12,6 +12,7 @@
  *   dllava_qkv_project         Q, K, V of the reduced set, K/V into the cache (Eq. 3 line 1 with S^{P*})
  *   dllava_predict             predictor logits with the predictors of Appendix A.4.1 (in place of dllava_score)
  *   dllava_masked_attn         attention of the training form, mask inside the softmax (Eq. 7)
+ *   dllava_compact             compaction of another layer's tensors with decisions already taken (Sec. 3.3)
  *
  * General conventions
  *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller
@@ -163,6 +164,19 @@ int dllava_select_compact(const float* logits,
                           int32_t* err_flag, int dtype,
                           void* workspace, size_t workspace_bytes, void* stream);
 size_t dllava_select_compact_workspace(int32_t B, int64_t sumN);
+
+/*
+ * Compaction with decisions taken earlier (Sec. 3.3: the predictors run once, after decoder layer l, and their
+ * decisions are shared by all subsequent layers): the gather half of dllava_select_compact, applied to the tensors
+ * and the KV cache of another layer.  kept_idx and out_off are the outputs of the dllava_select_compact call that took
+ * the decisions; everything else has the meaning it has there.  Sets cache->cache_len[b] = N*(b) (clamped to the
+ * capacity, with err_flag raised) when K and V are given.  No workspace.
+ *   Q needs `cache` too (it supplies H and Dh).  Any of the three tensor groups may be NULL.
+ */
+int dllava_compact(int32_t B, const int32_t* seq_off, const int32_t* kept_idx, const int32_t* out_off, int64_t sumN,
+                   const void* hidden, void* hidden_out, int64_t d,
+                   const void* Q, void* Q_out, const void* K, const void* V, const dllava_kv_cache* cache,
+                   int32_t* err_flag, int dtype, void* stream);
 
 /*
  * Causal scaled-dot-product attention over the reduced prefill set (Eq. 1 applied to S^{P*}):

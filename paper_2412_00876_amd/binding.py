@@ -87,6 +87,8 @@ def _load() -> C.CDLL:
     lib.dllava_predict.argtypes = [vp, i64, i64, i32, vp, vp, vp, C.POINTER(_Predictor), C.c_int, vp, vp, sz, vp]
     lib.dllava_predict_workspace.restype = sz
     lib.dllava_predict_workspace.argtypes = [i64, i32, i32]
+    lib.dllava_compact.restype = C.c_int
+    lib.dllava_compact.argtypes = [i32, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, vp, C.POINTER(_KvCache), vp, C.c_int, vp]
     lib.dllava_masked_attn.restype = C.c_int
     lib.dllava_masked_attn.argtypes = [vp, vp, vp, i32, vp, i64, i32, i32, f32, vp, vp, C.c_int, vp, sz, vp]
     lib.dllava_masked_attn_workspace.restype = sz
@@ -106,7 +108,7 @@ EXPORTS = ("dllava_version", "dllava_last_error", "dllava_score", "dllava_score_
            "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_qkv_project",
            "dllava_decode_step", "dllava_decode_step_workspace", "dllava_decode_commit",
            "dllava_predict", "dllava_predict_workspace", "dllava_linear", "dllava_layer_norm", "dllava_span_attn",
-           "dllava_masked_attn", "dllava_masked_attn_workspace")
+           "dllava_masked_attn", "dllava_masked_attn_workspace", "dllava_compact")
 
 
 def lib() -> C.CDLL:
@@ -194,6 +196,13 @@ def dllava_predict(x, ldx, M, B, seq_off, vis_start, vis_len, p: Predictor, dtyp
     ws, nbytes = _ws(workspace)
     _check(_lib.dllava_predict(_p(x), ldx, M, B, _p(seq_off), _p(vis_start), _p(vis_len), p.ref, dtype, _p(logits),
                                ws, nbytes, _stream(stream)))
+
+
+def dllava_compact(B, seq_off, kept_idx, out_off, sumN, hidden, hidden_out, d, Q, Q_out, K, V, cache, err_flag, dtype,
+                   stream=None):
+    _check(_lib.dllava_compact(B, _p(seq_off), _p(kept_idx), _p(out_off), sumN, _p(hidden), _p(hidden_out), d, _p(Q),
+                               _p(Q_out), _p(K), _p(V), cache.ref if cache is not None else None, _p(err_flag), dtype,
+                               _stream(stream)))
 
 
 def dllava_masked_attn_workspace(rows: int, B: int) -> int:

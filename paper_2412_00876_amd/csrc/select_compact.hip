@@ -232,6 +232,12 @@ struct GatherArgs {
   const uint4* K; const uint4* V; int64_t kv_chunks;              // per row, all heads
   uint4* pages; const int32_t* block_table;
   int32_t max_pages, H, head_chunks;                              // 16-byte chunks per (token, head)
+  // decisions taken earlier (dllava_compact): kept_idx is an INPUT, indexed by compacted row, and block 0 sets the
+  // cache lengths and the capacity flag
+  int32_t given;
+  int32_t* cache_len;
+  int32_t cap;
+  int32_t* err_flag;
 };
 
 // 16 readable bytes: the source of the (unused) clamped loads of a tensor that is not being moved
@@ -244,6 +250,13 @@ static __device__ __attribute__((aligned(16))) uint32_t kGatherPad[4] = {0u, 0u,
 __global__ __launch_bounds__(kThreads) void gather_kernel(GatherArgs a) {
   const int j = blockIdx.x, tid = threadIdx.x;
   const int total = a.out_off[a.B];
+  if (a.given && j == 0 && a.cache_len) {  // decisions taken earlier: the lengths of THIS cache follow from them
+    for (int bb = tid; bb < a.B; bb += kThreads) {
+      const int c = a.out_off[bb + 1] - a.out_off[bb];
+      a.cache_len[bb] = c > a.cap ? a.cap : c;
+      if (c > a.cap && a.err_flag) *a.err_flag = 1;
+    }
+  }
   if (j >= total) return;
   int lo = 0, hi = a.B;  // largest b with out_off[b] <= j
   while (hi - lo > 1) {
@@ -253,9 +266,9 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(GatherArgs a) {
   const int b = lo;
   const int pos = j - a.out_off[b];
   const int s0 = a.seq_off[b];
-  const int rel = a.ws_kept[static_cast<size_t>(s0) + pos];
+  const int rel = a.given ? a.kept_idx[j] : a.ws_kept[static_cast<size_t>(s0) + pos];
   const size_t src = static_cast<size_t>(s0) + rel;
-  if (tid == 0) a.kept_idx[j] = rel;
+  if (tid == 0 && !a.given) a.kept_idx[j] = rel;
 
   const bool do_h = a.hidden != nullptr, do_q = a.Q != nullptr;
   const bool do_kv = a.K != nullptr && pos < a.max_pages * kPage;
@@ -387,6 +400,55 @@ extern "C" int dllava_select_compact(const float* logits, int32_t B, const int32
   ga.Q = static_cast<const uint4*>(Q); ga.Q_out = static_cast<uint4*>(Q_out);
   ga.K = static_cast<const uint4*>(K); ga.V = static_cast<const uint4*>(V);
   hipLaunchKernelGGL(gather_kernel, dim3(static_cast<unsigned>(sumN)), dim3(kThreads), 0, st, ga);
+  DLLAVA_CHECK_LAUNCH("gather_kernel");
+  return DLLAVA_OK;
+}
+
+extern "C" int dllava_compact(int32_t B, const int32_t* seq_off, const int32_t* kept_idx, const int32_t* out_off,
+                              int64_t sumN, const void* hidden, void* hidden_out, int64_t d, const void* Q, void* Q_out,
+                              const void* K, const void* V, const dllava_kv_cache* cache, int32_t* err_flag, int dtype,
+                              void* stream) {
+  DLLAVA_REQUIRE(B >= 0 && sumN >= 0 && sumN <= 0x7fffffffLL, DLLAVA_EINVAL, "compact: B = %d, sumN = %lld", B,
+                 (long long)sumN);
+  DLLAVA_REQUIRE(dtype == DLLAVA_F32 || dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "compact: unknown dtype %d", dtype);
+  const int64_t es = dtype == DLLAVA_BF16 ? 2 : 4;
+  DLLAVA_REQUIRE(!hidden || (d > 0 && (d * es) % 16 == 0), DLLAVA_ESHAPE,
+                 "compact: rows of hidden must be a multiple of 16 bytes (d = %lld)", (long long)d);
+  DLLAVA_REQUIRE((hidden == nullptr) == (hidden_out == nullptr) && (Q == nullptr) == (Q_out == nullptr) &&
+                     (K == nullptr) == (V == nullptr),
+                 DLLAVA_ENULL, "compact: hidden/hidden_out, Q/Q_out and K/V go together");
+  if (Q || K) {
+    if (int rc = check_cache(cache, "compact")) return rc;
+    DLLAVA_REQUIRE(cache->dtype == dtype, DLLAVA_EDTYPE, "compact: cache dtype differs from the call's");
+  }
+  if (B == 0 || sumN == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(seq_off && kept_idx && out_off, DLLAVA_ENULL, "compact: seq_off, kept_idx and out_off are required");
+  DLLAVA_REQUIRE(aligned(hidden, 16) && aligned(hidden_out, 16) && aligned(Q, 16) && aligned(Q_out, 16) &&
+                     aligned(K, 16) && aligned(V, 16),
+                 DLLAVA_EINVAL, "compact: tensors must be 16-byte aligned");
+  GatherArgs ga{};
+  ga.seq_off = seq_off; ga.out_off = out_off; ga.kept_idx = const_cast<int32_t*>(kept_idx); ga.B = B;
+  ga.given = 1;
+  ga.hidden = static_cast<const uint4*>(hidden); ga.hidden_out = static_cast<uint4*>(hidden_out);
+  ga.hidden_chunks = hidden ? static_cast<int64_t>(d * es / 16) : 0;
+  if (cache && (Q || K)) {
+    ga.H = cache->H;
+    ga.head_chunks = static_cast<int32_t>(cache->Dh * es / 16);
+    ga.kv_chunks = static_cast<int64_t>(ga.H) * ga.head_chunks;
+    ga.q_chunks = ga.kv_chunks;
+    ga.max_pages = cache->max_pages_per_seq;
+    ga.pages = static_cast<uint4*>(cache->pages);
+    ga.block_table = cache->block_table;
+    if (K) {
+      ga.cache_len = cache->cache_len;
+      ga.cap = cache->max_pages_per_seq * cache->page_size;
+      ga.err_flag = err_flag;
+    }
+  }
+  ga.Q = static_cast<const uint4*>(Q); ga.Q_out = static_cast<uint4*>(Q_out);
+  ga.K = static_cast<const uint4*>(K); ga.V = static_cast<const uint4*>(V);
+  hipLaunchKernelGGL(gather_kernel, dim3(static_cast<unsigned>(sumN)), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                     ga);
   DLLAVA_CHECK_LAUNCH("gather_kernel");
   return DLLAVA_OK;
 }

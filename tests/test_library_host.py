@@ -230,3 +230,20 @@ def test_masked_attn_validates_on_the_host(lib):
     _expect(lib, EWORKSPACE, L.dllava_masked_attn, *call(64, 0.1, fake, 1, fake, 8))
     assert lib.dllava_masked_attn_workspace(64, 2) % 256 == 0
     assert lib.dllava_masked_attn_workspace(1 << 20, 16) >= (1 << 20) // 32 * 4
+
+
+def test_compact_validates_on_the_host(lib):
+    L = lib.lib()
+    EINVAL, ENULL, ESHAPE, EDTYPE = -1, -2, -3, -4
+    fake = C.c_void_p(0x1000)
+    cache = lib._KvCache(0x1000, 0x1000, 0x1000, 4, 2, 16, 2, 64, 1)
+    call = lambda sumN, hid, hid_out, d, K, V, c, dtype, idx=fake: (2, fake, idx, fake, sumN, hid, hid_out, d, None, None, K, V,
+                                                                    c, None, dtype, None)
+    _expect(lib, EDTYPE, L.dllava_compact, *call(40, fake, fake, 64, None, None, None, 5))
+    _expect(lib, ESHAPE, L.dllava_compact, *call(40, fake, fake, 36, None, None, None, 1))
+    _expect(lib, ENULL, L.dllava_compact, *call(40, fake, None, 64, None, None, None, 1))        # hidden without hidden_out
+    _expect(lib, ENULL, L.dllava_compact, *call(40, None, None, 0, fake, None, C.byref(cache), 1))  # K without V
+    _expect(lib, ENULL, L.dllava_compact, *call(40, None, None, 0, fake, fake, None, 1))         # K/V without a cache
+    _expect(lib, ENULL, L.dllava_compact, *call(40, fake, fake, 64, None, None, None, 1, idx=None))
+    _expect(lib, EINVAL, L.dllava_compact, *call(-1, fake, fake, 64, None, None, None, 1))
+    assert L.dllava_compact(*call(0, fake, fake, 64, None, None, None, 1)) == 0                  # nothing to move
