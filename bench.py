@@ -451,6 +451,13 @@ def main():
             pp = PaperPredictors(path, W)
             ms_pp_image = stage_ms(lambda i: pp.run_image(), 3)
             ms_pp_text = stage_ms(pp.run_text, min(T, 64))
+        ms_masked = None
+        if w.dtype == "bf16":   # the training form of the same attention (Eq. 7): full token set, mask inside the softmax
+            O_full = torch.zeros_like(path.pre["Q"])
+            ws_m = torch.zeros(P.dllava_masked_attn_workspace(w.sumN, B), dtype=torch.uint8, device="cuda:0")
+            ms_masked = stage_ms(lambda i: P.dllava_masked_attn(path.pre["Q"], path.pre["K"], path.pre["V"], B, path.seq_off,
+                                                                w.sumN, H, Dh, path.scale, path.keep_mask, O_full, path.code,
+                                                                ws_m), 3)
         ms_prefill = stage_ms(lambda i: path.prefill_attn(), 5)
         ms_sd = stage_ms(path.score_decode, T)                          # logits of all steps: inputs of the next line
         ms_da = stage_ms(path.decode_attn, T, before=path.select_compact)  # cache reset, then T attention launches
@@ -510,6 +517,9 @@ def main():
                                                                                        for n in (np.asarray(w.seq_len) + T)))},
             # the predictors in the appendix's form (also outside the timed step): image predictor over all vision
             # spans, output-text predictor over the B rows of a decode step
+            "masked_attn_full_token_set": None if ms_masked is None else {
+                "ms": ms_masked, "rows": int(w.sumN),
+                "tflops_causal": sum(4.0 * H * Dh * n * (n + 1) / 2 for n in w.seq_len) / (ms_masked * 1e-3) / 1e12},
             "predict_image": None if ms_pp_image is None else {
                 "ms": ms_pp_image, "rows": path.M_vis, "tflops": pp.flops_image() / (ms_pp_image * 1e-3) / 1e12,
                 "frac_mfma_peak": pp.flops_image() / (ms_pp_image * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
