@@ -87,6 +87,40 @@ def test_random_shape_whole_path(seed):
                 _assert_out_close(R.widen(Kg, w.dtype), Kr[off[b]:off[b + 1]], w.dtype, "projected K")
                 _assert_out_close(R.widen(Vg, w.dtype), Vr[off[b]:off[b + 1]], w.dtype, "projected V")
 
+    if w.dtype == "bf16":
+        # the same decisions applied to another cache (shared across layers) reproduce the pages bit for bit
+        g4 = h.GpuPath(w, pre, pred)
+        P.dllava_compact(w.B, g.seq_off, out["kept_idx"], out["out_off"], w.sumN, None, None, 0, None, None, g.pre["K"],
+                         g.pre["V"], g4.cache, g4.err, g4.code)
+        assert torch.equal(g4.pages, g.pages) and torch.equal(g4.cache_len, g.cache_len)
+        # training form (Eq. 7) on the full token set with the selection's mask
+        Om = torch.zeros_like(g.pre["Q"])
+        wsm = torch.empty(P.dllava_masked_attn_workspace(w.sumN, w.B), dtype=torch.uint8, device=h.DEV)
+        P.dllava_masked_attn(g.pre["Q"], g.pre["K"], g.pre["V"], w.B, g.seq_off, w.sumN, w.H, w.Dh, g.scale,
+                             out["keep_mask"], Om, g.code, wsm)
+        _assert_out_close(h.as_f64(Om), R.masked_attn(pre["Q"], pre["K"], pre["V"], w.seq_off, mask, g.scale, w.dtype),
+                          w.dtype, "masked attention")
+        # predictors in the appendix's form: image spans, and the rows of the first decode step
+        from oracle import predictor_ref as PR
+        from tests.test_gpu_predictor import TOL_IMAGE, upload
+        for nb in (2, 0):
+            Pw = W.paper_predictor(w, nb)
+            spans = nb == 2
+            M = len(vis) if spans else w.B
+            if M == 0:
+                continue
+            Dp = torch.zeros((M, 2), dtype=torch.float32, device=h.DEV)
+            wsp = torch.empty(P.dllava_predict_workspace(M, w.B, nb), dtype=torch.uint8, device=h.DEV)
+            if spans:
+                P.dllava_predict(g.pre["hidden"], w.d, M, w.B, g.seq_off, g.vis_start, g.vis_len, upload(h, Pw, w.d), P.BF16,
+                                 Dp, wsp)
+                ref = PR.predict(pre["hidden"][vis], np.concatenate([[0], np.cumsum(w.n_vis)]), Pw, "bf16")
+            else:
+                P.dllava_predict(h.to_dev(dec["x"][0], "bf16"), w.d, M, 0, None, None, None, upload(h, Pw, w.d), P.BF16,
+                                 Dp, wsp)
+                ref = PR.predict(dec["x"][0], None, Pw, "bf16")
+            assert np.abs(Dp.cpu().numpy() - ref).max() <= (TOL_IMAGE if spans else TOL)
+
     # decode, both forms, with forced decisions (a seeded pattern): outputs close, caches bit-exact
     pattern = W.keep_pattern(w, w.T)
     g3 = h.GpuPath(w, pre, pred)
