@@ -10,7 +10,9 @@ inputs resident in HBM before the timed region.  The step is recorded once into 
 (the library never synchronises with the host, cache lengths live on the device) and replayed;
 `--no-graph` times the same calls issued eagerly from Python instead.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric / value / unit, the roofline object of the decode launch (algorithmic bytes per launch over
+its measured duration, against the HBM peak), cpu_baseline (the oracle timed on the host on a bounded sample), and
+per-stage figures under "stages".
 """
 from __future__ import annotations
 
@@ -366,8 +368,8 @@ def pmc_probe(path, torch, L):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by sequence with no exchange; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (the path shards by sequence, or by head, with no exchange "
+              "between GPUs, so N GPUs would run N independent copies of this benchmark); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
