@@ -266,6 +266,34 @@ class PaperPredictors:
         p.P.dllava_predict(p.dec["x"][t], w.d, w.B, 0, None, None, None, self.text, p.code, self.logits_text,
                            self.ws_text)
 
+    def calibrate_theta(self):
+        """Threshold of the output-text predictor = median margin over the workload's decode tokens (as for the
+        two-layer predictor: the keep rate is a trained property, random weights need the threshold set)."""
+        p, w, torch = self.path, self.path.w, self.path.torch
+        x = p.dec["x"].view(-1, w.d)
+        M = x.shape[0]
+        D = torch.zeros((M, 2), dtype=torch.float32, device=x.device)
+        ws = torch.zeros(p.P.dllava_predict_workspace(M, 0, 0), dtype=torch.uint8, device=x.device)
+        p.P.dllava_predict(x, w.d, M, 0, None, None, None, self.text, p.code, D, ws)
+        torch.cuda.synchronize()
+        self.theta = float(torch.median(D[:, 1] - D[:, 0]).item())
+        self.logits_steps = torch.zeros((w.T, w.B, 2), dtype=torch.float32, device=x.device)
+        self.ws_attn = torch.zeros(p.P.dllava_decode_workspace(w.B, w.H, w.Dh, p.cache.max_pages_per_seq), dtype=torch.uint8,
+                                   device=x.device)
+
+    def text_step(self, t):
+        p, w = self.path, self.path.w
+        p.P.dllava_predict(p.dec["x"][t], w.d, w.B, 0, None, None, None, self.text, p.code, self.logits_steps[t], self.ws_text)
+
+    def attn_step(self, t):
+        """Attention + deferred append only (no scoring in the call): decisions from logits_steps[t - 1]."""
+        p, w, d = self.path, self.path.w, self.path.dec
+        prev = t > 0
+        p.P.dllava_decode_step(None, 0, 0, 0, None, None, None, None, d["q"][t], d["k"][t], d["v"][t],
+                               d["k"][t - 1] if prev else None, d["v"][t - 1] if prev else None,
+                               self.logits_steps[t - 1] if prev else None, None, w.B, self.theta, p.cache, p.scale,
+                               p.o_dec[t], None, None, p.err, self.ws_attn)
+
     def flops_image(self):
         w, M = self.path.w, self.path.M_vis
         lin = 2.0 * M * (w.d * 512 + 512 * 256 + 256 * 128 + 256) + 2 * 2.0 * M * 12 * 512 * 512
@@ -453,6 +481,25 @@ def main():
             pp = PaperPredictors(path, W)
             ms_pp_image = stage_ms(lambda i: pp.run_image(), 3)
             ms_pp_text = stage_ms(pp.run_text, min(T, 64))
+            # decode loop with the appendix-form text predictor: per step, the predictor of this step's tokens and the
+            # attention launch (which applies the PREVIOUS token's decision) are independent.  Same stream, then the
+            # predictor on a second stream beside the attention (joined before the next step's attention).
+            pp.calibrate_theta()
+            Tp = min(T, 256)
+
+            def seq_loop(i):
+                pp.text_step(i)
+                pp.attn_step(i)
+            ms_pp_seq = stage_ms(seq_loop, Tp, before=path.select_compact)
+            side = torch.cuda.Stream()
+
+            def par_loop(i):
+                side.wait_stream(stream)          # the step's input exists when the previous step is done
+                with torch.cuda.stream(side):
+                    pp.text_step(i)
+                pp.attn_step(i)
+                stream.wait_stream(side)          # the next step's attention needs these logits
+            ms_pp_par = stage_ms(par_loop, Tp, before=path.select_compact)
         ms_masked = None
         if w.dtype == "bf16":   # the training form of the same attention (Eq. 7): full token set, mask inside the softmax
             O_full = torch.zeros_like(path.pre["Q"])
@@ -526,6 +573,9 @@ def main():
                 "ms": ms_pp_image, "rows": path.M_vis, "tflops": pp.flops_image() / (ms_pp_image * 1e-3) / 1e12,
                 "frac_mfma_peak": pp.flops_image() / (ms_pp_image * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
             "predict_text": None if ms_pp_text is None else {"avg_us": float(ms_pp_text * 1e3), "rows": B},
+            "decode_step_appendix_predictor": None if ms_pp_text is None else {
+                "same_stream_us": float(ms_pp_seq * 1e3), "predictor_beside_attention_us": float(ms_pp_par * 1e3),
+                "steps": Tp, "note": "dllava_predict (output-text form) + dllava_decode_step without scoring, first steps of the generation"},
             # K/V held by a 32-layer decoder with the decisions taken once after layer l = 2 (Sec. 3.3) and shared by
             # the later layers: layers 1..2 keep every token, layers 3..32 the reduced prompt and the kept outputs
             # (this run's decisions); arithmetic on the cache lengths, checked against real caches by the tests

@@ -237,7 +237,10 @@ size_t dllava_decode_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pag
  * v_prev, logits_prev of the next call (the buffers must stay untouched until then), and finish a generation
  * with dllava_decode_commit.  After that the cache equals the one dllava_decode_attn_append leaves, bit for bit.
  *
- *   x [B, d] dtype (row stride ldx), W1 [dh, d], W2 [2, dh] dtype, b1 [dh], b2 [2] float32 or NULL: as dllava_score
+ *   x [B, d] dtype (row stride ldx), W1 [dh, d], W2 [2, dh] dtype, b1 [dh], b2 [2] float32 or NULL: as dllava_score.
+ *                x may be NULL: then nothing is scored in this call (W1, W2, logits ignored; the logits of this step's
+ *                tokens come from elsewhere, e.g. dllava_predict running beside this launch on another stream), the
+ *                workspace of dllava_decode_workspace suffices, and the call is attention + deferred append only
  *   q, k_new, v_new, k_prev, v_prev  [B, H, Dh] cache->dtype
  *   logits       [B, 2] float32 out;  logits_prev [B, 2] float32 in (a different buffer) or NULL
  *   keep_prev_out [B] uint8 out, may be NULL: keep_prev, written only when a previous token is given

@@ -633,15 +633,21 @@ extern "C" int dllava_decode_step(const void* x, int64_t ldx, int64_t d, int64_t
   DLLAVA_REQUIRE(B >= 0, DLLAVA_EINVAL, "decode_step: B = %d < 0", B);
   if (int rc = check_cache(cache, "decode_step")) return rc;
   if (B == 0) return DLLAVA_OK;
-  DLLAVA_REQUIRE(x && W1 && W2 && logits, DLLAVA_ENULL, "decode_step: x, W1, W2 and logits are required");
+  // x == NULL: no scoring in this call (the logits of this step's tokens come from elsewhere, e.g. dllava_predict
+  // running beside this launch); attention and the deferred append only
+  const bool score_here = x != nullptr;
+  DLLAVA_REQUIRE(!score_here || (W1 && W2 && logits), DLLAVA_ENULL, "decode_step: W1, W2 and logits go with x");
   const bool have_prev = logits_prev || keep_prev_override;
   DLLAVA_REQUIRE(!have_prev || (k_prev && v_prev), DLLAVA_ENULL,
                  "decode_step: k_prev and v_prev go with logits_prev / keep_prev_override");
   DLLAVA_REQUIRE(aligned(k_prev, 16) && aligned(v_prev, 16), DLLAVA_EINVAL, "decode_step: k_prev, v_prev must be 16-byte aligned");
-  DLLAVA_REQUIRE(logits_prev != logits, DLLAVA_EINVAL, "decode_step: logits and logits_prev must be different buffers");
+  DLLAVA_REQUIRE(!score_here || logits_prev != logits, DLLAVA_EINVAL,
+                 "decode_step: logits and logits_prev must be different buffers");
+  if (!score_here) { d = 0; dh = 0; }
   const int dtype = cache->dtype;
   const size_t need_dec = round_up(dllava_decode_workspace(B, cache->H, cache->Dh, cache->max_pages_per_seq), 256);
-  const size_t need_score = dllava_decode_step_workspace(B, cache->H, cache->Dh, cache->max_pages_per_seq, d, dh, dtype) - need_dec;
+  const size_t need_score =
+      score_here ? dllava_decode_step_workspace(B, cache->H, cache->Dh, cache->max_pages_per_seq, d, dh, dtype) - need_dec : 0;
   DecodeArgs a{};
   DecodeShape sh;
   if (int rc = prepare("decode_step", q, k_new, v_new, B, nullptr, threshold, nullptr, cache, scale, o, keep_prev_out,
@@ -659,7 +665,7 @@ extern "C" int dllava_decode_step(const void* x, int64_t ldx, int64_t d, int64_t
   SplitPlan p = split_plan(d > 0 ? d : 64, dh > 0 ? dh : 1);
   int nt = 0;
   const bool bf = dtype == DLLAVA_BF16;
-  if (bf && B <= 64 && d > 0 && d % 64 == 0 && ldx >= d && ldx % 8 == 0 && dh >= 1 && p.G <= kSpMaxGroups && d <= 16384 &&
+  if (score_here && bf && B <= 64 && d > 0 && d % 64 == 0 && ldx >= d && ldx % 8 == 0 && dh >= 1 && p.G <= kSpMaxGroups && d <= 16384 &&
       aligned(x, 16) && aligned(W1, 16))
     nt = B <= 16 ? 1 : 2;  // up to 64 rows: one or two groups of at most 32
   if (nt > 0) {
@@ -674,7 +680,7 @@ extern "C" int dllava_decode_step(const void* x, int64_t ldx, int64_t d, int64_t
       p.KS = (npairs + p.ppb - 1) / p.ppb;
     }
   }
-  if (nt == 0) {
+  if (nt == 0 && score_here) {
     if (int rc = dllava_score(x, ldx, B, 0, nullptr, nullptr, nullptr, d, dh, W1, b1, W2, b2, dtype, logits, ws_score,
                               need_score, stream))
       return rc;

@@ -127,3 +127,49 @@ def test_deferred_step_at_cache_capacity():
     assert any_err and int(g.err.item()) == 1
     assert g.cache_len.cpu().numpy().tolist() == [16, 16, 8] and cache.cache_len.tolist() == [16, 16, 8]
     assert np.array_equal(h.bits(g.pages), cache.pages)
+
+
+def test_deferred_step_with_logits_from_the_appendix_form_predictor():
+    """x == NULL: the call scores nothing; the decisions come from dllava_predict (output-text predictor of the
+    appendix) issued beside it.  Outputs and the final cache equal Eq. 6 with the oracle predictor's decisions."""
+    from oracle import predictor_ref as PR
+    from tests.test_gpu_predictor import upload
+    h = _H()
+    T = 6
+    w = W.make("stepp", "bf16", 256, 4, 128, 5, [9, 30, 2, 17, 44], 0, 0, 1.0, T, project_qkv=True, seed=321)
+    pre, dec, pred = W.prefill_inputs(w), W.decode_inputs(w, T), W.predictor(w)
+    g = h.GpuPath(w, pre, pred, extra_tokens=T)
+    D0 = np.zeros((1, 2), np.float32)
+    g.select_compact(torch.from_numpy(D0).to(h.DEV), with_hidden=False)
+    mask, idx, off = R.select(D0, w.seq_off, w.vis_start, w.vis_len, R.TOPK, w.keep_ratio, 0.0)
+    cache = R.PagedCache(g.pages.shape[0], g.bt_np, w.H, w.Dh, w.dtype)
+    R.compact(idx, off, w.seq_off, Q=pre["Q"], K=pre["K"], V=pre["V"], cache=cache)
+    Pw = W.paper_predictor(w, 0)
+    desc = upload(h, Pw, w.d)
+    ws_p = torch.empty(P.dllava_predict_workspace(w.B, w.B, 0), dtype=torch.uint8, device=h.DEV)
+    ws = torch.zeros(P.dllava_decode_workspace(w.B, w.H, w.Dh, g.cache.max_pages_per_seq), dtype=torch.uint8, device=h.DEV)
+    logits = torch.zeros((T, w.B, 2), dtype=torch.float32, device=h.DEV)
+    dev = {n: h.to_dev(dec[n], w.dtype) for n in ("x", "q", "k", "v")}
+    theta = 0.0
+    side = torch.cuda.Stream()
+    for t in range(T):
+        o = torch.zeros((w.B, w.H, w.Dh), dtype=torch.bfloat16, device=h.DEV)
+        prev = t > 0
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):      # the predictor of THIS step's tokens, beside the attention launch
+            P.dllava_predict(dev["x"][t], w.d, w.B, 0, None, None, None, desc, P.BF16, logits[t], ws_p)
+        P.dllava_decode_step(None, 0, 0, 0, None, None, None, None, dev["q"][t], dev["k"][t], dev["v"][t],
+                             dev["k"][t - 1] if prev else None, dev["v"][t - 1] if prev else None,
+                             logits[t - 1] if prev else None, None, w.B, theta, g.cache, g.scale, o, None, None, g.err, ws)
+        torch.cuda.current_stream().wait_stream(side)
+        Dr = PR.predict(dec["x"][t], None, Pw, "bf16")
+        Dg = logits[t].cpu().numpy()
+        assert np.abs(Dg - Dr).max() <= TOL
+        assert np.abs((Dr[:, 1] - Dr[:, 0]) - theta).min() > 10 * np.abs(Dg - Dr).max()      # away from ties
+        o_ref, err = R.decode_attn_append(dec["q"][t], dec["k"][t], dec["v"][t], R.decode_keep(Dr, theta), cache, g.scale)
+        assert not err.any()
+        _assert_out_close(h.as_f64(o), o_ref, w.dtype, f"step {t}")
+    P.dllava_decode_commit(dev["k"][T - 1], dev["v"][T - 1], logits[T - 1], None, w.B, theta, g.cache, None, g.err)
+    assert np.array_equal(g.cache_len.cpu().numpy(), cache.cache_len)
+    assert np.array_equal(h.bits(g.pages), cache.pages)
+    assert int(g.err.item()) == 0
