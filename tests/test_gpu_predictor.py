@@ -266,3 +266,24 @@ def test_text_predictor_at_the_benchmark_shape():
     logits = torch.zeros((B, 2), dtype=torch.float32, device=h.DEV)
     P.dllava_predict(h.to_dev(x, "bf16"), d, B, 0, None, None, None, upload(h, Pw, d), P.BF16, logits, _workspace(h, B, 0, 0))
     assert np.abs(logits.cpu().numpy() - PR.predict(x, None, Pw, "bf16")).max() <= TOL
+
+
+@pytest.mark.parametrize("n_vis", [[9, 0, 20], [40, 33, 30]])
+def test_text_form_on_gathered_spans(n_vis):
+    """n_blocks = 0 with row spans: the rows are gathered out of longer sequences (few rows: the small-batch kernels;
+    more than 64: the tile kernels) and rows are independent of the span structure."""
+    h = _H()
+    B, d = len(n_vis), 128
+    w = _wl(d, [2] * B, n_vis, [3] * B, 55 + sum(n_vis))
+    Pw = W.paper_predictor(w, 0)
+    hidden = W.store(rng.normal(w.seed, "hid", (w.sumN, d)), "bf16")
+    rows = _span_rows(w)
+    M = len(rows)
+    ref = PR.predict(hidden[rows], None, Pw, "bf16")
+    logits = torch.full((M + 3, 2), float("nan"), dtype=torch.float32, device=h.DEV)
+    dev_i = lambda a: torch.from_numpy(np.asarray(a, np.int32)).to(h.DEV)
+    P.dllava_predict(h.to_dev(hidden, "bf16"), d, M, B, dev_i(w.seq_off), dev_i(w.vis_start), dev_i(w.vis_len),
+                     upload(h, Pw, d), P.BF16, logits, _workspace(h, M, B, 0))
+    got = logits.cpu().numpy()
+    assert np.abs(got[:M] - ref).max() <= TOL
+    assert np.isnan(got[M:]).all()                      # nothing written past the rows of the spans
