@@ -593,6 +593,28 @@ def main():
         },
         "input_generation_s": path.gen_seconds,
     }
+    if ci == 2 and not args.decode_steps:
+        # The same step on the batch-1 prompt this workload batches (configs[1]: 35 | 576 | 64 tokens, 256 decode steps):
+        # 3.5-5.6 MB of K/V per decode launch, so every launch is latency, not bandwidth.  Reported beside the headline.
+        w1 = W.config(1)
+        p1 = Path(w1, torch, P, W)
+        p1.calibrate_theta()
+        with torch.cuda.stream(stream):
+            p1.step()
+            stream.synchronize()
+            g1 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g1, stream=stream):
+                p1.step()
+            for _ in range(3):
+                g1.replay()
+            stream.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                g1.replay()
+            stream.synchronize()
+            ms1 = (time.perf_counter() - t0) * 1e3 / 20
+        out["batch_1"] = {"workload": w1.name, "tokens_per_s": w1.B * w1.T / (ms1 * 1e-3), "ms_per_step": ms1,
+                          "decode_steps": w1.T, "us_per_decode_step": (ms1 * 1e3) / w1.T}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(path, args.cpu_seconds)
     print(json.dumps(out))
