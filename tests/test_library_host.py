@@ -91,7 +91,9 @@ def test_argument_errors_are_reported_on_the_host(lib):
     step = lambda **kw: tuple({**dict(x=fake, ldx=64, d=64, dh=16, W1=fake, b1=None, W2=fake, b2=None, q=fake, k=fake, v=fake,
                                       kp=None, vp=None, lp=None, ov=None, B=2, thr=0.0, cache=C.byref(cache), scale=0.1, o=fake,
                                       logits=fake, ko=None, err=None, ws=fake, wsb=1 << 24, st=None), **kw}.values())
-    _expect(lib, ENULL, L.dllava_decode_step, *step(x=None))
+    _expect(lib, ENULL, L.dllava_decode_step, *step(W1=None))                              # x without its predictor
+    _expect(lib, ENULL, L.dllava_decode_step, *step(x=None, q=None))                       # no scoring, but q is still required
+    _expect(lib, EWORKSPACE, L.dllava_decode_step, *step(x=None, wsb=64))
     _expect(lib, ENULL, L.dllava_decode_step, *step(logits=None))
     _expect(lib, ENULL, L.dllava_decode_step, *step(lp=C.c_void_p(0x2000)))                 # previous logits without previous K/V
     _expect(lib, EINVAL, L.dllava_decode_step, *step(kp=fake, vp=fake, lp=fake))            # logits_prev == logits
