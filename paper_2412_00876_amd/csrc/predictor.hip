@@ -9,8 +9,9 @@
 //  * ln_kernel         LayerNorm of 512-wide rows, one wave per row, the row held in registers.
 //  * attention         prefill_mfma_kernel without the causal mask, 8 heads of 64, one "sequence" per span.
 //  * head_out_kernel   the last layer 128 -> 2, one wave per row.
-// Nothing here reduces across blocks: every output element is produced by one thread in a fixed order, so the
-// results are bit-reproducible.
+//  * small_in_kernel, small_head_kernel   the whole text form on at most 64 rows (a decode step), see below.
+// Every output element is produced by one thread summing in a fixed order (the small-batch path adds its four
+// partial sums in a fixed order too), so the results are bit-reproducible.
 #include <cmath>
 
 #include "gemm_tile.h"
@@ -239,10 +240,9 @@ __global__ __launch_bounds__(kWave) void span_offsets_kernel(const int32_t* __re
 // With at most 64 rows the tile kernel above would pull the 2*512*d bytes of W_in through four compute units.
 // small_in_kernel spreads W_in over 64 blocks of 4 waves: block = 32 output features x a quarter of d, wave = a
 // sixteenth of d (every byte of W_in is read once, all loads of a wave in flight together), the four waves summed
-// through LDS in wave order, one partial per block.  small_head_kernel
-// (one block per 32 rows) adds the four partials and the bias in a fixed order, rounds the 512 features to the
-// storage type into LDS, and runs the head 512 -> 256 -> 128 -> 2 from there on the matrix cores, the weights of
-// both layers requested at its very start.
+// through LDS in wave order, one partial per block.  small_head_kernel (one block per 32 rows) adds the four
+// partials and the bias in a fixed order, rounds the 512 features to the storage type into LDS, and runs the head
+// 512 -> 256 -> 128 -> 2 from there on the matrix cores, the weights of both layers requested at its very start.
 constexpr int kSmallRows = 64;
 constexpr int kSmallSplit = 4;    // blocks along d
 constexpr int kZs = 520, kH1s = 264, kH2s = 136;  // LDS row strides (elements): 16-byte pieces of 16 rows fall in 16 bank groups
