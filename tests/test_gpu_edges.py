@@ -304,3 +304,69 @@ def test_decode_loop_replays_from_a_hip_graph():
             for a, b in zip(ref, got):
                 assert torch.equal(a, b), rep
     assert int(g.err.item()) == 0
+
+
+def test_widened_entry_points_replay_from_a_hip_graph():
+    """dllava_predict (both forms), dllava_masked_attn, dllava_compact, dllava_qkv_project and the no-scoring decode step
+    captured once and replayed: every replay, with eager work and synchronisations in between, reproduces the eager
+    result bit for bit (none of them synchronises with the host or relies on initialised workspace)."""
+    from tests.test_gpu_predictor import upload
+    h = _H()
+    w = W.make("graph2", "bf16", 128, 4, 64, 3, [2, 0, 1], [70, 25, 40], [6, 3, 9], 0.4, 3, project_qkv=True, seed=99)
+    pre, dec, pred = W.prefill_inputs(w), W.decode_inputs(w), W.predictor(w)
+    g, g2 = h.GpuPath(w, pre, pred), h.GpuPath(w, pre, pred)
+    M = int(sum(w.n_vis))
+    img, txt = upload(h, W.paper_predictor(w, 2), w.d), upload(h, W.paper_predictor(w, 0), w.d)
+    z8 = lambda n: torch.full((n,), 0x33, dtype=torch.uint8, device=h.DEV)
+    ws_img, ws_txt = z8(P.dllava_predict_workspace(M, w.B, 2)), z8(P.dllava_predict_workspace(w.B, w.B, 0))
+    ws_m = z8(P.dllava_masked_attn_workspace(w.sumN, w.B))
+    ws_d = torch.zeros(P.dllava_decode_workspace(w.B, w.H, w.Dh, g.cache.max_pages_per_seq), dtype=torch.uint8, device=h.DEV)
+    D = torch.zeros((M, 2), dtype=torch.float32, device=h.DEV)
+    Dt = torch.zeros((w.T, w.B, 2), dtype=torch.float32, device=h.DEV)
+    mask = torch.zeros(w.sumN, dtype=torch.uint8, device=h.DEV)
+    kidx = torch.zeros(w.sumN, dtype=torch.int32, device=h.DEV)
+    off = torch.zeros(w.B + 1, dtype=torch.int32, device=h.DEV)
+    hid = torch.zeros((w.sumN, w.d), dtype=torch.bfloat16, device=h.DEV)
+    Qp = torch.zeros((w.sumN, w.H, w.Dh), dtype=torch.bfloat16, device=h.DEV)
+    Om = torch.zeros_like(g.pre["Q"])
+    o = torch.zeros((w.T, w.B, w.H, w.Dh), dtype=torch.bfloat16, device=h.DEV)
+    aw = {k: h.to_dev(v, "bf16") for k, v in W.attn_weights(w).items()}
+    x, q, k, v = (h.to_dev(dec[n], "bf16") for n in ("x", "q", "k", "v"))
+
+    def loop():
+        P.dllava_predict(g.pre["hidden"], w.d, M, w.B, g.seq_off, g.vis_start, g.vis_len, img, P.BF16, D, ws_img)
+        P.dllava_select_compact(D, w.B, g.seq_off, g.vis_start, g.vis_len, w.sumN, P.MODE_TOPK, w.keep_ratio, 0.0,
+                                g.pre["hidden"], hid, w.d, None, None, None, None, None, mask, kidx, off, g.err, g.code,
+                                g.ws_select)
+        P.dllava_masked_attn(g.pre["Q"], g.pre["K"], g.pre["V"], w.B, g.seq_off, w.sumN, w.H, w.Dh, g.scale, mask, Om, P.BF16, ws_m)
+        P.dllava_compact(w.B, g.seq_off, kidx, off, w.sumN, None, None, 0, None, None, g.pre["K"], g.pre["V"], g.cache, g.err,
+                         g.code)
+        P.dllava_qkv_project(hid, w.d, w.sumN, w.d, w.B, off, kidx, aw["q"], aw["k"], aw["v"], 10000.0, Qp, g2.cache, g2.err,
+                             g2.code)
+        for t in range(w.T):
+            P.dllava_predict(x[t], w.d, w.B, 0, None, None, None, txt, P.BF16, Dt[t], ws_txt)
+            P.dllava_decode_step(None, 0, 0, 0, None, None, None, None, q[t], k[t], v[t], k[t - 1] if t else None,
+                                 v[t - 1] if t else None, Dt[t - 1] if t else None, None, w.B, 0.0, g.cache, g.scale, o[t],
+                                 None, None, g.err, ws_d)
+
+    outs = lambda: [D, Dt, mask, kidx, off, hid.view(torch.int16), Qp.view(torch.int16), Om.view(torch.int16),
+                    o.view(torch.int16), g.pages.view(torch.int16), g.cache_len, g2.pages.view(torch.int16), g2.cache_len]
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        loop()
+        st.synchronize()
+        ref = [t.clone() for t in outs()]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            loop()
+        for rep in range(3):
+            for t in (D, Dt, Om, o, Qp, hid):
+                t.zero_()                                      # eager work between replays
+            g.cache_len.fill_(777); g2.cache_len.fill_(777)
+            ws_img.fill_(rep); ws_txt.fill_(rep + 7); ws_m.fill_(rep + 9)
+            st.synchronize()
+            graph.replay()
+            st.synchronize()
+            for i, (a, b) in enumerate(zip(ref, outs())):
+                assert torch.equal(a, b), (rep, i)
+    assert int(g.err.item()) == 0 and int(g2.err.item()) == 0
