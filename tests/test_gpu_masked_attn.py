@@ -105,3 +105,30 @@ def test_masked_attention_long_sequences(n):
     ref = R.masked_attn_rows(q, k, v, off, keep, 1.0 / math.sqrt(Dh), "bf16", some)
     _assert_out_close(h.as_f64(O)[some], ref, "bf16", "sampled rows of a long sequence")
     assert torch.isfinite(O.float()).all()
+
+
+def test_many_sequences_take_the_other_block_numbering():
+    """More than 64 sequences: the kernel numbers its blocks sequence by sequence instead of with ballots; both the
+    masked (Eq. 7) and the unmasked-span forms go through it."""
+    from oracle import predictor_ref as PR
+    h = _H()
+    B, H, Dh = 70, 2, 64
+    lens = [int(x) for x in (rng.uniform01(70, "lens", 0, B) * 60).astype(int)]     # 0..59 rows each, some empty
+    lens[3] = 0
+    lens[10] = 200
+    rows = int(sum(lens))
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    q, k, v = _qkv(71, rows, H, Dh)
+    keep = rng.bernoulli(72, "keep", (rows,), 0.5).astype(np.uint8)
+    O = _run(h, q, k, v, off, keep, H, Dh)
+    _assert_out_close(h.as_f64(O), R.masked_attn(q, k, v, off, keep, 1.0 / math.sqrt(Dh), "bf16"), "bf16", "70 sequences")
+    # unmasked attention within each span (the image predictor's token mixing)
+    Os = torch.zeros((rows, H, Dh), dtype=torch.bfloat16, device=h.DEV)
+    P.dllava_span_attn(h.to_dev(q, "bf16"), h.to_dev(k, "bf16"), h.to_dev(v, "bf16"), B, torch.from_numpy(off).to(h.DEV),
+                       rows, H, Dh, 1.0 / math.sqrt(Dh), Os, P.BF16)
+    ref = np.zeros((rows, H * Dh))
+    f = lambda a: R.widen(a, "bf16").reshape(len(a), H * Dh)
+    for a, b in zip(off[:-1], off[1:]):
+        if b > a:
+            ref[a:b] = PR.attention(f(q[a:b]), f(k[a:b]), f(v[a:b]), heads=H)
+    _assert_out_close(h.as_f64(Os).reshape(rows, H * Dh), ref, "bf16", "70 spans")
