@@ -199,6 +199,21 @@ def paper_predictor(w: Workload, n_blocks: int, name: str = "ppred") -> Dict:
     return P
 
 
+def decoder_layers(w: Workload, n_layers: int, d_ff: int, name: str = "dec") -> list:
+    """Weights of n_layers LLaMA-style decoder layers (no biases): Xavier-uniform projections in storage dtype,
+    RMSNorm scales in [0.8, 1.2] float32.  Keys: Wq, Wk, Wv [H*Dh, d], Wo [d, H*Dh], Wg, Wu [d_ff, d], Wd [d, d_ff], g1, g2 [d]."""
+    out = []
+    hd = w.H * w.Dh
+    for i in range(n_layers):
+        t = f"{name}.{i}."
+        mat = lambda tag, fo, fi: store(_xavier(w.seed, t + tag, fo, fi), w.dtype)
+        out.append({"Wq": mat("Wq", hd, w.d), "Wk": mat("Wk", hd, w.d), "Wv": mat("Wv", hd, w.d), "Wo": mat("Wo", w.d, hd),
+                    "Wg": mat("Wg", d_ff, w.d), "Wu": mat("Wu", d_ff, w.d), "Wd": mat("Wd", w.d, d_ff),
+                    "g1": rng.uniform(w.seed, t + "g1", (w.d,), 0.8, 1.2).astype(np.float32),
+                    "g2": rng.uniform(w.seed, t + "g2", (w.d,), 0.8, 1.2).astype(np.float32)})
+    return out
+
+
 def _hidden(w: Workload, name: str, rows: int, unit_scale: bool) -> np.ndarray:
     g = _normal_big(w.seed, name, (rows, w.d))
     if not unit_scale:
