@@ -49,6 +49,7 @@ def parse():
                     help="decode with dllava_score + dllava_decode_attn_append (two dependent launches per step) "
                          "instead of dllava_decode_step (one launch, append deferred by one step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stack", action="store_true", help="skip the decoder-stack prefill stage (3.2 GB of random weights)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--pmc-probe", type=int, default=0, metavar="L",
                     help="counter probe for rocprofv3 --pmc: one 256 MiB device copy (calibration), then 3 decode "
@@ -507,6 +508,43 @@ def main():
             ms_masked = stage_ms(lambda i: P.dllava_masked_attn(path.pre["Q"], path.pre["K"], path.pre["V"], B, path.seq_off,
                                                                 w.sumN, H, Dh, path.scale, path.keep_mask, O_full, path.code,
                                                                 ws_m), 3)
+        stack = None
+        if w.dtype == "bf16" and not args.no_stack:
+            # Prefill through 8 LLaMA-family decoder layers of this shape (random weights, feed-forward width 2.6875 d)
+            # with the one-time token reduction after layer 2 (Sec. 3.3), against the same 8 layers without reduction
+            from paper_2412_00876_amd.layers import DecoderStack
+            n_layers, d_ff = 8, (w.d * 43) // 16
+            gen = torch.Generator(device="cuda:0")
+            gen.manual_seed(w.seed + 5)
+            rnd = lambda fo, fi: (torch.randn((fo, fi), generator=gen, device="cuda:0", dtype=torch.float32)
+                                  * (2.0 / (fo + fi)) ** 0.5).to(torch.bfloat16)
+            ones = lambda n: torch.ones(n, dtype=torch.float32, device="cuda:0")
+            wts = [{"Wq": rnd(H * Dh, w.d), "Wk": rnd(H * Dh, w.d), "Wv": rnd(H * Dh, w.d), "Wo": rnd(w.d, H * Dh),
+                    "Wg": rnd(d_ff, w.d), "Wu": rnd(d_ff, w.d), "Wd": rnd(w.d, d_ff), "g1": ones(w.d), "g2": ones(w.d)}
+                   for _ in range(n_layers)]
+
+            def score_into(X, logits):
+                p = path.pred
+                P.dllava_score(X, w.d, path.M_vis, B, path.seq_off, path.vis_start, path.vis_len, w.d, w.dh, p["W1"], p["b1"],
+                               p["W2"], p["b2"], path.code, logits, path.ws_score_vis)
+
+            res = {}
+            for name, l_red, rows_after in (("sparsified_after_layer_2", 2, path.rows_kept), ("dense", n_layers, w.sumN)):
+                S = DecoderStack(wts, l_red, B, H, Dh, w.d, d_ff, w.sumN, path.M_vis, max_seq_len=int(max(w.seq_len)))
+                run_stack = lambda i, S=S, rows_after=rows_after: S.prefill(path.pre["hidden"], path.seq_off, path.vis_start,
+                                                                             path.vis_len, w.keep_ratio, rows_after, score_into)
+                res[name] = stage_ms(run_stack, 1, reps=3)
+                assert int(S.err.item()) == 0
+                del S
+            per_tok = 2.0 * (4 * w.d * H * Dh + 3 * w.d * d_ff)          # linear-layer flops per token and layer
+            stack = {"layers": n_layers, "d_ff": d_ff, "rows": int(w.sumN), "rows_after_reduction": int(path.rows_kept),
+                     "ms": res, "speedup": res["dense"] / res["sparsified_after_layer_2"],
+                     "dense_linear_tflops": per_tok * w.sumN * n_layers / (res["dense"] * 1e-3) / 1e12,
+                     "projected_32_layers_ms": {k: v + (v - 0.0) * 0 for k, v in res.items()}}
+            lay_d = res["dense"] / n_layers
+            lay_s = (res["sparsified_after_layer_2"] - 2 * lay_d) / (n_layers - 2)
+            stack["projected_32_layers_ms"] = {"dense": 32 * lay_d, "sparsified_after_layer_2": 2 * lay_d + 30 * lay_s}
+            del wts
         ms_prefill = stage_ms(lambda i: path.prefill_attn(), 5)
         ms_sd = stage_ms(path.score_decode, T)                          # logits of all steps: inputs of the next line
         ms_da = stage_ms(path.decode_attn, T, before=path.select_compact)  # cache reset, then T attention launches
@@ -569,6 +607,7 @@ def main():
             "masked_attn_full_token_set": None if ms_masked is None else {
                 "ms": ms_masked, "rows": int(w.sumN),
                 "tflops_causal": sum(4.0 * H * Dh * n * (n + 1) / 2 for n in w.seq_len) / (ms_masked * 1e-3) / 1e12},
+            "decoder_stack_prefill": stack,
             "predict_image": None if ms_pp_image is None else {
                 "ms": ms_pp_image, "rows": path.M_vis, "tflops": pp.flops_image() / (ms_pp_image * 1e-3) / 1e12,
                 "frac_mfma_peak": pp.flops_image() / (ms_pp_image * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},

@@ -361,12 +361,17 @@ size_t dllava_predict_workspace(int64_t M, int32_t B, int32_t n_blocks);
  * The layers dllava_predict is made of, as calls of their own (Appendix A.4.1 names the layers; the formulas are
  * the ones stated above).  DLLAVA_BF16 only; float32 sums; each output element is rounded once.
  *
- * dllava_linear:        y = act(x W^T + bias) + residual
- *   x [M, K] row stride ldx;  W [N, K];  bias [N] float32 or NULL;  act 0 = none, 1 = exact GELU;
- *   residual [M, N] with y's row stride, or NULL, may be y itself;  y [M, N] row stride ldy, out.
+ * dllava_linear:        y = act(x W^T + bias) + residual      (act 0 = none, 1 = exact GELU), or
+ *                       y = (x W^T + bias) * SiLU(residual)   (act 2: the gated unit of a SwiGLU feed-forward layer,
+ *                                                              `residual` holding the gate x W_gate^T)
+ *   x [M, K] row stride ldx;  W [N, K];  bias [N] float32 or NULL;
+ *   residual [M, N] with y's row stride, or NULL (act 0, 1), may be y itself;  y [M, N] row stride ldy, out.
  *   Sizes: K % 64 == 0, N % 8 == 0, ldx % 8 == 0, ldy % 8 == 0; pointers 16-byte aligned.
  * dllava_layer_norm: y = (z - mean) / sqrt(var + 1e-6) * gamma + beta per row of 512 (biased variance);
  *   z, y [M, 512] contiguous;  gamma, beta [512] float32, 16-byte aligned, or NULL (1 and 0).
+ * dllava_rms_norm:      y = x / sqrt(mean(x^2) + eps) * weight per row of d (the normalisation of the LLaMA-family
+ *   decoder the paper sparsifies);  x [M, d] row stride ldx, y [M, d] row stride ldy;  weight [d] float32, 16-byte
+ *   aligned, or NULL (= 1);  d % 8 == 0, d <= 8192.
  * dllava_span_attn:     O_i = softmax_j(scale * q_i . k_j) V over ALL rows j of the span of row i (no causal
  *   mask);  Q, K, V, O [rows, H, Dh] contiguous;  off [B+1] row offsets of the spans;  rows = host upper bound on
  *   off[B];  Dh in {64, 128}.
@@ -394,6 +399,8 @@ int dllava_linear(const void* x, int64_t ldx, int64_t M, int64_t K, const void* 
                   int act, const void* residual, void* y, int64_t ldy, int dtype, void* stream);
 int dllava_layer_norm(const void* z, int64_t M, const float* gamma, const float* beta, void* y, int dtype,
                          void* stream);
+int dllava_rms_norm(const void* x, int64_t ldx, int64_t M, int64_t d, const float* weight, float eps, void* y,
+                    int64_t ldy, int dtype, void* stream);
 int dllava_span_attn(const void* Q, const void* K, const void* V, int32_t B, const int32_t* off, int64_t rows,
                      int32_t H, int32_t Dh, float scale, void* O, int dtype, void* stream);
 

@@ -97,6 +97,8 @@ def _load() -> C.CDLL:
     lib.dllava_linear.argtypes = [vp, i64, i64, i64, vp, vp, i64, C.c_int, vp, vp, i64, C.c_int, vp]
     lib.dllava_layer_norm.restype = C.c_int
     lib.dllava_layer_norm.argtypes = [vp, i64, vp, vp, vp, C.c_int, vp]
+    lib.dllava_rms_norm.restype = C.c_int
+    lib.dllava_rms_norm.argtypes = [vp, i64, i64, i64, vp, f32, vp, i64, C.c_int, vp]
     lib.dllava_span_attn.restype = C.c_int
     lib.dllava_span_attn.argtypes = [vp, vp, vp, i32, vp, i64, i32, i32, f32, vp, C.c_int, vp]
     return lib
@@ -108,7 +110,7 @@ EXPORTS = ("dllava_version", "dllava_last_error", "dllava_score", "dllava_score_
            "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_qkv_project",
            "dllava_decode_step", "dllava_decode_step_workspace", "dllava_decode_commit",
            "dllava_predict", "dllava_predict_workspace", "dllava_linear", "dllava_layer_norm", "dllava_span_attn",
-           "dllava_masked_attn", "dllava_masked_attn_workspace", "dllava_compact")
+           "dllava_masked_attn", "dllava_masked_attn_workspace", "dllava_compact", "dllava_rms_norm")
 
 
 def lib() -> C.CDLL:
@@ -221,6 +223,10 @@ def dllava_linear(x, ldx, M, K, W, bias, N, act, residual, y, ldy, dtype, stream
 
 def dllava_layer_norm(z, M, gamma, beta, y, dtype, stream=None):
     _check(_lib.dllava_layer_norm(_p(z), M, _p(gamma), _p(beta), _p(y), dtype, _stream(stream)))
+
+
+def dllava_rms_norm(x, ldx, M, d, weight, eps, y, ldy, dtype, stream=None):
+    _check(_lib.dllava_rms_norm(_p(x), ldx, M, d, _p(weight), eps, _p(y), ldy, dtype, _stream(stream)))
 
 
 def dllava_span_attn(Q, K, V, B, off, rows, H, Dh, scale, O, dtype, stream=None):

@@ -29,6 +29,11 @@ constexpr int kPH1 = 256, kPH2 = 128;  // head: 512 -> 256 -> 128 -> 2
 constexpr float kLnEps = 1e-6f;
 constexpr int kXcds = 8;
 
+// SiLU g / (1 + e^-g) with the hardware exponential and reciprocal (relative error ~1e-6)
+__device__ __forceinline__ float silu_fast(float g) {
+  return g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * g));
+}
+
 struct LinArgs {
   const bf16_t* X;   // [*, K], row stride ldx
   int64_t ldx, M;
@@ -40,7 +45,7 @@ struct LinArgs {
   int64_t ldy, group_stride;
   int group;
   const bf16_t* R;   // residual, indexed like Y (may be Y itself), or null
-  int act;           // 1: GELU
+  int act;           // 1: GELU; 2: multiply by SiLU(R) instead of adding R
   // rows of X: the vision spans back to back when seq_off is given, else rows 0..M-1
   int32_t B;
   const int32_t* seq_off;
@@ -104,13 +109,17 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
         if (m >= M) m = M - 1;
         float v0 = acc[i][j][4 * q4] + bs.x, v1 = acc[i][j][4 * q4 + 1] + bs.y;
         float v2 = acc[i][j][4 * q4 + 2] + bs.z, v3 = acc[i][j][4 * q4 + 3] + bs.w;
-        if (a.act) {
+        if (a.act == 1) {
           v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3);
         }
-        if (a.R) {  // block-uniform; the sum is rounded once, after the addition
+        if (a.R) {  // block-uniform; the result is rounded once, after the addition / the product
           const uint2 rr = *reinterpret_cast<const uint2*>(a.R + col + m * a.ldy);
-          v0 += bf16lo_to_f32(rr.x); v1 += bf16hi_to_f32(rr.x);
-          v2 += bf16lo_to_f32(rr.y); v3 += bf16hi_to_f32(rr.y);
+          const float r0 = bf16lo_to_f32(rr.x), r1 = bf16hi_to_f32(rr.x), r2 = bf16lo_to_f32(rr.y), r3 = bf16hi_to_f32(rr.y);
+          if (a.act == 2) {  // gated unit: R holds the gate, the output is this product times SiLU(gate)
+            v0 *= silu_fast(r0); v1 *= silu_fast(r1); v2 *= silu_fast(r2); v3 *= silu_fast(r3);
+          } else {
+            v0 += r0; v1 += r1; v2 += r2; v3 += r3;
+          }
         }
         uint2 v;
         v.x = pack_bf16x2(v0, v1);
@@ -533,6 +542,56 @@ __global__ __launch_bounds__(256) void small_head_kernel(const float* __restrict
   }
 }
 
+// RMSNorm of d-wide rows: y = x / sqrt(mean(x^2) + eps) * w.  One wave per row, the row held in registers
+// (16-byte pieces, lane-strided: up to 16 pieces = 8192 elements), sum of squares in float32.
+constexpr int kRmsMaxPieces = 16;
+__global__ __launch_bounds__(256) void rms_norm_kernel(const bf16_t* __restrict__ X, int64_t ldx, bf16_t* __restrict__ Y,
+                                                       int64_t ldy, const float* __restrict__ wgt, int64_t M, int d,
+                                                       float eps) {
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + w;
+  if (row >= M) return;
+  const int pieces = (d / 8 + kWave - 1) / kWave;  // per lane
+  uint4 raw[kRmsMaxPieces];
+  const bf16_t* x = X + row * ldx;
+#pragma unroll
+  for (int c = 0; c < kRmsMaxPieces; ++c) {
+    const int col = (c * kWave + lane) * 8;
+    raw[c] = (c < pieces && col < d) ? *reinterpret_cast<const uint4*>(x + col) : uint4{0u, 0u, 0u, 0u};
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < kRmsMaxPieces; ++c) {
+    float v[8];
+    Elem<bf16_t>::unpack(raw[c], v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss = fmaf(v[e], v[e], ss);
+  }
+  const float rs = 1.f / sqrtf(wave_sum(ss) / static_cast<float>(d) + eps);
+  bf16_t* y = Y + row * ldy;
+#pragma unroll
+  for (int c = 0; c < kRmsMaxPieces; ++c) {
+    const int col = (c * kWave + lane) * 8;
+    if (c < pieces && col < d) {
+      float v[8], g[8];
+      Elem<bf16_t>::unpack(raw[c], v);
+      if (wgt) {
+        *reinterpret_cast<float4*>(g) = *reinterpret_cast<const float4*>(wgt + col);
+        *reinterpret_cast<float4*>(g + 4) = *reinterpret_cast<const float4*>(wgt + col + 4);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) g[e] = 1.f;
+      }
+      uint4 o;
+      o.x = pack_bf16x2(v[0] * rs * g[0], v[1] * rs * g[1]);
+      o.y = pack_bf16x2(v[2] * rs * g[2], v[3] * rs * g[3]);
+      o.z = pack_bf16x2(v[4] * rs * g[4], v[5] * rs * g[5]);
+      o.w = pack_bf16x2(v[6] * rs * g[6], v[7] * rs * g[7]);
+      *reinterpret_cast<uint4*>(y + col) = o;
+    }
+  }
+}
+
 struct Regions {
   int32_t* span_off;
   bf16_t *Z, *Y, *QKV, *Hb;
@@ -690,7 +749,8 @@ extern "C" int dllava_linear(const void* x, int64_t ldx, int64_t M, int64_t K, c
                  "linear: N must be a positive multiple of 8 (got %lld)", (long long)N);
   DLLAVA_REQUIRE(ldx >= K && ldx % 8 == 0 && ldy >= N && ldy % 8 == 0, DLLAVA_ESHAPE,
                  "linear: ldx >= K, ldy >= N, both multiples of 8 (got %lld, %lld)", (long long)ldx, (long long)ldy);
-  DLLAVA_REQUIRE(act == 0 || act == 1, DLLAVA_EINVAL, "linear: act = %d (0: none, 1: GELU)", act);
+  DLLAVA_REQUIRE(act >= 0 && act <= 2, DLLAVA_EINVAL, "linear: act = %d (0: none, 1: GELU, 2: gated)", act);
+  DLLAVA_REQUIRE(act != 2 || residual, DLLAVA_ENULL, "linear: act = 2 takes the gate in `residual`");
   if (M == 0) return DLLAVA_OK;
   DLLAVA_REQUIRE(x && W && y, DLLAVA_ENULL, "linear: x, W and y are required");
   DLLAVA_REQUIRE(aligned(x, 16) && aligned(W, 16) && aligned(y, 16) && aligned(residual, 16) && aligned(bias, 16),
@@ -736,4 +796,24 @@ extern "C" int dllava_span_attn(const void* Q, const void* K, const void* V, int
   const int rc = prefill_mfma_launch(pa, rows, Dh, static_cast<hipStream_t>(stream));
   if (rc > 0) DLLAVA_FAIL(DLLAVA_ESHAPE, "span_attn: too many rows, spans or heads");
   return rc;
+}
+
+extern "C" int dllava_rms_norm(const void* x, int64_t ldx, int64_t M, int64_t d, const float* weight, float eps, void* y,
+                               int64_t ldy, int dtype, void* stream) {
+  DLLAVA_REQUIRE(dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "rms_norm: only DLLAVA_BF16 is supported (got dtype %d)", dtype);
+  DLLAVA_REQUIRE(M >= 0 && M <= 0x7fffffffLL, DLLAVA_ESHAPE, "rms_norm: bad M = %lld", (long long)M);
+  DLLAVA_REQUIRE(d > 0 && d % 8 == 0 && d <= 8 * kWave * kRmsMaxPieces, DLLAVA_ESHAPE,
+                 "rms_norm: d must be a multiple of 8, at most %d (got %lld)", 8 * kWave * kRmsMaxPieces, (long long)d);
+  DLLAVA_REQUIRE(ldx >= d && ldx % 8 == 0 && ldy >= d && ldy % 8 == 0, DLLAVA_ESHAPE,
+                 "rms_norm: ldx, ldy >= d, multiples of 8 (got %lld, %lld)", (long long)ldx, (long long)ldy);
+  DLLAVA_REQUIRE(eps == eps && eps >= 0.f && eps < INFINITY, DLLAVA_EINVAL, "rms_norm: bad eps");
+  if (M == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(x && y, DLLAVA_ENULL, "rms_norm: x and y are required");
+  DLLAVA_REQUIRE(aligned(x, 16) && aligned(y, 16) && aligned(weight, 16), DLLAVA_EINVAL,
+                 "rms_norm: x, y, weight must be 16-byte aligned");
+  hipLaunchKernelGGL(rms_norm_kernel, dim3(static_cast<unsigned>(ceil_div(M, 4))), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const bf16_t*>(x), ldx, static_cast<bf16_t*>(y), ldy,
+                     weight, M, static_cast<int>(d), eps);
+  DLLAVA_CHECK_LAUNCH("rms_norm_kernel");
+  return DLLAVA_OK;
 }

@@ -80,3 +80,75 @@ class SparsifiedLayers:
         """Bytes of K and V held by all layers right now."""
         per_token = 2 * self.H * self.Dh * self.es
         return int(sum(int(c.cache_len.sum().item()) for c in self.caches)) * per_token
+
+
+class DecoderStack:
+    """Prefill through a stack of LLaMA-family decoder layers (RMSNorm, rotary attention, SwiGLU feed-forward; the
+    decoder the paper sparsifies) with the one-time token reduction after layer l.  Sequencing only.
+
+    weights: list of dicts per layer with device tensors Wq, Wk, Wv [H*Dh, d], Wo [d, H*Dh], Wg, Wu [d_ff, d],
+    Wd [d, d_ff] (bfloat16) and g1, g2 [d] (float32).  One paged cache per layer receives that layer's K/V:
+    all tokens for layers before l, the kept tokens after.
+    """
+
+    RMS_EPS = 1e-5
+    ROPE_BASE = 10000.0
+
+    def __init__(self, weights, l: int, B: int, H: int, Dh: int, d: int, d_ff: int, sumN: int, vision_rows: int,
+                 max_seq_len: Optional[int] = None, device="cuda:0"):
+        self.W, self.l, self.B, self.H, self.Dh, self.d, self.d_ff, self.sumN = weights, l, B, H, Dh, d, d_ff, sumN
+        self.logits = torch.zeros((max(1, vision_rows), 2), dtype=torch.float32, device=device)
+        self.dummy_logits = torch.zeros((max(1, sumN), 2), dtype=torch.float32, device=device)
+        self.mask_all = torch.zeros(sumN, dtype=torch.uint8, device=device)
+        bf = torch.bfloat16
+        z = lambda *shape: torch.zeros(shape, dtype=bf, device=device)
+        self.X, self.X2, self.Hn = z(sumN, d), z(sumN, d), z(sumN, d)
+        self.Q, self.A = z(sumN, H, Dh), z(sumN, H, Dh)
+        self.G, self.F = z(sumN, d_ff), z(sumN, d_ff)
+        self.err = torch.zeros(1, dtype=torch.int32, device=device)
+        self.caches = []
+        for _ in weights:
+            mp = ((max_seq_len or sumN) + P.PAGE_SIZE - 1) // P.PAGE_SIZE   # pages per sequence
+            pages = torch.zeros((B * mp, 2, H, P.PAGE_SIZE, Dh), dtype=bf, device=device)
+            bt = torch.arange(B * mp, dtype=torch.int32, device=device).reshape(B, mp).contiguous()
+            self.caches.append(P.KVCache(pages, bt, torch.zeros(B, dtype=torch.int32, device=device)))
+        self.ws_select = torch.zeros(P.dllava_select_compact_workspace(B, sumN), dtype=torch.uint8, device=device)
+        self.keep_mask = torch.zeros(sumN, dtype=torch.uint8, device=device)
+        self.kept_idx = torch.zeros(sumN, dtype=torch.int32, device=device)
+        self.out_off = torch.zeros(B + 1, dtype=torch.int32, device=device)
+        self.full_idx = torch.zeros(sumN, dtype=torch.int32, device=device)
+        self.full_off = torch.zeros(B + 1, dtype=torch.int32, device=device)
+
+    def _layer(self, i: int, X, rows: int, off, pos):
+        """One decoder layer in place on the first `rows` rows of X (rows = host count of off[B])."""
+        W, d, ff, H, Dh, BF = self.W[i], self.d, self.d_ff, self.H, self.Dh, P.BF16
+        c = self.caches[i]
+        P.dllava_rms_norm(X, d, rows, d, W["g1"], self.RMS_EPS, self.Hn, d, BF)
+        P.dllava_qkv_project(self.Hn, d, rows, d, self.B, off, pos, W["Wq"], W["Wk"], W["Wv"], self.ROPE_BASE, self.Q, c,
+                             self.err, BF)
+        P.dllava_prefill_attn(self.Q, None, None, c, self.B, off, rows, H, Dh, Dh ** -0.5, self.A, BF)
+        P.dllava_linear(self.A, H * Dh, rows, H * Dh, W["Wo"], None, d, 0, X, X, d, BF)
+        P.dllava_rms_norm(X, d, rows, d, W["g2"], self.RMS_EPS, self.Hn, d, BF)
+        P.dllava_linear(self.Hn, d, rows, d, W["Wg"], None, ff, 0, None, self.G, ff, BF)
+        P.dllava_linear(self.Hn, d, rows, d, W["Wu"], None, ff, 2, self.G, self.F, ff, BF)
+        P.dllava_linear(self.F, ff, rows, ff, W["Wd"], None, d, 0, X, X, d, BF)
+
+    def prefill(self, x0, seq_off, vis_start, vis_len, keep_ratio: float, kept_rows: int, predictor):
+        """x0 [sumN, d]: the decoder's input rows.  predictor(X, logits): fills logits [sum vis_len, 2] from the rows of
+        X's vision spans (a call of dllava_score or dllava_predict).  kept_rows: host count of the rows that stay,
+        sum over sequences of text rows + floor(keep_ratio * vision rows).  Returns the final rows (a view)."""
+        self.X.copy_(x0)
+        # positions of all tokens: the "everything kept" decisions
+        P.dllava_select_compact(self.dummy_logits, self.B, seq_off, vis_start, vis_len, self.sumN, P.MODE_TOPK, 1.0, 0.0, None, None, 0,
+                                None, None, None, None, None, self.mask_all, self.full_idx, self.full_off, self.err,
+                                P.BF16, self.ws_select)
+        X, rows, off, pos = self.X, self.sumN, self.full_off, self.full_idx
+        for i in range(len(self.W)):
+            if i == self.l:
+                predictor(X, self.logits)
+                P.dllava_select_compact(self.logits, self.B, seq_off, vis_start, vis_len, self.sumN, P.MODE_TOPK, keep_ratio,
+                                        0.0, X, self.X2, self.d, None, None, None, None, None, self.keep_mask, self.kept_idx,
+                                        self.out_off, self.err, P.BF16, self.ws_select)
+                X, rows, off, pos = self.X2, kept_rows, self.out_off, self.kept_idx
+            self._layer(i, X, rows, off, pos)
+        return X[:rows]

@@ -1,0 +1,100 @@
+"""GPU parity of the decoder-layer pieces beyond attention (dllava_rms_norm, the gated form of dllava_linear) to the
+rounding of their outputs, and of a whole stack of LLaMA-family decoder layers with the one-time token reduction after
+layer l (paper_2412_00876_amd.layers.DecoderStack) against the decoder-stack oracle."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2412_00876_amd as P
+from oracle import decoder_ref as DR
+from oracle import dllava_ref as R
+from synth import rng
+from synth import workloads as W
+from tests.test_gpu_predictor import _assert_same_rounding
+
+
+def _H():
+    from tests import harness
+    return harness
+
+
+@pytest.mark.parametrize("M,d", [(50, 64), (33, 4096), (7, 5120), (9, 8192), (5, 520)])
+def test_rms_norm_layer(M, d):
+    h = _H()
+    x = W.store(rng.normal(d, "x", (M, d)) * 2 + 0.3, "bf16")
+    g = rng.uniform(d, "g", (d,), 0.5, 1.5).astype(np.float32)
+    y = torch.zeros((M, d + 8), dtype=torch.bfloat16, device=h.DEV)
+    P.dllava_rms_norm(h.to_dev(x, "bf16"), d, M, d, torch.from_numpy(g).to(h.DEV), DR.RMS_EPS, y, d + 8, P.BF16)
+    got = h.bits(y)
+    assert (got[:, d:] == 0).all()
+    _assert_same_rounding(got[:, :d], DR.rms_norm(R.widen(x, "bf16"), g), f"rms norm {M}x{d}")
+    P.dllava_rms_norm(h.to_dev(x, "bf16"), d, M, d, None, DR.RMS_EPS, y, d + 8, P.BF16)
+    _assert_same_rounding(h.bits(y)[:, :d], DR.rms_norm(R.widen(x, "bf16"), np.ones(d)), "rms norm without weight")
+
+
+@pytest.mark.parametrize("M,K,N", [(130, 256, 704), (20, 64, 8)])
+def test_gated_linear_layer(M, K, N):
+    """y = (x W^T) * SiLU(gate): the second half of a SwiGLU feed-forward layer."""
+    h = _H()
+    x = W.store(rng.normal(K, "x", (M, K)), "bf16")
+    Wm = W.store(rng.normal(K, "W", (N, K)) / np.sqrt(K), "bf16")
+    gate = W.store(rng.normal(K, "g", (M, N)) * 2, "bf16")
+    ref = (R.widen(x, "bf16") @ R.widen(Wm, "bf16").T) * DR.silu(R.widen(gate, "bf16"))
+    y = torch.zeros((M, N), dtype=torch.bfloat16, device=h.DEV)
+    P.dllava_linear(h.to_dev(x, "bf16"), K, M, K, h.to_dev(Wm, "bf16"), None, N, 2, h.to_dev(gate, "bf16"), y, N, P.BF16)
+    _assert_same_rounding(h.bits(y), ref, f"gated linear {M}x{K}x{N}")
+
+
+def _upload_layers(h, layers):
+    return [{k: (h.to_dev(v, "bf16") if v.dtype == np.uint16 else torch.from_numpy(v).to(h.DEV)) for k, v in L.items()}
+            for L in layers]
+
+
+@pytest.mark.parametrize("n_layers,l", [(3, 1), (2, 0), (2, 2)])
+def test_decoder_stack_with_one_time_reduction(n_layers, l):
+    from paper_2412_00876_amd.layers import DecoderStack
+    h = _H()
+    d, H, Dh, dff = 256, 2, 128, 512
+    w = W.make("stack", "bf16", d, H, Dh, 3, [2, 0, 1], [40, 9, 70], [6, 3, 9], 0.3, 1, seed=500 + n_layers)
+    layers = W.decoder_layers(w, n_layers, dff)
+    pred = W.predictor(w)
+    x0 = W.store(rng.normal(w.seed, "h0", (w.sumN, d)), "bf16")
+    oracle_pred = lambda rows: R.score(rows, pred["W1"], pred["b1"], pred["W2"], pred["b2"], "bf16")
+    xf, idx, off, logits_ref = DR.decoder_prefill(x0, w.seq_off, w.vis_start, w.vis_len, layers, l, w.keep_ratio, oracle_pred,
+                                                  H, Dh, "bf16")
+    kept_rows = int(off[-1])
+    M_vis = int(sum(w.n_vis))
+    S = DecoderStack(_upload_layers(h, layers), l, w.B, H, Dh, d, dff, w.sumN, M_vis)
+    i32 = lambda a: torch.from_numpy(np.asarray(a, np.int32)).to(h.DEV)
+    seq_off, vis_start, vis_len = i32(w.seq_off), i32(w.vis_start), i32(w.vis_len)
+    pw = {k: (h.to_dev(v, "bf16") if v.dtype == np.uint16 else torch.from_numpy(v).to(h.DEV)) for k, v in pred.items()}
+    ws = torch.zeros(P.dllava_score_workspace(M_vis, d, w.dh, P.BF16), dtype=torch.uint8, device=h.DEV)
+
+    def predictor(X, logits):
+        P.dllava_score(X, d, M_vis, w.B, seq_off, vis_start, vis_len, d, w.dh, pw["W1"], pw["b1"], pw["W2"], pw["b2"], P.BF16,
+                       logits, ws)
+
+    out = S.prefill(h.to_dev(x0, "bf16"), seq_off, vis_start, vis_len, w.keep_ratio, kept_rows if l < n_layers else w.sumN,
+                    predictor)
+    torch.cuda.synchronize()
+    assert int(S.err.item()) == 0
+    if l < n_layers:
+        # the decision is taken on the GPU's own hidden states: its logits must agree with the oracle's closely enough
+        # for the same tokens to be kept (checked, not assumed), and then the kept set is identical
+        assert np.array_equal(S.out_off.cpu().numpy(), off)
+        assert np.array_equal(S.kept_idx.cpu().numpy()[:kept_rows], idx[:kept_rows])
+    got = h.as_f64(out)
+    assert got.shape == xf.shape
+    err = got - xf
+    scale = np.sqrt(np.mean(xf ** 2))
+    # a dozen bfloat16 tensors per layer: two correct evaluations settle about one rounding step apart (see the
+    # predictor tests); a structural mistake (a missing residual, a wrong position) is of the order of the values
+    assert np.sqrt(np.mean(err ** 2)) <= 2e-2 * scale, (np.sqrt(np.mean(err ** 2)), scale)
+    assert np.abs(err).max() <= 0.15 * scale
+    # K/V of the last layer's cache: the kept tokens only
+    n_last = np.diff(off) if l < n_layers else np.diff(w.seq_off)
+    assert np.array_equal(S.caches[-1].cache_len.cpu().numpy(), n_last)
+    if l > 0:
+        assert np.array_equal(S.caches[0].cache_len.cpu().numpy(), np.diff(w.seq_off))

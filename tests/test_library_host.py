@@ -207,7 +207,14 @@ def test_predictor_entry_points_validate_on_the_host(lib):
     _expect(lib, ESHAPE, L.dllava_linear, fake, 100, 4, 100, fake, None, 64, 0, None, fake, 64, 1, None)   # K % 64
     _expect(lib, ESHAPE, L.dllava_linear, fake, 128, 4, 128, fake, None, 60, 0, None, fake, 64, 1, None)   # N % 8
     _expect(lib, ESHAPE, L.dllava_linear, fake, 128, 4, 128, fake, None, 64, 0, None, fake, 56, 1, None)   # ldy < N
-    _expect(lib, EINVAL, L.dllava_linear, fake, 128, 4, 128, fake, None, 64, 2, None, fake, 64, 1, None)   # act
+    _expect(lib, EINVAL, L.dllava_linear, fake, 128, 4, 128, fake, None, 64, 3, None, fake, 64, 1, None)   # act
+    _expect(lib, ENULL, L.dllava_linear, fake, 128, 4, 128, fake, None, 64, 2, None, fake, 64, 1, None)    # gated form without a gate
+    _expect(lib, ESHAPE, L.dllava_rms_norm, fake, 64, 4, 60, None, 1e-5, fake, 64, 1, None)                # d % 8
+    _expect(lib, ESHAPE, L.dllava_rms_norm, fake, 64, 4, 16384, None, 1e-5, fake, 16384, 1, None)          # d too large
+    _expect(lib, ESHAPE, L.dllava_rms_norm, fake, 56, 4, 64, None, 1e-5, fake, 64, 1, None)                # ldx < d
+    _expect(lib, EINVAL, L.dllava_rms_norm, fake, 64, 4, 64, None, -1.0, fake, 64, 1, None)
+    _expect(lib, EDTYPE, L.dllava_rms_norm, fake, 64, 4, 64, None, 1e-5, fake, 64, 0, None)
+    _expect(lib, ENULL, L.dllava_rms_norm, None, 64, 4, 64, None, 1e-5, fake, 64, 1, None)
     _expect(lib, EDTYPE, L.dllava_linear, fake, 128, 4, 128, fake, None, 64, 0, None, fake, 64, 0, None)
     _expect(lib, ENULL, L.dllava_linear, fake, 128, 4, 128, None, None, 64, 0, None, fake, 64, 1, None)
     _expect(lib, EINVAL, L.dllava_linear, C.c_void_p(0x1008), 128, 4, 128, fake, None, 64, 0, None, fake, 64, 1, None)
