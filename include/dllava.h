@@ -399,6 +399,19 @@ int dllava_linear(const void* x, int64_t ldx, int64_t M, int64_t K, const void* 
                   int act, const void* residual, void* y, int64_t ldy, int dtype, void* stream);
 int dllava_layer_norm(const void* z, int64_t M, const float* gamma, const float* beta, void* y, int dtype,
                          void* stream);
+/*
+ * The same linear layer for FEW rows (M <= 64: one row per sequence of a decode step), where the weight matrix is
+ * the traffic: W is read once, spread over the chip (blocks of 32 output features x a part of K), partial sums in
+ * `workspace` (dllava_linear_few_workspace(N, K) bytes, 256-byte aligned, scratch) added in a fixed order.
+ * Arguments as dllava_linear; N % 32 == 0.
+ * dllava_rope: rotary rotation IN PLACE of x [rows, H, Dh] at positions pos [rows] (int32), pairing and angles as in
+ * dllava_qkv_project (feature i with i + Dh/2, angle pos * rope_base^(-2i/Dh)): q and k of the tokens of a decode step.
+ */
+int dllava_linear_few(const void* x, int64_t ldx, int64_t M, int64_t K, const void* W, const float* bias, int64_t N,
+                      int act, const void* residual, void* y, int64_t ldy, int dtype,
+                      void* workspace, size_t workspace_bytes, void* stream);
+size_t dllava_linear_few_workspace(int64_t N, int64_t K);
+int dllava_rope(void* x, const int32_t* pos, int64_t rows, int32_t H, int32_t Dh, float rope_base, int dtype, void* stream);
 int dllava_rms_norm(const void* x, int64_t ldx, int64_t M, int64_t d, const float* weight, float eps, void* y,
                     int64_t ldy, int dtype, void* stream);
 int dllava_span_attn(const void* Q, const void* K, const void* V, int32_t B, const int32_t* off, int64_t rows,

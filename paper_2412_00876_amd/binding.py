@@ -97,6 +97,12 @@ def _load() -> C.CDLL:
     lib.dllava_linear.argtypes = [vp, i64, i64, i64, vp, vp, i64, C.c_int, vp, vp, i64, C.c_int, vp]
     lib.dllava_layer_norm.restype = C.c_int
     lib.dllava_layer_norm.argtypes = [vp, i64, vp, vp, vp, C.c_int, vp]
+    lib.dllava_linear_few.restype = C.c_int
+    lib.dllava_linear_few.argtypes = [vp, i64, i64, i64, vp, vp, i64, C.c_int, vp, vp, i64, C.c_int, vp, sz, vp]
+    lib.dllava_linear_few_workspace.restype = sz
+    lib.dllava_linear_few_workspace.argtypes = [i64, i64]
+    lib.dllava_rope.restype = C.c_int
+    lib.dllava_rope.argtypes = [vp, vp, i64, i32, i32, f32, C.c_int, vp]
     lib.dllava_rms_norm.restype = C.c_int
     lib.dllava_rms_norm.argtypes = [vp, i64, i64, i64, vp, f32, vp, i64, C.c_int, vp]
     lib.dllava_span_attn.restype = C.c_int
@@ -110,7 +116,8 @@ EXPORTS = ("dllava_version", "dllava_last_error", "dllava_score", "dllava_score_
            "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_qkv_project",
            "dllava_decode_step", "dllava_decode_step_workspace", "dllava_decode_commit",
            "dllava_predict", "dllava_predict_workspace", "dllava_linear", "dllava_layer_norm", "dllava_span_attn",
-           "dllava_masked_attn", "dllava_masked_attn_workspace", "dllava_compact", "dllava_rms_norm")
+           "dllava_masked_attn", "dllava_masked_attn_workspace", "dllava_compact", "dllava_rms_norm", "dllava_linear_few",
+           "dllava_linear_few_workspace", "dllava_rope")
 
 
 def lib() -> C.CDLL:
@@ -223,6 +230,20 @@ def dllava_linear(x, ldx, M, K, W, bias, N, act, residual, y, ldy, dtype, stream
 
 def dllava_layer_norm(z, M, gamma, beta, y, dtype, stream=None):
     _check(_lib.dllava_layer_norm(_p(z), M, _p(gamma), _p(beta), _p(y), dtype, _stream(stream)))
+
+
+def dllava_linear_few_workspace(N: int, K: int) -> int:
+    return _lib.dllava_linear_few_workspace(N, K)
+
+
+def dllava_linear_few(x, ldx, M, K, W, bias, N, act, residual, y, ldy, dtype, workspace, stream=None):
+    ws, nbytes = _ws(workspace)
+    _check(_lib.dllava_linear_few(_p(x), ldx, M, K, _p(W), _p(bias), N, act, _p(residual), _p(y), ldy, dtype, ws, nbytes,
+                                  _stream(stream)))
+
+
+def dllava_rope(x, pos, rows, H, Dh, rope_base, dtype, stream=None):
+    _check(_lib.dllava_rope(_p(x), _p(pos), rows, H, Dh, rope_base, dtype, _stream(stream)))
 
 
 def dllava_rms_norm(x, ldx, M, d, weight, eps, y, ldy, dtype, stream=None):

@@ -269,20 +269,22 @@ __device__ __forceinline__ void want_now(const uint4& v) { asm volatile("" ::"v"
 // load, one row per lane, touches 32 lines for the same bytes and was measured 4x slower here) and turned into
 // matrix-core fragments through a wave-private LDS area in the swizzled row-major form of gemm_tile.h: chunk c of
 // row rr at chunk position c ^ ((rr / 2) % 8).
+// Block = feature group fg (32 output features) x part kq of the input width; N output features in all, n_fg groups,
+// KQ parts (each cut again over the block's 4 waves); partial sums [KQ][32*NT rows][N] float32.
 template <int NT>  // tiles of 32 rows
 __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict__ X, int64_t ldx, int M, int K,
                                                        const bf16_t* __restrict__ W, float* __restrict__ partial,
                                                        int32_t B, const int32_t* __restrict__ seq_off,
                                                        const int32_t* __restrict__ vis_start,
-                                                       const int32_t* __restrict__ vis_len) {
+                                                       const int32_t* __restrict__ vis_len, int n_fg, int KQ, int N) {
   __shared__ float red[3][NT][16][kWave];
   __shared__ __align__(16) bf16_t stage[4][(1 + NT) * 32 * 64];  // per wave: 32 weight rows and 32*NT input rows x 64 elements
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-  const int fg = blockIdx.x & 15, kq = blockIdx.x >> 4;
+  const int fg = blockIdx.x % n_fg, kq = blockIdx.x / n_fg;
   const int r = lane & 31, g = lane >> 5;
   const int lr8 = lane >> 3, lc = lane & 7;
-  const int total = K / 64;            // 128-byte lines per row
-  const int per = (total + 15) / 16;   // lines of one wave (16 slices of d: 4 blocks x 4 waves)
+  const int total = K / 64;                        // 128-byte lines per row
+  const int per = (total + 4 * KQ - 1) / (4 * KQ); // lines of one wave (4*KQ slices of the input width)
   const int lbeg = (kq * 4 + w) * per;
   const int lend = lbeg + per < total ? lbeg + per : total;
   // this lane's rows: 8j + lane/8 of the 32 weight rows and of every 32-row input tile
@@ -371,7 +373,7 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
         const int i = 4 * q4 + e;
         pv[e] = ((acc[tt][i] + red[0][tt][i][lane]) + red[1][tt][i][lane]) + red[2][tt][i][lane];
       }
-      *reinterpret_cast<float4*>(partial + (static_cast<int64_t>(kq * (32 * NT) + 32 * tt + r)) * kPW + 32 * fg +
+      *reinterpret_cast<float4*>(partial + (static_cast<int64_t>(kq * (32 * NT) + 32 * tt + r)) * N + 32 * fg +
                                  8 * q4 + 4 * g) = v;
     }
 }
@@ -592,6 +594,56 @@ __global__ __launch_bounds__(256) void rms_norm_kernel(const bf16_t* __restrict_
   }
 }
 
+// Second half of a linear layer on few rows: sums the KQ partial results of small_in_kernel in a fixed order, adds
+// the bias, applies the activation and the residual (or the gate), rounds once.  Thread = 4 features of one row.
+__global__ __launch_bounds__(256) void few_finish_kernel(const float* __restrict__ partial, int KQ, int rows_pad, int M, int N,
+                                                         const float* __restrict__ bias, int act,
+                                                         const bf16_t* __restrict__ R, bf16_t* __restrict__ Y, int64_t ldy) {
+  const int64_t it = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int n4 = N / 4;
+  if (it >= static_cast<int64_t>(M) * n4) return;
+  const int m = static_cast<int>(it / n4), f = static_cast<int>(it % n4) * 4;
+  float4 sum = *reinterpret_cast<const float4*>(bias ? bias + f : kZeroWords);
+  for (int q = 0; q < KQ; ++q) {
+    const float4 pq = *reinterpret_cast<const float4*>(partial + (static_cast<int64_t>(q) * rows_pad + m) * N + f);
+    sum.x += pq.x; sum.y += pq.y; sum.z += pq.z; sum.w += pq.w;
+  }
+  if (act == 1) {
+    sum.x = gelu_erf_fast(sum.x); sum.y = gelu_erf_fast(sum.y); sum.z = gelu_erf_fast(sum.z); sum.w = gelu_erf_fast(sum.w);
+  }
+  if (R) {
+    const uint2 rr = *reinterpret_cast<const uint2*>(R + m * ldy + f);
+    const float r0 = bf16lo_to_f32(rr.x), r1 = bf16hi_to_f32(rr.x), r2 = bf16lo_to_f32(rr.y), r3 = bf16hi_to_f32(rr.y);
+    if (act == 2) {
+      sum.x *= silu_fast(r0); sum.y *= silu_fast(r1); sum.z *= silu_fast(r2); sum.w *= silu_fast(r3);
+    } else {
+      sum.x += r0; sum.y += r1; sum.z += r2; sum.w += r3;
+    }
+  }
+  uint2 v;
+  v.x = pack_bf16x2(sum.x, sum.y);
+  v.y = pack_bf16x2(sum.z, sum.w);
+  *reinterpret_cast<uint2*>(Y + m * ldy + f) = v;
+}
+
+// Rotary rotation in place of rows x [rows, H, Dh] at positions pos[row] (half-split pairing: feature i with i + Dh/2,
+// angle pos * base^(-2i/Dh), taken in float64).  Thread = one pair of one (row, head).
+__global__ __launch_bounds__(256) void rope_kernel(bf16_t* __restrict__ x, const int32_t* __restrict__ pos, int64_t rows, int H,
+                                                   int Dh, double log2_base) {
+  const int half = Dh / 2;
+  const int64_t it = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (it >= rows * H * half) return;
+  const int i = static_cast<int>(it % half);
+  const int64_t rh = it / half;  // row * H + head
+  const int64_t row = rh / H;
+  const double ang = static_cast<double>(pos[row]) * exp2(-2.0 * i / Dh * log2_base);
+  const float cs = static_cast<float>(cos(ang)), sn = static_cast<float>(sin(ang));
+  bf16_t* p = x + rh * Dh;
+  const float lo = bf16_to_f32(p[i]), hi = bf16_to_f32(p[i + half]);
+  p[i] = f32_to_bf16(lo * cs - hi * sn);
+  p[i + half] = f32_to_bf16(hi * cs + lo * sn);
+}
+
 struct Regions {
   int32_t* span_off;
   bf16_t *Z, *Y, *QKV, *Hb;
@@ -686,10 +738,10 @@ extern "C" int dllava_predict(const void* x, int64_t ldx, int64_t M, int32_t B, 
     const bf16_t* Wi = static_cast<const bf16_t*>(p->W_in);
     if (nt == 1)
       hipLaunchKernelGGL(small_in_kernel<1>, dim3(16 * kSmallSplit), dim3(256), 0, st, X, ldx, Mi, Ki, Wi, r.small, B,
-                         seq_off, vis_start, vis_len);
+                         seq_off, vis_start, vis_len, 16, kSmallSplit, kPW);
     else
       hipLaunchKernelGGL(small_in_kernel<2>, dim3(16 * kSmallSplit), dim3(256), 0, st, X, ldx, Mi, Ki, Wi, r.small, B,
-                         seq_off, vis_start, vis_len);
+                         seq_off, vis_start, vis_len, 16, kSmallSplit, kPW);
     DLLAVA_CHECK_LAUNCH("small_in_kernel");
     hipLaunchKernelGGL(small_head_kernel, dim3(nt), dim3(256), 0, st, r.small, 32 * nt, Mi, p->b_in,
                        static_cast<const bf16_t*>(p->W_h1), p->b_h1, static_cast<const bf16_t*>(p->W_h2), p->b_h2,
@@ -815,5 +867,78 @@ extern "C" int dllava_rms_norm(const void* x, int64_t ldx, int64_t M, int64_t d,
                      static_cast<hipStream_t>(stream), static_cast<const bf16_t*>(x), ldx, static_cast<bf16_t*>(y), ldy,
                      weight, M, static_cast<int>(d), eps);
   DLLAVA_CHECK_LAUNCH("rms_norm_kernel");
+  return DLLAVA_OK;
+}
+
+// ---- linear layer on few rows (one row per sequence of a decode step) ----------------------------------------------
+
+namespace {
+int few_parts(int64_t N, int64_t K) {  // parts of the input width across blocks: about 384 blocks in all
+  const int64_t n_fg = N / 32, lines = K / 64;
+  int64_t kq = (384 + n_fg - 1) / n_fg;
+  if (kq > 8) kq = 8;
+  if (kq * 4 > lines) kq = (lines + 3) / 4;
+  return static_cast<int>(kq < 1 ? 1 : kq);
+}
+}  // namespace
+
+extern "C" size_t dllava_linear_few_workspace(int64_t N, int64_t K) {
+  if (N <= 0 || K <= 0) return 256;
+  return round_up(static_cast<size_t>(few_parts(N, K)) * kSmallRows * static_cast<size_t>(N) * sizeof(float), 256);
+}
+
+extern "C" int dllava_linear_few(const void* x, int64_t ldx, int64_t M, int64_t K, const void* W, const float* bias,
+                                 int64_t N, int act, const void* residual, void* y, int64_t ldy, int dtype,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  DLLAVA_REQUIRE(dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "linear_few: only DLLAVA_BF16 is supported (got dtype %d)", dtype);
+  DLLAVA_REQUIRE(M >= 0 && M <= kSmallRows, DLLAVA_ESHAPE, "linear_few: at most %d rows (got %lld)", kSmallRows, (long long)M);
+  DLLAVA_REQUIRE(K > 0 && K % 64 == 0 && K <= 0x7fffffffLL, DLLAVA_ESHAPE,
+                 "linear_few: K must be a positive multiple of 64 (got %lld)", (long long)K);
+  DLLAVA_REQUIRE(N > 0 && N % 32 == 0 && N <= 0x7fffffffLL, DLLAVA_ESHAPE,
+                 "linear_few: N must be a positive multiple of 32 (got %lld)", (long long)N);
+  DLLAVA_REQUIRE(ldx >= K && ldx % 8 == 0 && ldy >= N && ldy % 8 == 0, DLLAVA_ESHAPE,
+                 "linear_few: ldx >= K, ldy >= N, both multiples of 8 (got %lld, %lld)", (long long)ldx, (long long)ldy);
+  DLLAVA_REQUIRE(act >= 0 && act <= 2, DLLAVA_EINVAL, "linear_few: act = %d (0: none, 1: GELU, 2: gated)", act);
+  DLLAVA_REQUIRE(act != 2 || residual, DLLAVA_ENULL, "linear_few: act = 2 takes the gate in `residual`");
+  if (M == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(x && W && y, DLLAVA_ENULL, "linear_few: x, W and y are required");
+  DLLAVA_REQUIRE(aligned(x, 16) && aligned(W, 16) && aligned(y, 16) && aligned(residual, 16) && aligned(bias, 16),
+                 DLLAVA_EINVAL, "linear_few: x, W, bias, residual, y must be 16-byte aligned");
+  const size_t need = dllava_linear_few_workspace(N, K);
+  DLLAVA_REQUIRE(workspace && aligned(workspace, 256) && workspace_bytes >= need, DLLAVA_EWORKSPACE,
+                 "linear_few: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int kq = few_parts(N, K), n_fg = static_cast<int>(N / 32), nt = M <= 32 ? 1 : 2;
+  float* partial = static_cast<float*>(workspace);
+  const bf16_t* X = static_cast<const bf16_t*>(x);
+  const bf16_t* Wb = static_cast<const bf16_t*>(W);
+  const int Mi = static_cast<int>(M), Ki = static_cast<int>(K), Ni = static_cast<int>(N);
+  if (nt == 1)
+    hipLaunchKernelGGL(small_in_kernel<1>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, Wb, partial, 0, nullptr, nullptr,
+                       nullptr, n_fg, kq, Ni);
+  else
+    hipLaunchKernelGGL(small_in_kernel<2>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, Wb, partial, 0, nullptr, nullptr,
+                       nullptr, n_fg, kq, Ni);
+  DLLAVA_CHECK_LAUNCH("small_in_kernel");
+  const int64_t items = M * (N / 4);
+  hipLaunchKernelGGL(few_finish_kernel, dim3(static_cast<unsigned>(ceil_div(items, 256))), dim3(256), 0, st, partial, kq,
+                     32 * nt, Mi, Ni, bias, act, static_cast<const bf16_t*>(residual), static_cast<bf16_t*>(y), ldy);
+  DLLAVA_CHECK_LAUNCH("few_finish_kernel");
+  return DLLAVA_OK;
+}
+
+extern "C" int dllava_rope(void* x, const int32_t* pos, int64_t rows, int32_t H, int32_t Dh, float rope_base, int dtype,
+                           void* stream) {
+  DLLAVA_REQUIRE(dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "rope: only DLLAVA_BF16 is supported (got dtype %d)", dtype);
+  DLLAVA_REQUIRE(rows >= 0 && rows <= 0x7fffffffLL && H > 0 && Dh > 0 && Dh % 2 == 0, DLLAVA_ESHAPE,
+                 "rope: rows = %lld, H = %d, Dh = %d", (long long)rows, H, Dh);
+  DLLAVA_REQUIRE(rope_base > 0.f && rope_base < INFINITY, DLLAVA_EINVAL, "rope: bad rope_base");
+  if (rows == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(x && pos, DLLAVA_ENULL, "rope: x and pos are required");
+  const int64_t items = rows * H * (Dh / 2);
+  hipLaunchKernelGGL(rope_kernel, dim3(static_cast<unsigned>(ceil_div(items, 256))), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<bf16_t*>(x), pos, rows, H, Dh,
+                     log2(static_cast<double>(rope_base)));
+  DLLAVA_CHECK_LAUNCH("rope_kernel");
   return DLLAVA_OK;
 }

@@ -98,3 +98,50 @@ def test_decoder_stack_with_one_time_reduction(n_layers, l):
     assert np.array_equal(S.caches[-1].cache_len.cpu().numpy(), n_last)
     if l > 0:
         assert np.array_equal(S.caches[0].cache_len.cpu().numpy(), np.diff(w.seq_off))
+
+
+@pytest.mark.parametrize("M,K,N,act,res", [(16, 4096, 4096, 0, "inplace"), (8, 4096, 11008, 2, "gate"), (40, 11008, 4096, 0, None),
+                                            (1, 64, 32, 1, None), (64, 320, 96, 0, "other")])
+def test_linear_layer_on_few_rows(M, K, N, act, res):
+    h = _H()
+    seed = 3000 + M + K + N
+    x = W.store(rng.normal(seed, "x", (M, K)), "bf16")
+    Wm = W.store(W._normal_big(seed, "W", (N, K)) / np.sqrt(K), "bf16")
+    b = rng.uniform(seed, "b", (N,), -0.5, 0.5).astype(np.float32)
+    r = W.store(rng.normal(seed, "r", (M, N)), "bf16") if res else None
+    ref = R.widen(x, "bf16") @ R.widen(Wm, "bf16").T + b
+    if act == 1:
+        ref = R.gelu(ref)
+    if res == "gate":
+        ref = ref * DR.silu(R.widen(r, "bf16"))
+    elif res:
+        ref = ref + R.widen(r, "bf16")
+    y = torch.zeros((M, N), dtype=torch.bfloat16, device=h.DEV)
+    rd = None
+    if res == "inplace":
+        y.copy_(h.to_dev(r, "bf16"))
+        rd = y
+    elif res:
+        rd = h.to_dev(r, "bf16")
+    ws = torch.full((P.dllava_linear_few_workspace(N, K),), 0x44, dtype=torch.uint8, device=h.DEV)
+    P.dllava_linear_few(h.to_dev(x, "bf16"), K, M, K, h.to_dev(Wm, "bf16"), torch.from_numpy(b).to(h.DEV), N, act, rd, y, N,
+                        P.BF16, ws)
+    _assert_same_rounding(h.bits(y), ref, f"linear on few rows {M}x{K}x{N}")
+    # the tile kernel computes the same layer: the two agree to the rounding of the output
+    y2 = torch.zeros((M, N), dtype=torch.bfloat16, device=h.DEV)
+    if res == "inplace":
+        y2.copy_(h.to_dev(r, "bf16"))
+    P.dllava_linear(h.to_dev(x, "bf16"), K, M, K, h.to_dev(Wm, "bf16"), torch.from_numpy(b).to(h.DEV), N, act,
+                    y2 if res == "inplace" else rd, y2, N, P.BF16)
+    _assert_same_rounding(h.bits(y2), ref, "the tile kernel on the same rows")
+
+
+def test_rope_in_place():
+    h = _H()
+    rows, H, Dh = 37, 3, 128
+    x = W.store(rng.normal(8, "x", (rows, H, Dh)), "bf16")
+    pos = (rng.uniform01(8, "p", 0, rows) * 5000).astype(np.int32)
+    ref = R.rope_rotate(R.widen(x, "bf16"), pos, DR.ROPE_BASE)
+    xd = h.to_dev(x, "bf16")
+    P.dllava_rope(xd, torch.from_numpy(pos).to(h.DEV), rows, H, Dh, DR.ROPE_BASE, P.BF16)
+    _assert_same_rounding(h.bits(xd), ref, "rope")
