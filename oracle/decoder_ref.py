@@ -81,7 +81,7 @@ def decoder_layer(x: np.ndarray, off, pos, L: Dict, H: int, Dh: int, dtype: str,
 
 
 def decoder_prefill(x0, seq_off, vis_start, vis_len, layers: List[Dict], l: int, keep_ratio: float, predictor, H: int,
-                    Dh: int, dtype: str, round_intermediates: bool = True):
+                    Dh: int, dtype: str, round_intermediates: bool = True, caches: Optional[list] = None):
     """Prefill through all layers; after layer l (1-based count of full layers) the image predictor's logits decide
     which image tokens stay (Eq. 11) and the later layers see the reduced set only.
 
@@ -103,5 +103,40 @@ def decoder_prefill(x0, seq_off, vis_start, vis_len, layers: List[Dict], l: int,
             _, idx, off = R.select(logits, seq_off, vis_start, vis_len, R.TOPK, keep_ratio, 0.0)
             src = np.concatenate([seq_off[b] + idx[off[b]:off[b + 1]] for b in range(B)]).astype(np.int64)
             x, pos = x[src], idx[: off[-1]].astype(np.int64)
-        x = decoder_layer(x, off, pos, L, H, Dh, dtype, round_intermediates)
+        x = decoder_layer(x, off, pos, L, H, Dh, dtype, round_intermediates, cache=caches[i] if caches else None)
     return x, idx, off, logits
+
+
+def decoder_decode_step(x_new, pos, layers: List[Dict], caches: list, l: int, theta: float, predictor, H: int, Dh: int,
+                        dtype: str, round_intermediates: bool = True, keep_override=None):
+    """One generated token per sequence through all layers (Eq. 3 per layer; Eq. 6 for the caches).
+
+    x_new [B, d] stored: the token's input rows; pos [B]: its position in the ORIGINAL sequence (dropped tokens count).
+    Layers before l append the token's K/V to their caches unconditionally; after layer l the output-text
+    predictor's logits on the hidden rows decide once (margin > theta), and every later layer appends only if kept
+    (the token still takes part in its own attention in every layer).  Returns (x_out [B, d] float64, keep, logits).
+    """
+    rnd = round_intermediates
+    x = R.widen(x_new, dtype)
+    B = x.shape[0]
+    scale = 1.0 / math.sqrt(Dh)
+    keep, logits = np.ones(B, np.uint8), None
+    for i, L in enumerate(layers):
+        if i == l:
+            logits = predictor(R.narrow(x, dtype))
+            keep = np.asarray(keep_override, np.uint8) if keep_override is not None else R.decode_keep(logits, theta)
+        h1 = _st(rms_norm(x, L["g1"]), dtype, rnd)
+        q, k, v = (h1 @ R.widen(L[n], dtype).T for n in ("Wq", "Wk", "Wv"))
+        q = R.rope_rotate(q.reshape(B, H, Dh), pos, ROPE_BASE)
+        k = R.rope_rotate(k.reshape(B, H, Dh), pos, ROPE_BASE)
+        o, err = R.decode_attn_append(R.narrow(q, dtype), R.narrow(k, dtype), R.narrow(v.reshape(B, H, Dh), dtype),
+                                      keep if i >= l else np.ones(B, np.uint8), caches[i], scale)
+        if np.any(err):
+            raise ValueError("cache capacity exceeded")
+        a = _st(o.reshape(B, H * Dh), dtype, rnd)
+        x = _st(x + a @ R.widen(L["Wo"], dtype).T, dtype, rnd)
+        h2 = _st(rms_norm(x, L["g2"]), dtype, rnd)
+        gate = _st(h2 @ R.widen(L["Wg"], dtype).T, dtype, rnd)
+        f = _st(silu(gate) * (h2 @ R.widen(L["Wu"], dtype).T), dtype, rnd)
+        x = _st(x + f @ R.widen(L["Wd"], dtype).T, dtype, rnd)
+    return x, keep, logits

@@ -105,3 +105,41 @@ def test_layer_attention_equals_the_path_oracle():
     L0 = dict(Lw, Wd=np.zeros_like(Lw["Wd"]))
     got = DR.decoder_layer(R.widen(x, "bf16"), w.seq_off, pos, L0, w.H, w.Dh, "bf16", True)
     assert np.array_equal(got, R.widen(R.narrow(xa, "bf16"), "bf16"))
+
+
+def test_decode_step_equals_prefill_of_the_extended_sequence():
+    """With every generated token kept, a decode step through the stack (caches) gives the last row of a prefill over
+    the sequence extended by that token; with tokens dropped, later layers' caches stay shorter while layers before l
+    keep everything (Sec. 3.3: the decision is taken once and shared by the subsequent layers)."""
+    w = _wl()
+    n_layers, l, T = 3, 1, 3
+    layers = W.decoder_layers(w, n_layers, 96)
+    B, d = w.B, w.d
+    n0 = np.diff(w.seq_off)
+    x0 = W.store(rng.normal(w.seed, "h0", (w.sumN, d)), "f32")
+    xs = [W.store(rng.normal(w.seed, f"new{t}", (B, d)), "f32") for t in range(T)]
+    no_pred = lambda rows: np.tile(np.array([[0.0, 1.0]], np.float32), (len(rows), 1))      # margin +1: keep
+    mk = lambda: [R.PagedCache(B * 4, np.arange(B * 4, dtype=np.int32).reshape(B, 4), w.H, w.Dh, "f32") for _ in layers]
+    caches = mk()
+    DR.decoder_prefill(x0, w.seq_off, w.vis_start, w.vis_len, layers, n_layers, 1.0, no_pred, w.H, w.Dh, "f32", False, caches)
+    outs = []
+    for t in range(T):
+        xo, keep, _ = DR.decoder_decode_step(xs[t], n0 + t, layers, caches, l, 0.0, no_pred, w.H, w.Dh, "f32", False)
+        assert keep.all()
+        outs.append(xo)
+    # the same through one prefill over the extended sequences
+    ext = np.concatenate([np.concatenate([x0[w.seq_off[b]:w.seq_off[b + 1]]] + [xs[t][b:b + 1] for t in range(T)])
+                          for b in range(B)])
+    off_e = np.concatenate([[0], np.cumsum(n0 + T)])
+    xe, _, _, _ = DR.decoder_prefill(ext, off_e, w.vis_start, w.vis_len, layers, n_layers, 1.0, no_pred, w.H, w.Dh, "f32", False)
+    for t in range(T):
+        for b in range(B):
+            assert np.abs(outs[t][b] - xe[off_e[b] + n0[b] + t]).max() < 1e-4      # K/V pass through float32 storage
+    # dropped tokens: layers >= l do not grow, layers < l do
+    caches = mk()
+    DR.decoder_prefill(x0, w.seq_off, w.vis_start, w.vis_len, layers, n_layers, 1.0, no_pred, w.H, w.Dh, "f32", False, caches)
+    drop = lambda rows: np.tile(np.array([[1.0, 0.0]], np.float32), (len(rows), 1))
+    for t in range(T):
+        _, keep, _ = DR.decoder_decode_step(xs[t], n0 + t, layers, caches, l, 0.0, drop, w.H, w.Dh, "f32", False)
+        assert not keep.any()
+    assert list(caches[0].cache_len) == list(n0 + T) and list(caches[1].cache_len) == list(n0) == list(caches[2].cache_len)
