@@ -95,7 +95,7 @@ class DecoderStack:
     ROPE_BASE = 10000.0
 
     def __init__(self, weights, l: int, B: int, H: int, Dh: int, d: int, d_ff: int, sumN: int, vision_rows: int,
-                 max_seq_len: Optional[int] = None, device="cuda:0"):
+                 max_seq_len: Optional[int] = None, extra_tokens: int = 0, device="cuda:0"):
         self.W, self.l, self.B, self.H, self.Dh, self.d, self.d_ff, self.sumN = weights, l, B, H, Dh, d, d_ff, sumN
         self.logits = torch.zeros((max(1, vision_rows), 2), dtype=torch.float32, device=device)
         self.dummy_logits = torch.zeros((max(1, sumN), 2), dtype=torch.float32, device=device)
@@ -108,7 +108,7 @@ class DecoderStack:
         self.err = torch.zeros(1, dtype=torch.int32, device=device)
         self.caches = []
         for _ in weights:
-            mp = ((max_seq_len or sumN) + P.PAGE_SIZE - 1) // P.PAGE_SIZE   # pages per sequence
+            mp = ((max_seq_len or sumN) + extra_tokens + P.PAGE_SIZE - 1) // P.PAGE_SIZE   # pages per sequence
             pages = torch.zeros((B * mp, 2, H, P.PAGE_SIZE, Dh), dtype=bf, device=device)
             bt = torch.arange(B * mp, dtype=torch.int32, device=device).reshape(B, mp).contiguous()
             self.caches.append(P.KVCache(pages, bt, torch.zeros(B, dtype=torch.int32, device=device)))
@@ -118,6 +118,47 @@ class DecoderStack:
         self.out_off = torch.zeros(B + 1, dtype=torch.int32, device=device)
         self.full_idx = torch.zeros(sumN, dtype=torch.int32, device=device)
         self.full_off = torch.zeros(B + 1, dtype=torch.int32, device=device)
+        # decode: one row per sequence
+        self.xd, self.hd = z(B, d), z(B, d)
+        self.qd, self.kd, self.vd, self.od = z(B, H, Dh), z(B, H, Dh), z(B, H, Dh), z(B, H, Dh)
+        self.gd, self.fd = z(B, d_ff), z(B, d_ff)
+        self.ones = torch.ones(B, dtype=torch.uint8, device=device)
+        self.logits_d = torch.zeros((B, 2), dtype=torch.float32, device=device)
+        self.keep_d = torch.zeros(B, dtype=torch.uint8, device=device)
+        zb = lambda n: torch.zeros(n, dtype=torch.uint8, device=device)
+        self.ws_few = zb(max(P.dllava_linear_few_workspace(n, k) for n, k in ((H * Dh, d), (d, H * Dh), (d_ff, d), (d, d_ff))))
+        self.ws_decode = zb(P.dllava_decode_workspace(B, H, Dh, self.caches[0].max_pages_per_seq))
+
+    def decode_step(self, x_new, pos, theta: float, predictor):
+        """One generated token per sequence through all layers.  x_new [B, d]; pos [B] int32: the token's position in the
+        ORIGINAL sequence; predictor(X, logits): the output-text predictor on the B hidden rows after layer l.  Layers
+        before l append the token to their caches; later layers append it where the shared decision says keep.
+        Returns the output rows [B, d] (a view) — the decision is left in self.keep_d / self.logits_d."""
+        W_, d, ff, H, Dh, B, BF = self.W, self.d, self.d_ff, self.H, self.Dh, self.B, P.BF16
+        few = lambda x, K, Wm, N, act, res, y: P.dllava_linear_few(x, K, B, K, Wm, None, N, act, res, y, N, BF, self.ws_few)
+        self.xd.copy_(x_new)
+        X = self.xd
+        for i, Wl in enumerate(W_):
+            if i == self.l:
+                predictor(X, self.logits_d)
+            P.dllava_rms_norm(X, d, B, d, Wl["g1"], self.RMS_EPS, self.hd, d, BF)
+            few(self.hd, d, Wl["Wq"], H * Dh, 0, None, self.qd)
+            few(self.hd, d, Wl["Wk"], H * Dh, 0, None, self.kd)
+            few(self.hd, d, Wl["Wv"], H * Dh, 0, None, self.vd)
+            P.dllava_rope(self.qd, pos, B, H, Dh, self.ROPE_BASE, BF)
+            P.dllava_rope(self.kd, pos, B, H, Dh, self.ROPE_BASE, BF)
+            if i < self.l:
+                P.dllava_decode_attn_append(self.qd, self.kd, self.vd, B, None, 0.0, self.ones, self.caches[i], Dh ** -0.5,
+                                            self.od, None, self.err, self.ws_decode)
+            else:
+                P.dllava_decode_attn_append(self.qd, self.kd, self.vd, B, self.logits_d, theta, None, self.caches[i],
+                                            Dh ** -0.5, self.od, self.keep_d, self.err, self.ws_decode)
+            few(self.od, H * Dh, Wl["Wo"], d, 0, X, X)
+            P.dllava_rms_norm(X, d, B, d, Wl["g2"], self.RMS_EPS, self.hd, d, BF)
+            few(self.hd, d, Wl["Wg"], ff, 0, None, self.gd)
+            few(self.hd, d, Wl["Wu"], ff, 2, self.gd, self.fd)
+            few(self.fd, ff, Wl["Wd"], d, 0, X, X)
+        return X
 
     def _layer(self, i: int, X, rows: int, off, pos):
         """One decoder layer in place on the first `rows` rows of X (rows = host count of off[B])."""

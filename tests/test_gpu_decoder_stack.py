@@ -145,3 +145,59 @@ def test_rope_in_place():
     xd = h.to_dev(x, "bf16")
     P.dllava_rope(xd, torch.from_numpy(pos).to(h.DEV), rows, H, Dh, DR.ROPE_BASE, P.BF16)
     _assert_same_rounding(h.bits(xd), ref, "rope")
+
+
+def test_decode_steps_through_the_stack():
+    """Prefill with the reduction after layer l, then generated tokens one by one through all layers: the text
+    predictor decides once per token (after layer l), layers before l keep every token, later layers the kept ones."""
+    from paper_2412_00876_amd.layers import DecoderStack
+    h = _H()
+    d, H, Dh, dff, n_layers, l, T = 256, 2, 128, 512, 3, 1, 5
+    w = W.make("stackd", "bf16", d, H, Dh, 3, [2, 0, 1], [40, 9, 70], [6, 3, 9], 0.3, T, seed=611)
+    layers = W.decoder_layers(w, n_layers, dff)
+    pred, predt = W.predictor(w), W.predictor(w, random_bias=True)
+    x0 = W.store(rng.normal(w.seed, "h0", (w.sumN, d)), "bf16")
+    xs = [W.store(rng.normal(w.seed, f"new{t}", (w.B, d)), "bf16") for t in range(T)]
+    img = lambda rows: R.score(rows, pred["W1"], pred["b1"], pred["W2"], pred["b2"], "bf16")
+    txt = lambda rows: R.score(rows, predt["W1"], predt["b1"], predt["W2"], predt["b2"], "bf16")
+    n0 = np.diff(w.seq_off)
+    cap = int(n0.max()) + T
+    mp = (cap + 15) // 16
+    caches = [R.PagedCache(w.B * mp, np.arange(w.B * mp, dtype=np.int32).reshape(w.B, mp), H, Dh, "bf16") for _ in layers]
+    xf, idx, off, _ = DR.decoder_prefill(x0, w.seq_off, w.vis_start, w.vis_len, layers, l, w.keep_ratio, img, H, Dh, "bf16",
+                                         True, caches)
+    M_vis = int(sum(w.n_vis))
+    S = DecoderStack(_upload_layers(h, layers), l, w.B, H, Dh, d, dff, w.sumN, M_vis, max_seq_len=int(n0.max()), extra_tokens=T)
+    i32 = lambda a: torch.from_numpy(np.asarray(a, np.int32)).to(h.DEV)
+    seq_off, vis_start, vis_len = i32(w.seq_off), i32(w.vis_start), i32(w.vis_len)
+    up = lambda P_: {k: (h.to_dev(v, "bf16") if v.dtype == np.uint16 else torch.from_numpy(v).to(h.DEV)) for k, v in P_.items()}
+    pw, pt = up(pred), up(predt)
+    ws = torch.zeros(P.dllava_score_workspace(max(M_vis, 64), d, w.dh, P.BF16), dtype=torch.uint8, device=h.DEV)
+
+    def image_predictor(X, logits):
+        P.dllava_score(X, d, M_vis, w.B, seq_off, vis_start, vis_len, d, w.dh, pw["W1"], pw["b1"], pw["W2"], pw["b2"], P.BF16,
+                       logits, ws)
+
+    def text_predictor(X, logits):
+        P.dllava_score(X, d, w.B, 0, None, None, None, d, w.dh, pt["W1"], pt["b1"], pt["W2"], pt["b2"], P.BF16, logits, ws)
+
+    S.prefill(h.to_dev(x0, "bf16"), seq_off, vis_start, vis_len, w.keep_ratio, int(off[-1]), image_predictor)
+    assert np.array_equal(S.out_off.cpu().numpy(), off)
+    theta = 0.0
+    for t in range(T):
+        pos = n0 + t
+        xo_ref, keep_ref, logits_ref = DR.decoder_decode_step(xs[t], pos, layers, caches, l, theta, txt, H, Dh, "bf16")
+        xo = S.decode_step(h.to_dev(xs[t], "bf16"), i32(pos), theta, text_predictor)
+        torch.cuda.synchronize()
+        lg = S.logits_d.cpu().numpy()
+        assert np.abs(lg - logits_ref).max() <= 5e-2
+        assert np.abs((logits_ref[:, 1] - logits_ref[:, 0]) - theta).min() > 4 * np.abs(lg - logits_ref).max()   # away from ties
+        assert np.array_equal(S.keep_d.cpu().numpy(), keep_ref)
+        err = h.as_f64(xo) - xo_ref
+        scale = np.sqrt(np.mean(xo_ref ** 2))
+        assert np.sqrt(np.mean(err ** 2)) <= 2e-2 * scale and np.abs(err).max() <= 0.15 * scale, t
+        for i in range(n_layers):
+            assert np.array_equal(S.caches[i].cache_len.cpu().numpy(), caches[i].cache_len), (t, i)
+    assert int(S.err.item()) == 0
+    assert list(caches[0].cache_len) == list(n0 + T)                                 # a layer before l keeps every token
+    assert list(caches[2].cache_len) != list(np.diff(off) + T)                       # later layers dropped some
