@@ -528,12 +528,23 @@ def main():
                 P.dllava_score(X, w.d, path.M_vis, B, path.seq_off, path.vis_start, path.vis_len, w.d, w.dh, p["W1"], p["b1"],
                                p["W2"], p["b2"], path.code, logits, path.ws_score_vis)
 
-            res = {}
+            def score_rows(X, logits):
+                p = path.pred
+                P.dllava_score(X, w.d, B, 0, None, None, None, w.d, w.dh, p["W1"], p["b1"], p["W2"], p["b2"], path.code, logits,
+                               path.ws_score_dec)
+
+            res, res_dec, kv_dec = {}, {}, {}
+            Td = 32                                            # decode steps through the stack, right after the prefill
+            pos_t = torch.from_numpy((np.asarray(w.seq_len)[None, :] + np.arange(Td)[:, None]).astype(np.int32)).to("cuda:0")
             for name, l_red, rows_after in (("sparsified_after_layer_2", 2, path.rows_kept), ("dense", n_layers, w.sumN)):
-                S = DecoderStack(wts, l_red, B, H, Dh, w.d, d_ff, w.sumN, path.M_vis, max_seq_len=int(max(w.seq_len)))
+                S = DecoderStack(wts, l_red, B, H, Dh, w.d, d_ff, w.sumN, path.M_vis, max_seq_len=int(max(w.seq_len)),
+                                 extra_tokens=Td)
                 run_stack = lambda i, S=S, rows_after=rows_after: S.prefill(path.pre["hidden"], path.seq_off, path.vis_start,
                                                                              path.vis_len, w.keep_ratio, rows_after, score_into)
                 res[name] = stage_ms(run_stack, 1, reps=3)
+                run_dec = lambda i, S=S: S.decode_step(path.dec["x"][i], pos_t[i], w.theta, score_rows)
+                res_dec[name] = stage_ms(run_dec, Td, before=lambda S=S, r=run_stack: r(0), reps=2) * 1e3    # us per step
+                kv_dec[name] = S.kv_bytes() / 1e9
                 assert int(S.err.item()) == 0
                 del S
             per_tok = 2.0 * (4 * w.d * H * Dh + 3 * w.d * d_ff)          # linear-layer flops per token and layer
@@ -544,6 +555,10 @@ def main():
             lay_d = res["dense"] / n_layers
             lay_s = (res["sparsified_after_layer_2"] - 2 * lay_d) / (n_layers - 2)
             stack["projected_32_layers_ms"] = {"dense": 32 * lay_d, "sparsified_after_layer_2": 2 * lay_d + 30 * lay_s}
+            stack["decode_us_per_step"] = res_dec
+            stack["decode_tokens_per_s"] = {k: B / (v * 1e-6) for k, v in res_dec.items()}
+            stack["decode_steps"] = Td
+            stack["kv_gb_after_decode"] = kv_dec
             del wts
         ms_prefill = stage_ms(lambda i: path.prefill_attn(), 5)
         ms_sd = stage_ms(path.score_decode, T)                          # logits of all steps: inputs of the next line

@@ -160,6 +160,10 @@ class DecoderStack:
             few(self.fd, ff, Wl["Wd"], d, 0, X, X)
         return X
 
+    def kv_bytes(self) -> int:
+        """Bytes of K and V held by all layers right now."""
+        return int(sum(int(c.cache_len.sum().item()) for c in self.caches)) * 2 * self.H * self.Dh * 2
+
     def _layer(self, i: int, X, rows: int, off, pos):
         """One decoder layer in place on the first `rows` rows of X (rows = host count of off[B])."""
         W, d, ff, H, Dh, BF = self.W[i], self.d, self.d_ff, self.H, self.Dh, P.BF16
