@@ -256,3 +256,24 @@ def test_compact_validates_on_the_host(lib):
     _expect(lib, ENULL, L.dllava_compact, *call(40, fake, fake, 64, None, None, None, 1, idx=None))
     _expect(lib, EINVAL, L.dllava_compact, *call(-1, fake, fake, 64, None, None, None, 1))
     assert L.dllava_compact(*call(0, fake, fake, 64, None, None, None, 1)) == 0                  # nothing to move
+
+
+def test_few_rows_linear_and_rope_validate_on_the_host(lib):
+    L = lib.lib()
+    EINVAL, ENULL, ESHAPE, EDTYPE, EWORKSPACE = -1, -2, -3, -4, -6
+    fake = C.c_void_p(0x1000)
+    big = 1 << 28
+    call = lambda M, K, N, act, res, ws, wsb, dtype=1: (fake, K, M, K, fake, None, N, act, res, fake, N, dtype, ws, wsb, None)
+    _expect(lib, ESHAPE, L.dllava_linear_few, *call(65, 128, 64, 0, None, fake, big))        # too many rows for this form
+    _expect(lib, ESHAPE, L.dllava_linear_few, *call(4, 100, 64, 0, None, fake, big))
+    _expect(lib, ESHAPE, L.dllava_linear_few, *call(4, 128, 40, 0, None, fake, big))         # N % 32
+    _expect(lib, ENULL, L.dllava_linear_few, *call(4, 128, 64, 2, None, fake, big))
+    _expect(lib, EWORKSPACE, L.dllava_linear_few, *call(4, 128, 64, 0, None, None, 0))
+    _expect(lib, EWORKSPACE, L.dllava_linear_few, *call(4, 128, 64, 0, None, fake, 16))
+    _expect(lib, EDTYPE, L.dllava_linear_few, *call(4, 128, 64, 0, None, fake, big, dtype=0))
+    assert lib.dllava_linear_few_workspace(4096, 4096) % 256 == 0
+    assert lib.dllava_linear_few_workspace(11008, 4096) >= 64 * 11008 * 4
+    _expect(lib, ESHAPE, L.dllava_rope, fake, fake, 4, 2, 63, 10000.0, 1, None)
+    _expect(lib, EINVAL, L.dllava_rope, fake, fake, 4, 2, 64, 0.0, 1, None)
+    _expect(lib, ENULL, L.dllava_rope, fake, None, 4, 2, 64, 10000.0, 1, None)
+    _expect(lib, EDTYPE, L.dllava_rope, fake, fake, 4, 2, 64, 10000.0, 0, None)
