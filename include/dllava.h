@@ -412,6 +412,20 @@ int dllava_linear_few(const void* x, int64_t ldx, int64_t M, int64_t K, const vo
                       void* workspace, size_t workspace_bytes, void* stream);
 size_t dllava_linear_few_workspace(int64_t N, int64_t K);
 int dllava_rope(void* x, const int32_t* pos, int64_t rows, int32_t H, int32_t Dh, float rope_base, int dtype, void* stream);
+/*
+ * Two fused forms of dllava_linear_few for a decode step through a decoder layer (M <= 64 rows):
+ * dllava_qkv_few:   q, k, v [M, H, Dh] = x Wq^T, x Wk^T, x Wv^T with q and k rotated at pos[row] (as dllava_rope), the
+ *                   three matrices [H*Dh, d] read once in one launch.
+ * dllava_gated_few: y [M, F] = (x Wu^T) * SiLU(x Wg^T), the gate rounded to dtype before the SiLU (as if it had been
+ *                   stored), Wg and Wu [F, d] read once in one launch.  F % 32 == 0.
+ * workspace: dllava_decode_proj_workspace(N_total, d) bytes with N_total = 3*H*Dh resp. 2*F, 256-byte aligned, scratch.
+ */
+int dllava_qkv_few(const void* x, int64_t ldx, int64_t M, int64_t d, const void* Wq, const void* Wk, const void* Wv,
+                   int32_t H, int32_t Dh, const int32_t* pos, float rope_base, void* q, void* k, void* v, int dtype,
+                   void* workspace, size_t workspace_bytes, void* stream);
+int dllava_gated_few(const void* x, int64_t ldx, int64_t M, int64_t d, const void* Wg, const void* Wu, int64_t F,
+                     void* y, int64_t ldy, int dtype, void* workspace, size_t workspace_bytes, void* stream);
+size_t dllava_decode_proj_workspace(int64_t N_total, int64_t K);
 int dllava_rms_norm(const void* x, int64_t ldx, int64_t M, int64_t d, const float* weight, float eps, void* y,
                     int64_t ldy, int dtype, void* stream);
 int dllava_span_attn(const void* Q, const void* K, const void* V, int32_t B, const int32_t* off, int64_t rows,

@@ -8,7 +8,7 @@ _BINDING_NAMES = ("BF16", "F32", "MODE_THRESHOLD", "MODE_THRESHOLD_KEEP_LAST", "
                   "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_prefill_attn", "dllava_score",
                   "dllava_score_workspace", "dllava_qkv_project", "dllava_decode_step", "dllava_decode_step_workspace",
                   "dllava_decode_commit", "dllava_predict", "dllava_predict_workspace", "Predictor", "dllava_linear", "dllava_layer_norm",
-                  "dllava_span_attn", "dllava_masked_attn", "dllava_masked_attn_workspace", "dllava_compact", "dllava_rms_norm", "dllava_linear_few", "dllava_linear_few_workspace", "dllava_rope",
+                  "dllava_span_attn", "dllava_masked_attn", "dllava_masked_attn_workspace", "dllava_compact", "dllava_rms_norm", "dllava_linear_few", "dllava_linear_few_workspace", "dllava_rope", "dllava_qkv_few", "dllava_gated_few", "dllava_decode_proj_workspace",
                   "dllava_select_compact", "dllava_select_compact_workspace", "dllava_version", "lib")
 
 

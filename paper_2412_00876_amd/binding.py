@@ -101,6 +101,12 @@ def _load() -> C.CDLL:
     lib.dllava_linear_few.argtypes = [vp, i64, i64, i64, vp, vp, i64, C.c_int, vp, vp, i64, C.c_int, vp, sz, vp]
     lib.dllava_linear_few_workspace.restype = sz
     lib.dllava_linear_few_workspace.argtypes = [i64, i64]
+    lib.dllava_qkv_few.restype = C.c_int
+    lib.dllava_qkv_few.argtypes = [vp, i64, i64, i64, vp, vp, vp, i32, i32, vp, f32, vp, vp, vp, C.c_int, vp, sz, vp]
+    lib.dllava_gated_few.restype = C.c_int
+    lib.dllava_gated_few.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, i64, C.c_int, vp, sz, vp]
+    lib.dllava_decode_proj_workspace.restype = sz
+    lib.dllava_decode_proj_workspace.argtypes = [i64, i64]
     lib.dllava_rope.restype = C.c_int
     lib.dllava_rope.argtypes = [vp, vp, i64, i32, i32, f32, C.c_int, vp]
     lib.dllava_rms_norm.restype = C.c_int
@@ -117,7 +123,8 @@ EXPORTS = ("dllava_version", "dllava_last_error", "dllava_score", "dllava_score_
            "dllava_decode_step", "dllava_decode_step_workspace", "dllava_decode_commit",
            "dllava_predict", "dllava_predict_workspace", "dllava_linear", "dllava_layer_norm", "dllava_span_attn",
            "dllava_masked_attn", "dllava_masked_attn_workspace", "dllava_compact", "dllava_rms_norm", "dllava_linear_few",
-           "dllava_linear_few_workspace", "dllava_rope")
+           "dllava_linear_few_workspace", "dllava_rope", "dllava_qkv_few", "dllava_gated_few",
+           "dllava_decode_proj_workspace")
 
 
 def lib() -> C.CDLL:
@@ -240,6 +247,21 @@ def dllava_linear_few(x, ldx, M, K, W, bias, N, act, residual, y, ldy, dtype, wo
     ws, nbytes = _ws(workspace)
     _check(_lib.dllava_linear_few(_p(x), ldx, M, K, _p(W), _p(bias), N, act, _p(residual), _p(y), ldy, dtype, ws, nbytes,
                                   _stream(stream)))
+
+
+def dllava_decode_proj_workspace(N_total: int, K: int) -> int:
+    return _lib.dllava_decode_proj_workspace(N_total, K)
+
+
+def dllava_qkv_few(x, ldx, M, d, Wq, Wk, Wv, H, Dh, pos, rope_base, q, k, v, dtype, workspace, stream=None):
+    ws, nbytes = _ws(workspace)
+    _check(_lib.dllava_qkv_few(_p(x), ldx, M, d, _p(Wq), _p(Wk), _p(Wv), H, Dh, _p(pos), rope_base, _p(q), _p(k), _p(v),
+                               dtype, ws, nbytes, _stream(stream)))
+
+
+def dllava_gated_few(x, ldx, M, d, Wg, Wu, F, y, ldy, dtype, workspace, stream=None):
+    ws, nbytes = _ws(workspace)
+    _check(_lib.dllava_gated_few(_p(x), ldx, M, d, _p(Wg), _p(Wu), F, _p(y), ldy, dtype, ws, nbytes, _stream(stream)))
 
 
 def dllava_rope(x, pos, rows, H, Dh, rope_base, dtype, stream=None):

@@ -276,7 +276,10 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
                                                        const bf16_t* __restrict__ W, float* __restrict__ partial,
                                                        int32_t B, const int32_t* __restrict__ seq_off,
                                                        const int32_t* __restrict__ vis_start,
-                                                       const int32_t* __restrict__ vis_len, int n_fg, int KQ, int N) {
+                                                       const int32_t* __restrict__ vis_len, int n_fg, int KQ, int N,
+                                                       const bf16_t* __restrict__ W1, const bf16_t* __restrict__ W2,
+                                                       int fg_each) {
+  // up to three matrices of fg_each feature groups each, one after the other along the N output features
   __shared__ float red[3][NT][16][kWave];
   __shared__ __align__(16) bf16_t stage[4][(1 + NT) * 32 * 64];  // per wave: 32 weight rows and 32*NT input rows x 64 elements
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
@@ -292,7 +295,9 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
   const bf16_t* xrow[NT][4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    wrow[j] = W + static_cast<int64_t>(32 * fg + 8 * j + lr8) * K + 8 * lc;
+    const int which = fg / fg_each;
+    const bf16_t* Wm = which == 0 ? W : (which == 1 ? W1 : W2);
+    wrow[j] = Wm + static_cast<int64_t>(32 * (fg % fg_each) + 8 * j + lr8) * K + 8 * lc;
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) {
       int64_t m = 32 * tt + 8 * j + lr8;
@@ -644,6 +649,68 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t* __restrict__ x, const
   p[i + half] = f32_to_bf16(hi * cs + lo * sn);
 }
 
+// Finish of the fused q|k|v layer of a decode step: partial sums over [q | k | v] features (3 * H * Dh), rotary
+// rotation of q and k at pos[row] (pairs (i, i + Dh/2) of a head), one rounding.  Thread = 4 features of the lower
+// half of a head and their 4 partners of the upper half, of q, k or v of one row.
+__global__ __launch_bounds__(256) void few_finish_qkv_kernel(const float* __restrict__ partial, int KQ, int rows_pad, int M,
+                                                             int H, int Dh, const int32_t* __restrict__ pos,
+                                                             double log2_base, bf16_t* __restrict__ q,
+                                                             bf16_t* __restrict__ k, bf16_t* __restrict__ v) {
+  const int half = Dh / 2, per_head = half / 4, HD = H * Dh, N = 3 * HD;
+  const int64_t it = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (it >= static_cast<int64_t>(M) * 3 * H * per_head) return;
+  const int i4 = static_cast<int>(it % per_head) * 4;
+  const int head = static_cast<int>((it / per_head) % H);
+  const int which = static_cast<int>((it / (per_head * H)) % 3);
+  const int m = static_cast<int>(it / (static_cast<int64_t>(per_head) * H * 3));
+  const int f = which * HD + head * Dh + i4;
+  float lo[4] = {0.f, 0.f, 0.f, 0.f}, hi[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int p = 0; p < KQ; ++p) {
+    const float* row = partial + (static_cast<int64_t>(p) * rows_pad + m) * N + f;
+    const float4 a = *reinterpret_cast<const float4*>(row), b = *reinterpret_cast<const float4*>(row + half);
+    lo[0] += a.x; lo[1] += a.y; lo[2] += a.z; lo[3] += a.w;
+    hi[0] += b.x; hi[1] += b.y; hi[2] += b.z; hi[3] += b.w;
+  }
+  if (which < 2) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const double ang = static_cast<double>(pos[m]) * exp2(-2.0 * (i4 + e) / Dh * log2_base);
+      const float cs = static_cast<float>(cos(ang)), sn = static_cast<float>(sin(ang));
+      const float a = lo[e], b = hi[e];
+      lo[e] = a * cs - b * sn;
+      hi[e] = b * cs + a * sn;
+    }
+  }
+  bf16_t* out = (which == 0 ? q : (which == 1 ? k : v)) + static_cast<int64_t>(m) * HD + head * Dh + i4;
+  uint2 w0, w1;
+  w0.x = pack_bf16x2(lo[0], lo[1]); w0.y = pack_bf16x2(lo[2], lo[3]);
+  w1.x = pack_bf16x2(hi[0], hi[1]); w1.y = pack_bf16x2(hi[2], hi[3]);
+  *reinterpret_cast<uint2*>(out) = w0;
+  *reinterpret_cast<uint2*>(out + half) = w1;
+}
+
+// Finish of the fused gate|up layer: y = up * SiLU(gate), the gate rounded to the storage type first (as if stored).
+__global__ __launch_bounds__(256) void few_finish_gated_kernel(const float* __restrict__ partial, int KQ, int rows_pad, int M,
+                                                               int F, bf16_t* __restrict__ Y, int64_t ldy) {
+  const int64_t it = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int n4 = F / 4;
+  if (it >= static_cast<int64_t>(M) * n4) return;
+  const int m = static_cast<int>(it / n4), f = static_cast<int>(it % n4) * 4;
+  float4 gs = {0.f, 0.f, 0.f, 0.f}, us = {0.f, 0.f, 0.f, 0.f};
+  for (int p = 0; p < KQ; ++p) {
+    const float* row = partial + (static_cast<int64_t>(p) * rows_pad + m) * (2 * F) + f;
+    const float4 a = *reinterpret_cast<const float4*>(row), b = *reinterpret_cast<const float4*>(row + F);
+    gs.x += a.x; gs.y += a.y; gs.z += a.z; gs.w += a.w;
+    us.x += b.x; us.y += b.y; us.z += b.z; us.w += b.w;
+  }
+  const float g0 = bf16_to_f32(f32_to_bf16(gs.x)), g1 = bf16_to_f32(f32_to_bf16(gs.y));
+  const float g2 = bf16_to_f32(f32_to_bf16(gs.z)), g3 = bf16_to_f32(f32_to_bf16(gs.w));
+  uint2 o;
+  o.x = pack_bf16x2(us.x * silu_fast(g0), us.y * silu_fast(g1));
+  o.y = pack_bf16x2(us.z * silu_fast(g2), us.w * silu_fast(g3));
+  *reinterpret_cast<uint2*>(Y + m * ldy + f) = o;
+}
+
 struct Regions {
   int32_t* span_off;
   bf16_t *Z, *Y, *QKV, *Hb;
@@ -738,10 +805,10 @@ extern "C" int dllava_predict(const void* x, int64_t ldx, int64_t M, int32_t B, 
     const bf16_t* Wi = static_cast<const bf16_t*>(p->W_in);
     if (nt == 1)
       hipLaunchKernelGGL(small_in_kernel<1>, dim3(16 * kSmallSplit), dim3(256), 0, st, X, ldx, Mi, Ki, Wi, r.small, B,
-                         seq_off, vis_start, vis_len, 16, kSmallSplit, kPW);
+                         seq_off, vis_start, vis_len, 16, kSmallSplit, kPW, nullptr, nullptr, 16);
     else
       hipLaunchKernelGGL(small_in_kernel<2>, dim3(16 * kSmallSplit), dim3(256), 0, st, X, ldx, Mi, Ki, Wi, r.small, B,
-                         seq_off, vis_start, vis_len, 16, kSmallSplit, kPW);
+                         seq_off, vis_start, vis_len, 16, kSmallSplit, kPW, nullptr, nullptr, 16);
     DLLAVA_CHECK_LAUNCH("small_in_kernel");
     hipLaunchKernelGGL(small_head_kernel, dim3(nt), dim3(256), 0, st, r.small, 32 * nt, Mi, p->b_in,
                        static_cast<const bf16_t*>(p->W_h1), p->b_h1, static_cast<const bf16_t*>(p->W_h2), p->b_h2,
@@ -915,10 +982,10 @@ extern "C" int dllava_linear_few(const void* x, int64_t ldx, int64_t M, int64_t 
   const int Mi = static_cast<int>(M), Ki = static_cast<int>(K), Ni = static_cast<int>(N);
   if (nt == 1)
     hipLaunchKernelGGL(small_in_kernel<1>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, Wb, partial, 0, nullptr, nullptr,
-                       nullptr, n_fg, kq, Ni);
+                       nullptr, n_fg, kq, Ni, nullptr, nullptr, n_fg);
   else
     hipLaunchKernelGGL(small_in_kernel<2>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, Wb, partial, 0, nullptr, nullptr,
-                       nullptr, n_fg, kq, Ni);
+                       nullptr, n_fg, kq, Ni, nullptr, nullptr, n_fg);
   DLLAVA_CHECK_LAUNCH("small_in_kernel");
   const int64_t items = M * (N / 4);
   hipLaunchKernelGGL(few_finish_kernel, dim3(static_cast<unsigned>(ceil_div(items, 256))), dim3(256), 0, st, partial, kq,
@@ -940,5 +1007,88 @@ extern "C" int dllava_rope(void* x, const int32_t* pos, int64_t rows, int32_t H,
                      static_cast<hipStream_t>(stream), static_cast<bf16_t*>(x), pos, rows, H, Dh,
                      log2(static_cast<double>(rope_base)));
   DLLAVA_CHECK_LAUNCH("rope_kernel");
+  return DLLAVA_OK;
+}
+
+// ---- fused forms for a decode step: q|k|v with rotary rotation, gate|up with the gating ---------------------------
+
+extern "C" size_t dllava_decode_proj_workspace(int64_t N_total, int64_t K) { return dllava_linear_few_workspace(N_total, K); }
+
+extern "C" int dllava_qkv_few(const void* x, int64_t ldx, int64_t M, int64_t d, const void* Wq, const void* Wk,
+                              const void* Wv, int32_t H, int32_t Dh, const int32_t* pos, float rope_base, void* q, void* k,
+                              void* v, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  DLLAVA_REQUIRE(dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "qkv_few: only DLLAVA_BF16 is supported (got dtype %d)", dtype);
+  DLLAVA_REQUIRE(M >= 0 && M <= kSmallRows, DLLAVA_ESHAPE, "qkv_few: at most %d rows (got %lld)", kSmallRows, (long long)M);
+  DLLAVA_REQUIRE(d > 0 && d % 64 == 0 && d <= 0x7fffffffLL && ldx >= d && ldx % 8 == 0, DLLAVA_ESHAPE,
+                 "qkv_few: d must be a positive multiple of 64, ldx >= d a multiple of 8 (got %lld, %lld)", (long long)d,
+                 (long long)ldx);
+  DLLAVA_REQUIRE(H > 0 && Dh > 0 && Dh % 8 == 0 && (static_cast<int64_t>(H) * Dh) % 32 == 0, DLLAVA_ESHAPE,
+                 "qkv_few: H = %d, Dh = %d (Dh %% 8 == 0, H * Dh %% 32 == 0)", H, Dh);
+  DLLAVA_REQUIRE(rope_base > 0.f && rope_base < INFINITY, DLLAVA_EINVAL, "qkv_few: bad rope_base");
+  if (M == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(x && Wq && Wk && Wv && pos && q && k && v, DLLAVA_ENULL, "qkv_few: x, Wq, Wk, Wv, pos, q, k, v are required");
+  DLLAVA_REQUIRE(aligned(x, 16) && aligned(Wq, 16) && aligned(Wk, 16) && aligned(Wv, 16) && aligned(q, 16) && aligned(k, 16) &&
+                     aligned(v, 16),
+                 DLLAVA_EINVAL, "qkv_few: tensors must be 16-byte aligned");
+  const int64_t HD = static_cast<int64_t>(H) * Dh, N = 3 * HD;
+  const size_t need = dllava_linear_few_workspace(N, d);
+  DLLAVA_REQUIRE(workspace && aligned(workspace, 256) && workspace_bytes >= need, DLLAVA_EWORKSPACE,
+                 "qkv_few: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int kq = few_parts(N, d), n_fg = static_cast<int>(N / 32), nt = M <= 32 ? 1 : 2;
+  float* partial = static_cast<float*>(workspace);
+  const bf16_t* X = static_cast<const bf16_t*>(x);
+  const int Mi = static_cast<int>(M), Ki = static_cast<int>(d), Ni = static_cast<int>(N), each = static_cast<int>(HD / 32);
+  if (nt == 1)
+    hipLaunchKernelGGL(small_in_kernel<1>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, static_cast<const bf16_t*>(Wq),
+                       partial, 0, nullptr, nullptr, nullptr, n_fg, kq, Ni, static_cast<const bf16_t*>(Wk),
+                       static_cast<const bf16_t*>(Wv), each);
+  else
+    hipLaunchKernelGGL(small_in_kernel<2>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, static_cast<const bf16_t*>(Wq),
+                       partial, 0, nullptr, nullptr, nullptr, n_fg, kq, Ni, static_cast<const bf16_t*>(Wk),
+                       static_cast<const bf16_t*>(Wv), each);
+  DLLAVA_CHECK_LAUNCH("small_in_kernel");
+  const int64_t items = M * 3 * H * (Dh / 8);
+  hipLaunchKernelGGL(few_finish_qkv_kernel, dim3(static_cast<unsigned>(ceil_div(items, 256))), dim3(256), 0, st, partial, kq,
+                     32 * nt, Mi, H, Dh, pos, log2(static_cast<double>(rope_base)), static_cast<bf16_t*>(q),
+                     static_cast<bf16_t*>(k), static_cast<bf16_t*>(v));
+  DLLAVA_CHECK_LAUNCH("few_finish_qkv_kernel");
+  return DLLAVA_OK;
+}
+
+extern "C" int dllava_gated_few(const void* x, int64_t ldx, int64_t M, int64_t d, const void* Wg, const void* Wu, int64_t F,
+                                void* y, int64_t ldy, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  DLLAVA_REQUIRE(dtype == DLLAVA_BF16, DLLAVA_EDTYPE, "gated_few: only DLLAVA_BF16 is supported (got dtype %d)", dtype);
+  DLLAVA_REQUIRE(M >= 0 && M <= kSmallRows, DLLAVA_ESHAPE, "gated_few: at most %d rows (got %lld)", kSmallRows, (long long)M);
+  DLLAVA_REQUIRE(d > 0 && d % 64 == 0 && d <= 0x7fffffffLL && ldx >= d && ldx % 8 == 0, DLLAVA_ESHAPE,
+                 "gated_few: d must be a positive multiple of 64, ldx >= d a multiple of 8 (got %lld, %lld)", (long long)d,
+                 (long long)ldx);
+  DLLAVA_REQUIRE(F > 0 && F % 32 == 0 && F <= 0x3fffffffLL && ldy >= F && ldy % 8 == 0, DLLAVA_ESHAPE,
+                 "gated_few: F must be a positive multiple of 32, ldy >= F a multiple of 8 (got %lld, %lld)", (long long)F,
+                 (long long)ldy);
+  if (M == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(x && Wg && Wu && y, DLLAVA_ENULL, "gated_few: x, Wg, Wu and y are required");
+  DLLAVA_REQUIRE(aligned(x, 16) && aligned(Wg, 16) && aligned(Wu, 16) && aligned(y, 16), DLLAVA_EINVAL,
+                 "gated_few: tensors must be 16-byte aligned");
+  const int64_t N = 2 * F;
+  const size_t need = dllava_linear_few_workspace(N, d);
+  DLLAVA_REQUIRE(workspace && aligned(workspace, 256) && workspace_bytes >= need, DLLAVA_EWORKSPACE,
+                 "gated_few: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int kq = few_parts(N, d), n_fg = static_cast<int>(N / 32), nt = M <= 32 ? 1 : 2;
+  float* partial = static_cast<float*>(workspace);
+  const bf16_t* X = static_cast<const bf16_t*>(x);
+  const int Mi = static_cast<int>(M), Ki = static_cast<int>(d), Ni = static_cast<int>(N), each = static_cast<int>(F / 32);
+  if (nt == 1)
+    hipLaunchKernelGGL(small_in_kernel<1>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, static_cast<const bf16_t*>(Wg),
+                       partial, 0, nullptr, nullptr, nullptr, n_fg, kq, Ni, static_cast<const bf16_t*>(Wu), nullptr, each);
+  else
+    hipLaunchKernelGGL(small_in_kernel<2>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, static_cast<const bf16_t*>(Wg),
+                       partial, 0, nullptr, nullptr, nullptr, n_fg, kq, Ni, static_cast<const bf16_t*>(Wu), nullptr, each);
+  DLLAVA_CHECK_LAUNCH("small_in_kernel");
+  const int64_t items = M * (F / 4);
+  hipLaunchKernelGGL(few_finish_gated_kernel, dim3(static_cast<unsigned>(ceil_div(items, 256))), dim3(256), 0, st, partial, kq,
+                     32 * nt, Mi, static_cast<int>(F), static_cast<bf16_t*>(y), ldy);
+  DLLAVA_CHECK_LAUNCH("few_finish_gated_kernel");
   return DLLAVA_OK;
 }

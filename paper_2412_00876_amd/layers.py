@@ -121,12 +121,13 @@ class DecoderStack:
         # decode: one row per sequence
         self.xd, self.hd = z(B, d), z(B, d)
         self.qd, self.kd, self.vd, self.od = z(B, H, Dh), z(B, H, Dh), z(B, H, Dh), z(B, H, Dh)
-        self.gd, self.fd = z(B, d_ff), z(B, d_ff)
+        self.fd = z(B, d_ff)
         self.ones = torch.ones(B, dtype=torch.uint8, device=device)
         self.logits_d = torch.zeros((B, 2), dtype=torch.float32, device=device)
         self.keep_d = torch.zeros(B, dtype=torch.uint8, device=device)
         zb = lambda n: torch.zeros(n, dtype=torch.uint8, device=device)
-        self.ws_few = zb(max(P.dllava_linear_few_workspace(n, k) for n, k in ((H * Dh, d), (d, H * Dh), (d_ff, d), (d, d_ff))))
+        self.ws_few = zb(max(P.dllava_linear_few_workspace(n, k)
+                             for n, k in ((3 * H * Dh, d), (d, H * Dh), (2 * d_ff, d), (d, d_ff))))
         self.ws_decode = zb(P.dllava_decode_workspace(B, H, Dh, self.caches[0].max_pages_per_seq))
 
     def decode_step(self, x_new, pos, theta: float, predictor):
@@ -142,11 +143,8 @@ class DecoderStack:
             if i == self.l:
                 predictor(X, self.logits_d)
             P.dllava_rms_norm(X, d, B, d, Wl["g1"], self.RMS_EPS, self.hd, d, BF)
-            few(self.hd, d, Wl["Wq"], H * Dh, 0, None, self.qd)
-            few(self.hd, d, Wl["Wk"], H * Dh, 0, None, self.kd)
-            few(self.hd, d, Wl["Wv"], H * Dh, 0, None, self.vd)
-            P.dllava_rope(self.qd, pos, B, H, Dh, self.ROPE_BASE, BF)
-            P.dllava_rope(self.kd, pos, B, H, Dh, self.ROPE_BASE, BF)
+            P.dllava_qkv_few(self.hd, d, B, d, Wl["Wq"], Wl["Wk"], Wl["Wv"], H, Dh, pos, self.ROPE_BASE, self.qd, self.kd,
+                             self.vd, BF, self.ws_few)
             if i < self.l:
                 P.dllava_decode_attn_append(self.qd, self.kd, self.vd, B, None, 0.0, self.ones, self.caches[i], Dh ** -0.5,
                                             self.od, None, self.err, self.ws_decode)
@@ -155,8 +153,7 @@ class DecoderStack:
                                             Dh ** -0.5, self.od, self.keep_d, self.err, self.ws_decode)
             few(self.od, H * Dh, Wl["Wo"], d, 0, X, X)
             P.dllava_rms_norm(X, d, B, d, Wl["g2"], self.RMS_EPS, self.hd, d, BF)
-            few(self.hd, d, Wl["Wg"], ff, 0, None, self.gd)
-            few(self.hd, d, Wl["Wu"], ff, 2, self.gd, self.fd)
+            P.dllava_gated_few(self.hd, d, B, d, Wl["Wg"], Wl["Wu"], ff, self.fd, ff, BF, self.ws_few)
             few(self.fd, ff, Wl["Wd"], d, 0, X, X)
         return X
 

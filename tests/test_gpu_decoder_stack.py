@@ -201,3 +201,43 @@ def test_decode_steps_through_the_stack():
     assert int(S.err.item()) == 0
     assert list(caches[0].cache_len) == list(n0 + T)                                 # a layer before l keeps every token
     assert list(caches[2].cache_len) != list(np.diff(off) + T)                       # later layers dropped some
+
+
+@pytest.mark.parametrize("M,d,H,Dh", [(16, 4096, 32, 128), (5, 256, 2, 64), (40, 320, 3, 32)])
+def test_fused_qkv_of_a_decode_step(M, d, H, Dh):
+    h = _H()
+    seed = 4000 + M + d
+    x = W.store(rng.normal(seed, "x", (M, d)), "bf16")
+    Ws = [W.store(W._normal_big(seed, n, (H * Dh, d)) / np.sqrt(d), "bf16") for n in "qkv"]
+    pos = (rng.uniform01(seed, "p", 0, M) * 3000).astype(np.int32)
+    xs = R.widen(x, "bf16")
+    q, k, v = ((xs @ R.widen(Wm, "bf16").T).reshape(M, H, Dh) for Wm in Ws)
+    q, k = R.rope_rotate(q, pos, DR.ROPE_BASE), R.rope_rotate(k, pos, DR.ROPE_BASE)
+    out = [torch.zeros((M, H, Dh), dtype=torch.bfloat16, device=h.DEV) for _ in range(3)]
+    ws = torch.full((P.dllava_decode_proj_workspace(3 * H * Dh, d),), 0x21, dtype=torch.uint8, device=h.DEV)
+    P.dllava_qkv_few(h.to_dev(x, "bf16"), d, M, d, *(h.to_dev(Wm, "bf16") for Wm in Ws), H, Dh, torch.from_numpy(pos).to(h.DEV),
+                     DR.ROPE_BASE, *out, P.BF16, ws)
+    for got, ref, name in zip(out, (q, k, v), "qkv"):
+        _assert_same_rounding(h.bits(got), ref, f"fused {name}")
+
+
+@pytest.mark.parametrize("M,d,F", [(16, 4096, 11008), (3, 128, 96)])
+def test_fused_gated_layer_of_a_decode_step(M, d, F):
+    h = _H()
+    seed = 5000 + M + d
+    x = W.store(rng.normal(seed, "x", (M, d)), "bf16")
+    Wg = W.store(W._normal_big(seed, "g", (F, d)) / np.sqrt(d) * 2, "bf16")
+    Wu = W.store(W._normal_big(seed, "u", (F, d)) / np.sqrt(d), "bf16")
+    xs = R.widen(x, "bf16")
+    gate = R.widen(R.narrow(xs @ R.widen(Wg, "bf16").T, "bf16"), "bf16")          # the gate as if it had been stored
+    ref = DR.silu(gate) * (xs @ R.widen(Wu, "bf16").T)
+    y = torch.zeros((M, F), dtype=torch.bfloat16, device=h.DEV)
+    ws = torch.full((P.dllava_decode_proj_workspace(2 * F, d),), 0x21, dtype=torch.uint8, device=h.DEV)
+    P.dllava_gated_few(h.to_dev(x, "bf16"), d, M, d, h.to_dev(Wg, "bf16"), h.to_dev(Wu, "bf16"), F, y, F, P.BF16, ws)
+    # where the GPU's float32 gate sum rounds to the other neighbour, the product moves by the gate's step times the
+    # slope of SiLU: allowed as a one-step difference of the gate, counted with the other one-step differences
+    got = R.widen(h.bits(y), "bf16")
+    err = np.abs(got - ref)
+    up = np.abs(xs @ R.widen(Wu, "bf16").T)
+    assert (err <= 2.0 ** -7 * np.abs(ref) + 1.2 * 2.0 ** -8 * np.abs(gate) * up + 1e-6).all()
+    assert (h.bits(y) != R.narrow(ref, "bf16")).mean() <= 0.03
