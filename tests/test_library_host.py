@@ -277,3 +277,25 @@ def test_few_rows_linear_and_rope_validate_on_the_host(lib):
     _expect(lib, EINVAL, L.dllava_rope, fake, fake, 4, 2, 64, 0.0, 1, None)
     _expect(lib, ENULL, L.dllava_rope, fake, None, 4, 2, 64, 10000.0, 1, None)
     _expect(lib, EDTYPE, L.dllava_rope, fake, fake, 4, 2, 64, 10000.0, 0, None)
+
+
+def test_fused_decode_projections_validate_on_the_host(lib):
+    L = lib.lib()
+    EINVAL, ENULL, ESHAPE, EDTYPE, EWORKSPACE = -1, -2, -3, -4, -6
+    fake = C.c_void_p(0x1000)
+    big = 1 << 28
+    qkv = lambda M=4, d=128, H=2, Dh=64, pos=fake, base=10000.0, dtype=1, ws=fake, wsb=big: (
+        fake, d, M, d, fake, fake, fake, H, Dh, pos, base, fake, fake, fake, dtype, ws, wsb, None)
+    _expect(lib, ESHAPE, L.dllava_qkv_few, *qkv(M=65))
+    _expect(lib, ESHAPE, L.dllava_qkv_few, *qkv(d=100))
+    _expect(lib, ESHAPE, L.dllava_qkv_few, *qkv(Dh=12))
+    _expect(lib, EINVAL, L.dllava_qkv_few, *qkv(base=0.0))
+    _expect(lib, ENULL, L.dllava_qkv_few, *qkv(pos=None))
+    _expect(lib, EDTYPE, L.dllava_qkv_few, *qkv(dtype=0))
+    _expect(lib, EWORKSPACE, L.dllava_qkv_few, *qkv(ws=None, wsb=0))
+    gated = lambda M=4, d=128, F=96, dtype=1, ws=fake, wsb=big: (fake, d, M, d, fake, fake, F, fake, F, dtype, ws, wsb, None)
+    _expect(lib, ESHAPE, L.dllava_gated_few, *gated(F=40))
+    _expect(lib, ESHAPE, L.dllava_gated_few, *gated(M=100))
+    _expect(lib, EDTYPE, L.dllava_gated_few, *gated(dtype=0))
+    _expect(lib, EWORKSPACE, L.dllava_gated_few, *gated(wsb=32))
+    assert lib.dllava_decode_proj_workspace(3 * 4096, 4096) == lib.dllava_linear_few_workspace(3 * 4096, 4096)
