@@ -534,7 +534,7 @@ def main():
                                path.ws_score_dec)
 
             res, res_dec, kv_dec = {}, {}, {}
-            Td = 32                                            # decode steps through the stack, right after the prefill
+            Td = min(32, T)                                    # decode steps through the stack, right after the prefill
             pos_t = torch.from_numpy((np.asarray(w.seq_len)[None, :] + np.arange(Td)[:, None]).astype(np.int32)).to("cuda:0")
             for name, l_red, rows_after in (("sparsified_after_layer_2", 2, path.rows_kept), ("dense", n_layers, w.sumN)):
                 S = DecoderStack(wts, l_red, B, H, Dh, w.d, d_ff, w.sumN, path.M_vis, max_seq_len=int(max(w.seq_len)),
