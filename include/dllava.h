@@ -401,8 +401,11 @@ int dllava_layer_norm(const void* z, int64_t M, const float* gamma, const float*
                          void* stream);
 /*
  * The same linear layer for FEW rows (M <= 64: one row per sequence of a decode step), where the weight matrix is
- * the traffic: W is read once, spread over the chip (blocks of 32 output features x a part of K), partial sums in
- * `workspace` (dllava_linear_few_workspace(N, K) bytes, 256-byte aligned, scratch) added in a fixed order.
+ * the traffic: W is read once, spread over the chip (blocks of 32 output features x a part of K), in ONE launch: the
+ * blocks of one feature group hand their sums over through `workspace` and the last to arrive adds them in a fixed
+ * order and applies bias, activation and residual.  workspace: dllava_linear_few_workspace(N, K) bytes, 256-byte
+ * aligned, ZERO-FILLED once before its first use (its first 4096 bytes are counters that every call returns to
+ * zero); one buffer of the largest size may serve all three few-rows entry points, calls ordered on one stream.
  * Arguments as dllava_linear; N % 32 == 0.
  * dllava_rope: rotary rotation IN PLACE of x [rows, H, Dh] at positions pos [rows] (int32), pairing and angles as in
  * dllava_qkv_project (feature i with i + Dh/2, angle pos * rope_base^(-2i/Dh)): q and k of the tokens of a decode step.
@@ -418,7 +421,8 @@ int dllava_rope(void* x, const int32_t* pos, int64_t rows, int32_t H, int32_t Dh
  *                   three matrices [H*Dh, d] read once in one launch.
  * dllava_gated_few: y [M, F] = (x Wu^T) * SiLU(x Wg^T), the gate rounded to dtype before the SiLU (as if it had been
  *                   stored), Wg and Wu [F, d] read once in one launch.  F % 32 == 0.
- * workspace: dllava_decode_proj_workspace(N_total, d) bytes with N_total = 3*H*Dh resp. 2*F, 256-byte aligned, scratch.
+ * workspace: dllava_decode_proj_workspace(N_total, d) bytes with N_total = 3*H*Dh resp. 2*F, as for dllava_linear_few.
+ * Dh % 32 == 0 (a block rotates 16 features of the lower half of a head with their partners), F % 32 == 0.
  */
 int dllava_qkv_few(const void* x, int64_t ldx, int64_t M, int64_t d, const void* Wq, const void* Wk, const void* Wv,
                    int32_t H, int32_t Dh, const int32_t* pos, float rope_base, void* q, void* k, void* v, int dtype,

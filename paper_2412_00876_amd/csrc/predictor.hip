@@ -269,57 +269,23 @@ __device__ __forceinline__ void want_now(const uint4& v) { asm volatile("" ::"v"
 // load, one row per lane, touches 32 lines for the same bytes and was measured 4x slower here) and turned into
 // matrix-core fragments through a wave-private LDS area in the swizzled row-major form of gemm_tile.h: chunk c of
 // row rr at chunk position c ^ ((rr / 2) % 8).
-// Block = feature group fg (32 output features) x part kq of the input width; N output features in all, n_fg groups,
-// KQ parts (each cut again over the block's 4 waves); partial sums [KQ][32*NT rows][N] float32.
-template <int NT>  // tiles of 32 rows
-__global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict__ X, int64_t ldx, int M, int K,
-                                                       const bf16_t* __restrict__ W, float* __restrict__ partial,
-                                                       int32_t B, const int32_t* __restrict__ seq_off,
-                                                       const int32_t* __restrict__ vis_start,
-                                                       const int32_t* __restrict__ vis_len, int n_fg, int KQ, int N,
-                                                       const bf16_t* __restrict__ W1, const bf16_t* __restrict__ W2,
-                                                       int fg_each) {
-  // up to three matrices of fg_each feature groups each, one after the other along the N output features
-  __shared__ float red[3][NT][16][kWave];
-  __shared__ __align__(16) bf16_t stage[4][(1 + NT) * 32 * 64];  // per wave: 32 weight rows and 32*NT input rows x 64 elements
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-  const int fg = blockIdx.x % n_fg, kq = blockIdx.x / n_fg;
+//
+// few_accumulate: one wave's share of a product on few rows.  wrow[j] / xrow[tt][j]: this lane's 16-byte column
+// (8 * (lane % 8) elements into a 128-byte line) of weight row 8j + lane/8 of the block's 32 features and of input
+// row 8j + lane/8 of row tile tt; lines lbeg .. lend-1 of the input width, LB lines of every row requested together.
+// Result: acc[tt] register i of lane = feature 8*(i/4) + 4*(lane/32) + i%4 of input row 32*tt + lane%32.
+template <int NT, int LB>
+__device__ __forceinline__ void few_accumulate(const bf16_t* const (&wrow)[4], const bf16_t* const (&xrow)[NT][4], int lbeg,
+                                               int lend, bf16_t* sw, int lane, f32x16 (&acc)[NT]) {
   const int r = lane & 31, g = lane >> 5;
   const int lr8 = lane >> 3, lc = lane & 7;
-  const int total = K / 64;                        // 128-byte lines per row
-  const int per = (total + 4 * KQ - 1) / (4 * KQ); // lines of one wave (4*KQ slices of the input width)
-  const int lbeg = (kq * 4 + w) * per;
-  const int lend = lbeg + per < total ? lbeg + per : total;
-  // this lane's rows: 8j + lane/8 of the 32 weight rows and of every 32-row input tile
-  const bf16_t* wrow[4];
-  const bf16_t* xrow[NT][4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int which = fg / fg_each;
-    const bf16_t* Wm = which == 0 ? W : (which == 1 ? W1 : W2);
-    wrow[j] = Wm + static_cast<int64_t>(32 * (fg % fg_each) + 8 * j + lr8) * K + 8 * lc;
-#pragma unroll
-    for (int tt = 0; tt < NT; ++tt) {
-      int64_t m = 32 * tt + 8 * j + lr8;
-      if (m >= M) m = M - 1;  // rows past M repeat the last one and are dropped later
-      int64_t sr = score_src_row(seq_off, vis_start, vis_len, B, m);
-      if (sr < 0) sr = 0;
-      xrow[tt][j] = X + sr * ldx + 8 * lc;
-    }
-  }
-  f32x16 acc[NT];
-#pragma unroll
-  for (int tt = 0; tt < NT; ++tt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[tt][i] = 0.f;
-  bf16_t* sw = stage[w];
   bf16_t* sx = sw + 32 * 64;
   const int st_off = lr8 * 64 + ((lc ^ ((lr8 >> 1) & 3)) * 8);  // row 8j + lane/8: ((8j + lr8) / 2) % 8 = 4*(j%2) + lr8/2
   const int fr_off = r * 64 + ((g ^ ((r >> 1) & 7)) * 8);       // row r, chunk 2*step + g
-  for (int l0 = lbeg; l0 < lend; l0 += 4) {
-    uint4 wf[4][4], xf[NT][4][4];  // [line of the batch][row group j]
+  for (int l0 = lbeg; l0 < lend; l0 += LB) {
+    uint4 wf[LB][4], xf[NT][LB][4];  // [line of the batch][row group j]
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {  // all loads of the batch first (past the end: the last line again, unused)
+    for (int c = 0; c < LB; ++c) {  // all loads of the batch first (past the end: the last line again, unused)
       const int line = l0 + c < lend ? l0 + c : lend - 1;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -329,7 +295,7 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
       }
     }
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
+    for (int c = 0; c < LB; ++c)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         want_now(wf[c][j]);
@@ -337,7 +303,7 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
         for (int tt = 0; tt < NT; ++tt) want_now(xf[tt][c][j]);
       }
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
+    for (int c = 0; c < LB; ++c)
       if (l0 + c < lend) {  // wave-uniform
         wave_lds_order();
 #pragma unroll
@@ -358,14 +324,64 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
         }
       }
   }
-  if (w > 0) {
+}
+
+// Leaves the wave's sums in its own staging area as float32 [(16*tt + i) * 64 + lane].
+template <int NT>
+__device__ __forceinline__ void few_leave_sums(const f32x16 (&acc)[NT], bf16_t* sw, int lane) {
+  static_assert(NT * 16 * kWave * sizeof(float) <= (1 + NT) * 32 * 64 * sizeof(bf16_t), "a wave's sums fit its own area");
+  wave_lds_order();  // the wave's last fragment reads come before its sums go to the same area
+  float* mine = reinterpret_cast<float*>(sw);
 #pragma unroll
-    for (int tt = 0; tt < NT; ++tt)
+  for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) red[w - 1][tt][i][lane] = acc[tt][i];
+    for (int i = 0; i < 16; ++i) mine[(tt * 16 + i) * kWave + lane] = acc[tt][i];
+}
+
+// First layer of the output-text predictor: block = feature group fg (32 of the 512 features) x part kq of the input
+// width (each cut again over the block's 4 waves); partial sums [KQ][32*NT rows][N] float32 for small_head_kernel.
+template <int NT>  // tiles of 32 rows
+__global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict__ X, int64_t ldx, int M, int K,
+                                                       const bf16_t* __restrict__ W, float* __restrict__ partial,
+                                                       int32_t B, const int32_t* __restrict__ seq_off,
+                                                       const int32_t* __restrict__ vis_start,
+                                                       const int32_t* __restrict__ vis_len, int n_fg, int KQ, int N) {
+  // per wave: 32 weight rows and 32*NT input rows x 64 elements; after its last line a wave's area carries its sums
+  __shared__ __align__(16) bf16_t stage[4][(1 + NT) * 32 * 64];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+  const int fg = blockIdx.x % n_fg, kq = blockIdx.x / n_fg;
+  const int r = lane & 31, g = lane >> 5;
+  const int lr8 = lane >> 3, lc = lane & 7;
+  const int total = K / 64;                        // 128-byte lines per row
+  const int per = (total + 4 * KQ - 1) / (4 * KQ); // lines of one wave (4*KQ slices of the input width)
+  const int lbeg = (kq * 4 + w) * per;
+  const int lend = lbeg + per < total ? lbeg + per : total;
+  const bf16_t* wrow[4];
+  const bf16_t* xrow[NT][4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    wrow[j] = W + static_cast<int64_t>(32 * fg + 8 * j + lr8) * K + 8 * lc;
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt) {
+      int64_t m = 32 * tt + 8 * j + lr8;
+      if (m >= M) m = M - 1;  // rows past M repeat the last one and are dropped later
+      int64_t sr = score_src_row(seq_off, vis_start, vis_len, B, m);
+      if (sr < 0) sr = 0;
+      xrow[tt][j] = X + sr * ldx + 8 * lc;
+    }
   }
+  f32x16 acc[NT];
+#pragma unroll
+  for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[tt][i] = 0.f;
+  few_accumulate<NT, 4>(wrow, xrow, lbeg, lend, stage[w], lane, acc);
+  if (w > 0) few_leave_sums<NT>(acc, stage[w], lane);
   __syncthreads();
   if (w != 0) return;
+  const float* red1 = reinterpret_cast<const float*>(stage[1]);
+  const float* red2 = reinterpret_cast<const float*>(stage[2]);
+  const float* red3 = reinterpret_cast<const float*>(stage[3]);
   // lane: row 32*tt + r; register i: feature 32*fg + 8*(i/4) + 4*g + i%4
 #pragma unroll
   for (int tt = 0; tt < NT; ++tt)
@@ -375,12 +391,220 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
       float* pv = &v.x;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int i = 4 * q4 + e;
-        pv[e] = ((acc[tt][i] + red[0][tt][i][lane]) + red[1][tt][i][lane]) + red[2][tt][i][lane];
+        const int i = 4 * q4 + e, o = (tt * 16 + i) * kWave + lane;
+        pv[e] = ((acc[tt][i] + red1[o]) + red2[o]) + red3[o];
       }
-      *reinterpret_cast<float4*>(partial + (static_cast<int64_t>(kq * (32 * NT) + 32 * tt + r)) * N + 32 * fg +
-                                 8 * q4 + 4 * g) = v;
+      if (32 * tt + r < M)  // rows past M were copies of the last one
+        *reinterpret_cast<float4*>(partial + (static_cast<int64_t>(kq * (32 * NT) + 32 * tt + r)) * N + 32 * fg +
+                                   8 * q4 + 4 * g) = v;
     }
+}
+
+// ---- a linear layer of the decoder on few rows (one row per sequence of a decode step), whole in one launch --------
+// The weights are the traffic (the rows are few): block = 32 output features x part kq of the input width, cut again
+// over the block's 4 waves, every weight byte read once.  The four waves' sums meet in LDS; with KQ > 1 the blocks
+// of one feature group hand their sums over through the workspace and a device-scope counter, and the last one to
+// arrive adds them in part order (fixed order: bit-reproducible), so the epilogue runs in the same launch:
+//   kFewPlain  y = act(x W^T + bias) (+ residual | * SiLU(gate rows));
+//   kFewQkv    [q | k | v] = x [Wq | Wk | Wv]^T with the rotary rotation of q and k: a q/k block takes 16 features of
+//              the lower half of a head and their 16 partners of the upper half, so a pair sits in one thread;
+//   kFewGated  y = (x Wu^T) * SiLU(x Wg^T): a block takes 16 gate features and the same 16 up features.
+// In all three a thread of the epilogue owns block-local features 8*q4 + 4*g + e ("lo") and 16 + the same ("hi"),
+// e = 0..3, of one row.
+enum { kFewPlain = 0, kFewQkv = 1, kFewGated = 2 };
+constexpr int kFewBatch = 2;     // 128-byte lines per row in flight per wave (2: 101 registers; 4 measured 7 % slower)
+constexpr int kFewBlocks = 384;  // blocks aimed at (more measured slower: the launch is bound by its ramp and memory)
+constexpr size_t kFewCounterBytes = 4096;
+
+struct FewEpi {
+  float* partial;     // [KQ][32*NT][32 * n_fg] block-local feature order
+  int32_t* counters;  // one per feature group, zero between launches
+  const float* bias;  // plain
+  int act;
+  const bf16_t* R;
+  bf16_t* Y;          // plain, gated
+  int64_t ldy;
+  int H, Dh;          // qkv
+  const int32_t* pos;
+  double rope_ratio;  // base^(-2/Dh)
+  bf16_t *q, *k, *v;
+};
+
+template <int NT, int EPI>
+__global__ __launch_bounds__(256) void few_fused_kernel(const bf16_t* __restrict__ X, int64_t ldx, int M, int K,
+                                                        const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
+                                                        const bf16_t* __restrict__ W2, int n_fg, int KQ, int fg_each,
+                                                        FewEpi ep) {
+  __shared__ __align__(16) bf16_t stage[4][(1 + NT) * 32 * 64];
+  __shared__ int sm_last;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+  const int fg = blockIdx.x % n_fg, kq = blockIdx.x / n_fg;
+  const int lr8 = lane >> 3, lc = lane & 7;
+  const int total = K / 64;
+  const int per = (total + 4 * KQ - 1) / (4 * KQ);
+  const int lbeg = (kq * 4 + w) * per;
+  const int lend = lbeg + per < total ? lbeg + per : total;
+  // which matrix and which of its rows the block's 32 features are
+  const int which = EPI == kFewQkv ? fg / fg_each : 0, lf = EPI == kFewQkv ? fg % fg_each : fg;
+  const int half = ep.Dh / 2, per_head = EPI == kFewQkv ? ep.Dh / 32 : 1;
+  const int head = lf / per_head, t16 = lf % per_head;
+  const bf16_t* wrow[4];
+  const bf16_t* xrow[NT][4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int f = 8 * j + lr8;
+    const bf16_t* Wm = W0;
+    int64_t row = 32 * static_cast<int64_t>(fg) + f;
+    if (EPI == kFewQkv) {
+      Wm = which == 0 ? W0 : (which == 1 ? W1 : W2);
+      row = which < 2 ? static_cast<int64_t>(head) * ep.Dh + 16 * t16 + (f & 15) + (f >> 4) * half
+                      : 32 * static_cast<int64_t>(lf) + f;
+    } else if (EPI == kFewGated) {
+      Wm = f < 16 ? W0 : W1;
+      row = 16 * static_cast<int64_t>(fg) + (f & 15);
+    }
+    wrow[j] = Wm + row * K + 8 * lc;
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt) {
+      int m = 32 * tt + f;
+      if (m >= M) m = M - 1;  // rows past M repeat the last one and are dropped later
+      xrow[tt][j] = X + static_cast<int64_t>(m) * ldx + 8 * lc;
+    }
+  }
+  f32x16 acc[NT];
+#pragma unroll
+  for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[tt][i] = 0.f;
+  few_accumulate<NT, kFewBatch>(wrow, xrow, lbeg, lend, stage[w], lane, acc);
+  few_leave_sums<NT>(acc, stage[w], lane);
+  __syncthreads();
+
+  // epilogue thread: row m, block-local features lo = 8*q4 + 4*g + e and hi = 16 + lo
+  const bool has = tid < 128 * NT;
+  const int r = tid & 31, g = (tid >> 5) & 1, q4 = (tid >> 6) & 1, tt = (tid >> 7) & (NT - 1);
+  const int m = 32 * tt + r, f0 = 8 * q4 + 4 * g;
+  const bool live = has && m < M;
+  float lo[4], hi[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int o = (tt * 16 + 4 * q4 + e) * kWave + g * 32 + r;
+    const float* s0 = reinterpret_cast<const float*>(stage[0]);
+    const float* s1 = reinterpret_cast<const float*>(stage[1]);
+    const float* s2 = reinterpret_cast<const float*>(stage[2]);
+    const float* s3 = reinterpret_cast<const float*>(stage[3]);
+    lo[e] = ((s0[o] + s1[o]) + s2[o]) + s3[o];
+    hi[e] = ((s0[o + 8 * kWave] + s1[o + 8 * kWave]) + s2[o + 8 * kWave]) + s3[o + 8 * kWave];
+  }
+  if (KQ > 1) {  // uniform over the launch
+    const int64_t cols = 32 * static_cast<int64_t>(n_fg);
+    float* mine = ep.partial + (static_cast<int64_t>(kq) * (32 * NT) + m) * cols + 32 * fg + f0;
+    if (live) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        st_agent(mine + e, lo[e]);
+        st_agent(mine + 16 + e, hi[e]);
+      }
+    }
+    block_publish();
+    if (tid == 0) sm_last = (add_agent(&ep.counters[fg], 1) == KQ - 1);
+    __syncthreads();
+    if (!sm_last) return;
+    if (live) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) lo[e] = hi[e] = 0.f;
+      for (int p = 0; p < KQ; ++p) {
+        const float* src = ep.partial + (static_cast<int64_t>(p) * (32 * NT) + m) * cols + 32 * fg + f0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          lo[e] += ld_agent(src + e);
+          hi[e] += ld_agent(src + 16 + e);
+        }
+      }
+    }
+    if (tid == 0) zero_agent(&ep.counters[fg]);
+  }
+  if (!live) return;
+
+  if (EPI == kFewPlain) {
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      float* v = hf ? hi : lo;
+      const int64_t f = 32 * static_cast<int64_t>(fg) + 16 * hf + f0;
+      if (ep.bias) {
+        const float4 bb = *reinterpret_cast<const float4*>(ep.bias + f);
+        v[0] += bb.x; v[1] += bb.y; v[2] += bb.z; v[3] += bb.w;
+      }
+      if (ep.act == 1) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = gelu_erf_fast(v[e]);
+      }
+      if (ep.R) {
+        const uint2 rr = *reinterpret_cast<const uint2*>(ep.R + m * ep.ldy + f);
+        const float r0 = bf16lo_to_f32(rr.x), r1 = bf16hi_to_f32(rr.x), r2 = bf16lo_to_f32(rr.y), r3 = bf16hi_to_f32(rr.y);
+        if (ep.act == 2) {
+          v[0] *= silu_fast(r0); v[1] *= silu_fast(r1); v[2] *= silu_fast(r2); v[3] *= silu_fast(r3);
+        } else {
+          v[0] += r0; v[1] += r1; v[2] += r2; v[3] += r3;
+        }
+      }
+      uint2 o;
+      o.x = pack_bf16x2(v[0], v[1]);
+      o.y = pack_bf16x2(v[2], v[3]);
+      *reinterpret_cast<uint2*>(ep.Y + m * ep.ldy + f) = o;
+    }
+  } else if (EPI == kFewQkv) {
+    const int64_t HD = static_cast<int64_t>(ep.H) * ep.Dh;
+    bf16_t* out = (which == 0 ? ep.q : (which == 1 ? ep.k : ep.v)) + m * HD;
+    int64_t at_lo, at_hi;
+    if (which < 2) {  // uniform over the block
+      const int i4 = 16 * t16 + f0;  // index into the lower half of the head
+      // angle of pair i: pos * ratio^i with ratio = base^(-2/Dh), in float64 and in turns; only its fraction
+      // goes to the float32 sine and cosine (absolute error about 1e-6, far below the step of the storage type)
+      double freq = 1.0, sq = ep.rope_ratio;
+      for (int n = i4; n > 0; n >>= 1, sq *= sq)
+        if (n & 1) freq *= sq;
+      const double turns0 = static_cast<double>(ep.pos[m]) * 0.15915494309189535;  // pos / (2 pi)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        double tn = turns0 * freq;
+        tn -= rint(tn);
+        const float cs = __builtin_amdgcn_cosf(static_cast<float>(tn)), sn = __builtin_amdgcn_sinf(static_cast<float>(tn));
+        const float a = lo[e], b = hi[e];
+        lo[e] = a * cs - b * sn;
+        hi[e] = b * cs + a * sn;
+        freq *= ep.rope_ratio;
+      }
+      at_lo = static_cast<int64_t>(head) * ep.Dh + i4;
+      at_hi = at_lo + half;
+    } else {
+      at_lo = 32 * static_cast<int64_t>(lf) + f0;
+      at_hi = at_lo + 16;
+    }
+    uint2 w0, w1;
+    w0.x = pack_bf16x2(lo[0], lo[1]); w0.y = pack_bf16x2(lo[2], lo[3]);
+    w1.x = pack_bf16x2(hi[0], hi[1]); w1.y = pack_bf16x2(hi[2], hi[3]);
+    *reinterpret_cast<uint2*>(out + at_lo) = w0;
+    *reinterpret_cast<uint2*>(out + at_hi) = w1;
+  } else {  // gated: lo = gate (rounded to the storage type first, as if stored), hi = up
+    float gte[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) gte[e] = bf16_to_f32(f32_to_bf16(lo[e]));
+    uint2 o;
+    o.x = pack_bf16x2(hi[0] * silu_fast(gte[0]), hi[1] * silu_fast(gte[1]));
+    o.y = pack_bf16x2(hi[2] * silu_fast(gte[2]), hi[3] * silu_fast(gte[3]));
+    *reinterpret_cast<uint2*>(ep.Y + m * ep.ldy + 16 * static_cast<int64_t>(fg) + f0) = o;
+  }
+}
+
+template <int EPI>
+void launch_few_fused(int nt, hipStream_t st, const bf16_t* X, int64_t ldx, int M, int K, const bf16_t* W0, const bf16_t* W1,
+                      const bf16_t* W2, int n_fg, int KQ, int fg_each, const FewEpi& ep) {
+  const dim3 grid(static_cast<unsigned>(n_fg) * static_cast<unsigned>(KQ)), block(256);
+  if (nt == 1)
+    hipLaunchKernelGGL((few_fused_kernel<1, EPI>), grid, block, 0, st, X, ldx, M, K, W0, W1, W2, n_fg, KQ, fg_each, ep);
+  else
+    hipLaunchKernelGGL((few_fused_kernel<2, EPI>), grid, block, 0, st, X, ldx, M, K, W0, W1, W2, n_fg, KQ, fg_each, ep);
 }
 
 __global__ __launch_bounds__(256) void small_head_kernel(const float* __restrict__ partial, int rows_pad, int M,
@@ -599,36 +823,51 @@ __global__ __launch_bounds__(256) void rms_norm_kernel(const bf16_t* __restrict_
   }
 }
 
-// Second half of a linear layer on few rows: sums the KQ partial results of small_in_kernel in a fixed order, adds
-// the bias, applies the activation and the residual (or the gate), rounds once.  Thread = 4 features of one row.
-__global__ __launch_bounds__(256) void few_finish_kernel(const float* __restrict__ partial, int KQ, int rows_pad, int M, int N,
-                                                         const float* __restrict__ bias, int act,
-                                                         const bf16_t* __restrict__ R, bf16_t* __restrict__ Y, int64_t ldy) {
-  const int64_t it = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  const int n4 = N / 4;
-  if (it >= static_cast<int64_t>(M) * n4) return;
-  const int m = static_cast<int>(it / n4), f = static_cast<int>(it % n4) * 4;
-  float4 sum = *reinterpret_cast<const float4*>(bias ? bias + f : kZeroWords);
-  for (int q = 0; q < KQ; ++q) {
-    const float4 pq = *reinterpret_cast<const float4*>(partial + (static_cast<int64_t>(q) * rows_pad + m) * N + f);
-    sum.x += pq.x; sum.y += pq.y; sum.z += pq.z; sum.w += pq.w;
+// The same on few rows (a decode step): one block per row, every load of the row and of the weights requested at
+// once, the four waves' sums of squares added in wave order.
+__global__ __launch_bounds__(256) void rms_norm_row_kernel(const bf16_t* __restrict__ X, int64_t ldx, bf16_t* __restrict__ Y,
+                                                           int64_t ldy, const float* __restrict__ wgt, int d, float eps) {
+  __shared__ float part[4];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+  const bf16_t* x = X + static_cast<int64_t>(blockIdx.x) * ldx;
+  constexpr int kP = kRmsMaxPieces * kWave / 256;  // 16-byte pieces per thread
+  uint4 raw[kP];
+  float4 g[kP][2];
+#pragma unroll
+  for (int c = 0; c < kP; ++c) {
+    const int col = (c * 256 + tid) * 8;
+    const bool in = col < d;
+    raw[c] = in ? *reinterpret_cast<const uint4*>(x + col) : uint4{0u, 0u, 0u, 0u};
+    g[c][0] = (in && wgt) ? *reinterpret_cast<const float4*>(wgt + col) : float4{1.f, 1.f, 1.f, 1.f};
+    g[c][1] = (in && wgt) ? *reinterpret_cast<const float4*>(wgt + col + 4) : float4{1.f, 1.f, 1.f, 1.f};
   }
-  if (act == 1) {
-    sum.x = gelu_erf_fast(sum.x); sum.y = gelu_erf_fast(sum.y); sum.z = gelu_erf_fast(sum.z); sum.w = gelu_erf_fast(sum.w);
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < kP; ++c) {
+    float v[8];
+    Elem<bf16_t>::unpack(raw[c], v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss = fmaf(v[e], v[e], ss);
   }
-  if (R) {
-    const uint2 rr = *reinterpret_cast<const uint2*>(R + m * ldy + f);
-    const float r0 = bf16lo_to_f32(rr.x), r1 = bf16hi_to_f32(rr.x), r2 = bf16lo_to_f32(rr.y), r3 = bf16hi_to_f32(rr.y);
-    if (act == 2) {
-      sum.x *= silu_fast(r0); sum.y *= silu_fast(r1); sum.z *= silu_fast(r2); sum.w *= silu_fast(r3);
-    } else {
-      sum.x += r0; sum.y += r1; sum.z += r2; sum.w += r3;
+  ss = wave_sum(ss);
+  if (lane == 0) part[w] = ss;
+  __syncthreads();
+  const float rs = 1.f / sqrtf((((part[0] + part[1]) + part[2]) + part[3]) / static_cast<float>(d) + eps);
+  bf16_t* y = Y + static_cast<int64_t>(blockIdx.x) * ldy;
+#pragma unroll
+  for (int c = 0; c < kP; ++c) {
+    const int col = (c * 256 + tid) * 8;
+    if (col < d) {
+      float v[8];
+      Elem<bf16_t>::unpack(raw[c], v);
+      uint4 o;
+      o.x = pack_bf16x2(v[0] * rs * g[c][0].x, v[1] * rs * g[c][0].y);
+      o.y = pack_bf16x2(v[2] * rs * g[c][0].z, v[3] * rs * g[c][0].w);
+      o.z = pack_bf16x2(v[4] * rs * g[c][1].x, v[5] * rs * g[c][1].y);
+      o.w = pack_bf16x2(v[6] * rs * g[c][1].z, v[7] * rs * g[c][1].w);
+      *reinterpret_cast<uint4*>(y + col) = o;
     }
   }
-  uint2 v;
-  v.x = pack_bf16x2(sum.x, sum.y);
-  v.y = pack_bf16x2(sum.z, sum.w);
-  *reinterpret_cast<uint2*>(Y + m * ldy + f) = v;
 }
 
 // Rotary rotation in place of rows x [rows, H, Dh] at positions pos[row] (half-split pairing: feature i with i + Dh/2,
@@ -647,68 +886,6 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t* __restrict__ x, const
   const float lo = bf16_to_f32(p[i]), hi = bf16_to_f32(p[i + half]);
   p[i] = f32_to_bf16(lo * cs - hi * sn);
   p[i + half] = f32_to_bf16(hi * cs + lo * sn);
-}
-
-// Finish of the fused q|k|v layer of a decode step: partial sums over [q | k | v] features (3 * H * Dh), rotary
-// rotation of q and k at pos[row] (pairs (i, i + Dh/2) of a head), one rounding.  Thread = 4 features of the lower
-// half of a head and their 4 partners of the upper half, of q, k or v of one row.
-__global__ __launch_bounds__(256) void few_finish_qkv_kernel(const float* __restrict__ partial, int KQ, int rows_pad, int M,
-                                                             int H, int Dh, const int32_t* __restrict__ pos,
-                                                             double log2_base, bf16_t* __restrict__ q,
-                                                             bf16_t* __restrict__ k, bf16_t* __restrict__ v) {
-  const int half = Dh / 2, per_head = half / 4, HD = H * Dh, N = 3 * HD;
-  const int64_t it = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  if (it >= static_cast<int64_t>(M) * 3 * H * per_head) return;
-  const int i4 = static_cast<int>(it % per_head) * 4;
-  const int head = static_cast<int>((it / per_head) % H);
-  const int which = static_cast<int>((it / (per_head * H)) % 3);
-  const int m = static_cast<int>(it / (static_cast<int64_t>(per_head) * H * 3));
-  const int f = which * HD + head * Dh + i4;
-  float lo[4] = {0.f, 0.f, 0.f, 0.f}, hi[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int p = 0; p < KQ; ++p) {
-    const float* row = partial + (static_cast<int64_t>(p) * rows_pad + m) * N + f;
-    const float4 a = *reinterpret_cast<const float4*>(row), b = *reinterpret_cast<const float4*>(row + half);
-    lo[0] += a.x; lo[1] += a.y; lo[2] += a.z; lo[3] += a.w;
-    hi[0] += b.x; hi[1] += b.y; hi[2] += b.z; hi[3] += b.w;
-  }
-  if (which < 2) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const double ang = static_cast<double>(pos[m]) * exp2(-2.0 * (i4 + e) / Dh * log2_base);
-      const float cs = static_cast<float>(cos(ang)), sn = static_cast<float>(sin(ang));
-      const float a = lo[e], b = hi[e];
-      lo[e] = a * cs - b * sn;
-      hi[e] = b * cs + a * sn;
-    }
-  }
-  bf16_t* out = (which == 0 ? q : (which == 1 ? k : v)) + static_cast<int64_t>(m) * HD + head * Dh + i4;
-  uint2 w0, w1;
-  w0.x = pack_bf16x2(lo[0], lo[1]); w0.y = pack_bf16x2(lo[2], lo[3]);
-  w1.x = pack_bf16x2(hi[0], hi[1]); w1.y = pack_bf16x2(hi[2], hi[3]);
-  *reinterpret_cast<uint2*>(out) = w0;
-  *reinterpret_cast<uint2*>(out + half) = w1;
-}
-
-// Finish of the fused gate|up layer: y = up * SiLU(gate), the gate rounded to the storage type first (as if stored).
-__global__ __launch_bounds__(256) void few_finish_gated_kernel(const float* __restrict__ partial, int KQ, int rows_pad, int M,
-                                                               int F, bf16_t* __restrict__ Y, int64_t ldy) {
-  const int64_t it = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  const int n4 = F / 4;
-  if (it >= static_cast<int64_t>(M) * n4) return;
-  const int m = static_cast<int>(it / n4), f = static_cast<int>(it % n4) * 4;
-  float4 gs = {0.f, 0.f, 0.f, 0.f}, us = {0.f, 0.f, 0.f, 0.f};
-  for (int p = 0; p < KQ; ++p) {
-    const float* row = partial + (static_cast<int64_t>(p) * rows_pad + m) * (2 * F) + f;
-    const float4 a = *reinterpret_cast<const float4*>(row), b = *reinterpret_cast<const float4*>(row + F);
-    gs.x += a.x; gs.y += a.y; gs.z += a.z; gs.w += a.w;
-    us.x += b.x; us.y += b.y; us.z += b.z; us.w += b.w;
-  }
-  const float g0 = bf16_to_f32(f32_to_bf16(gs.x)), g1 = bf16_to_f32(f32_to_bf16(gs.y));
-  const float g2 = bf16_to_f32(f32_to_bf16(gs.z)), g3 = bf16_to_f32(f32_to_bf16(gs.w));
-  uint2 o;
-  o.x = pack_bf16x2(us.x * silu_fast(g0), us.y * silu_fast(g1));
-  o.y = pack_bf16x2(us.z * silu_fast(g2), us.w * silu_fast(g3));
-  *reinterpret_cast<uint2*>(Y + m * ldy + f) = o;
 }
 
 struct Regions {
@@ -805,10 +982,10 @@ extern "C" int dllava_predict(const void* x, int64_t ldx, int64_t M, int32_t B, 
     const bf16_t* Wi = static_cast<const bf16_t*>(p->W_in);
     if (nt == 1)
       hipLaunchKernelGGL(small_in_kernel<1>, dim3(16 * kSmallSplit), dim3(256), 0, st, X, ldx, Mi, Ki, Wi, r.small, B,
-                         seq_off, vis_start, vis_len, 16, kSmallSplit, kPW, nullptr, nullptr, 16);
+                         seq_off, vis_start, vis_len, 16, kSmallSplit, kPW);
     else
       hipLaunchKernelGGL(small_in_kernel<2>, dim3(16 * kSmallSplit), dim3(256), 0, st, X, ldx, Mi, Ki, Wi, r.small, B,
-                         seq_off, vis_start, vis_len, 16, kSmallSplit, kPW, nullptr, nullptr, 16);
+                         seq_off, vis_start, vis_len, 16, kSmallSplit, kPW);
     DLLAVA_CHECK_LAUNCH("small_in_kernel");
     hipLaunchKernelGGL(small_head_kernel, dim3(nt), dim3(256), 0, st, r.small, 32 * nt, Mi, p->b_in,
                        static_cast<const bf16_t*>(p->W_h1), p->b_h1, static_cast<const bf16_t*>(p->W_h2), p->b_h2,
@@ -930,9 +1107,13 @@ extern "C" int dllava_rms_norm(const void* x, int64_t ldx, int64_t M, int64_t d,
   DLLAVA_REQUIRE(x && y, DLLAVA_ENULL, "rms_norm: x and y are required");
   DLLAVA_REQUIRE(aligned(x, 16) && aligned(y, 16) && aligned(weight, 16), DLLAVA_EINVAL,
                  "rms_norm: x, y, weight must be 16-byte aligned");
-  hipLaunchKernelGGL(rms_norm_kernel, dim3(static_cast<unsigned>(ceil_div(M, 4))), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), static_cast<const bf16_t*>(x), ldx, static_cast<bf16_t*>(y), ldy,
-                     weight, M, static_cast<int>(d), eps);
+  if (M <= 1024)  // too few rows to fill the chip one wave per row: one block per row
+    hipLaunchKernelGGL(rms_norm_row_kernel, dim3(static_cast<unsigned>(M)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const bf16_t*>(x), ldx, static_cast<bf16_t*>(y), ldy, weight, static_cast<int>(d), eps);
+  else
+    hipLaunchKernelGGL(rms_norm_kernel, dim3(static_cast<unsigned>(ceil_div(M, 4))), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const bf16_t*>(x), ldx, static_cast<bf16_t*>(y), ldy,
+                       weight, M, static_cast<int>(d), eps);
   DLLAVA_CHECK_LAUNCH("rms_norm_kernel");
   return DLLAVA_OK;
 }
@@ -940,18 +1121,27 @@ extern "C" int dllava_rms_norm(const void* x, int64_t ldx, int64_t M, int64_t d,
 // ---- linear layer on few rows (one row per sequence of a decode step) ----------------------------------------------
 
 namespace {
-int few_parts(int64_t N, int64_t K) {  // parts of the input width across blocks: about 384 blocks in all
+int few_parts(int64_t N, int64_t K) {  // parts of the input width across blocks: about kFewBlocks blocks in all
   const int64_t n_fg = N / 32, lines = K / 64;
-  int64_t kq = (384 + n_fg - 1) / n_fg;
+  int64_t kq = (kFewBlocks + n_fg - 1) / n_fg;
   if (kq > 8) kq = 8;
   if (kq * 4 > lines) kq = (lines + 3) / 4;
   return static_cast<int>(kq < 1 ? 1 : kq);
 }
+// counters, then the sums that the blocks of one feature group hand over (none when the input width is not cut)
+FewEpi few_epilogue(void* workspace) {
+  FewEpi ep = {};
+  ep.counters = static_cast<int32_t*>(workspace);
+  ep.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + kFewCounterBytes);
+  return ep;
+}
 }  // namespace
 
 extern "C" size_t dllava_linear_few_workspace(int64_t N, int64_t K) {
-  if (N <= 0 || K <= 0) return 256;
-  return round_up(static_cast<size_t>(few_parts(N, K)) * kSmallRows * static_cast<size_t>(N) * sizeof(float), 256);
+  if (N <= 0 || K <= 0) return kFewCounterBytes;
+  const int kq = few_parts(N, K);
+  const size_t sums = kq > 1 ? static_cast<size_t>(kq) * kSmallRows * static_cast<size_t>(N) * sizeof(float) : 0;
+  return kFewCounterBytes + round_up(sums, 256);
 }
 
 extern "C" int dllava_linear_few(const void* x, int64_t ldx, int64_t M, int64_t K, const void* W, const float* bias,
@@ -976,21 +1166,16 @@ extern "C" int dllava_linear_few(const void* x, int64_t ldx, int64_t M, int64_t 
                  "linear_few: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int kq = few_parts(N, K), n_fg = static_cast<int>(N / 32), nt = M <= 32 ? 1 : 2;
-  float* partial = static_cast<float*>(workspace);
   const bf16_t* X = static_cast<const bf16_t*>(x);
   const bf16_t* Wb = static_cast<const bf16_t*>(W);
-  const int Mi = static_cast<int>(M), Ki = static_cast<int>(K), Ni = static_cast<int>(N);
-  if (nt == 1)
-    hipLaunchKernelGGL(small_in_kernel<1>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, Wb, partial, 0, nullptr, nullptr,
-                       nullptr, n_fg, kq, Ni, nullptr, nullptr, n_fg);
-  else
-    hipLaunchKernelGGL(small_in_kernel<2>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, Wb, partial, 0, nullptr, nullptr,
-                       nullptr, n_fg, kq, Ni, nullptr, nullptr, n_fg);
-  DLLAVA_CHECK_LAUNCH("small_in_kernel");
-  const int64_t items = M * (N / 4);
-  hipLaunchKernelGGL(few_finish_kernel, dim3(static_cast<unsigned>(ceil_div(items, 256))), dim3(256), 0, st, partial, kq,
-                     32 * nt, Mi, Ni, bias, act, static_cast<const bf16_t*>(residual), static_cast<bf16_t*>(y), ldy);
-  DLLAVA_CHECK_LAUNCH("few_finish_kernel");
+  FewEpi ep = few_epilogue(workspace);
+  ep.bias = bias;
+  ep.act = act;
+  ep.R = static_cast<const bf16_t*>(residual);
+  ep.Y = static_cast<bf16_t*>(y);
+  ep.ldy = ldy;
+  launch_few_fused<kFewPlain>(nt, st, X, ldx, static_cast<int>(M), static_cast<int>(K), Wb, nullptr, nullptr, n_fg, kq, n_fg, ep);
+  DLLAVA_CHECK_LAUNCH("few_fused_kernel");
   return DLLAVA_OK;
 }
 
@@ -1022,8 +1207,7 @@ extern "C" int dllava_qkv_few(const void* x, int64_t ldx, int64_t M, int64_t d, 
   DLLAVA_REQUIRE(d > 0 && d % 64 == 0 && d <= 0x7fffffffLL && ldx >= d && ldx % 8 == 0, DLLAVA_ESHAPE,
                  "qkv_few: d must be a positive multiple of 64, ldx >= d a multiple of 8 (got %lld, %lld)", (long long)d,
                  (long long)ldx);
-  DLLAVA_REQUIRE(H > 0 && Dh > 0 && Dh % 8 == 0 && (static_cast<int64_t>(H) * Dh) % 32 == 0, DLLAVA_ESHAPE,
-                 "qkv_few: H = %d, Dh = %d (Dh %% 8 == 0, H * Dh %% 32 == 0)", H, Dh);
+  DLLAVA_REQUIRE(H > 0 && Dh > 0 && Dh % 32 == 0, DLLAVA_ESHAPE, "qkv_few: H = %d, Dh = %d (Dh %% 32 == 0)", H, Dh);
   DLLAVA_REQUIRE(rope_base > 0.f && rope_base < INFINITY, DLLAVA_EINVAL, "qkv_few: bad rope_base");
   if (M == 0) return DLLAVA_OK;
   DLLAVA_REQUIRE(x && Wq && Wk && Wv && pos && q && k && v, DLLAVA_ENULL, "qkv_few: x, Wq, Wk, Wv, pos, q, k, v are required");
@@ -1036,23 +1220,19 @@ extern "C" int dllava_qkv_few(const void* x, int64_t ldx, int64_t M, int64_t d, 
                  "qkv_few: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int kq = few_parts(N, d), n_fg = static_cast<int>(N / 32), nt = M <= 32 ? 1 : 2;
-  float* partial = static_cast<float*>(workspace);
   const bf16_t* X = static_cast<const bf16_t*>(x);
-  const int Mi = static_cast<int>(M), Ki = static_cast<int>(d), Ni = static_cast<int>(N), each = static_cast<int>(HD / 32);
-  if (nt == 1)
-    hipLaunchKernelGGL(small_in_kernel<1>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, static_cast<const bf16_t*>(Wq),
-                       partial, 0, nullptr, nullptr, nullptr, n_fg, kq, Ni, static_cast<const bf16_t*>(Wk),
-                       static_cast<const bf16_t*>(Wv), each);
-  else
-    hipLaunchKernelGGL(small_in_kernel<2>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, static_cast<const bf16_t*>(Wq),
-                       partial, 0, nullptr, nullptr, nullptr, n_fg, kq, Ni, static_cast<const bf16_t*>(Wk),
-                       static_cast<const bf16_t*>(Wv), each);
-  DLLAVA_CHECK_LAUNCH("small_in_kernel");
-  const int64_t items = M * 3 * H * (Dh / 8);
-  hipLaunchKernelGGL(few_finish_qkv_kernel, dim3(static_cast<unsigned>(ceil_div(items, 256))), dim3(256), 0, st, partial, kq,
-                     32 * nt, Mi, H, Dh, pos, log2(static_cast<double>(rope_base)), static_cast<bf16_t*>(q),
-                     static_cast<bf16_t*>(k), static_cast<bf16_t*>(v));
-  DLLAVA_CHECK_LAUNCH("few_finish_qkv_kernel");
+  FewEpi ep = few_epilogue(workspace);
+  ep.H = H;
+  ep.Dh = Dh;
+  ep.pos = pos;
+  ep.rope_ratio = pow(static_cast<double>(rope_base), -2.0 / Dh);
+  ep.q = static_cast<bf16_t*>(q);
+  ep.k = static_cast<bf16_t*>(k);
+  ep.v = static_cast<bf16_t*>(v);
+  launch_few_fused<kFewQkv>(nt, st, X, ldx, static_cast<int>(M), static_cast<int>(d), static_cast<const bf16_t*>(Wq),
+                            static_cast<const bf16_t*>(Wk), static_cast<const bf16_t*>(Wv), n_fg, kq,
+                            static_cast<int>(HD / 32), ep);
+  DLLAVA_CHECK_LAUNCH("few_fused_kernel");
   return DLLAVA_OK;
 }
 
@@ -1076,19 +1256,12 @@ extern "C" int dllava_gated_few(const void* x, int64_t ldx, int64_t M, int64_t d
                  "gated_few: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int kq = few_parts(N, d), n_fg = static_cast<int>(N / 32), nt = M <= 32 ? 1 : 2;
-  float* partial = static_cast<float*>(workspace);
   const bf16_t* X = static_cast<const bf16_t*>(x);
-  const int Mi = static_cast<int>(M), Ki = static_cast<int>(d), Ni = static_cast<int>(N), each = static_cast<int>(F / 32);
-  if (nt == 1)
-    hipLaunchKernelGGL(small_in_kernel<1>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, static_cast<const bf16_t*>(Wg),
-                       partial, 0, nullptr, nullptr, nullptr, n_fg, kq, Ni, static_cast<const bf16_t*>(Wu), nullptr, each);
-  else
-    hipLaunchKernelGGL(small_in_kernel<2>, dim3(n_fg * kq), dim3(256), 0, st, X, ldx, Mi, Ki, static_cast<const bf16_t*>(Wg),
-                       partial, 0, nullptr, nullptr, nullptr, n_fg, kq, Ni, static_cast<const bf16_t*>(Wu), nullptr, each);
-  DLLAVA_CHECK_LAUNCH("small_in_kernel");
-  const int64_t items = M * (F / 4);
-  hipLaunchKernelGGL(few_finish_gated_kernel, dim3(static_cast<unsigned>(ceil_div(items, 256))), dim3(256), 0, st, partial, kq,
-                     32 * nt, Mi, static_cast<int>(F), static_cast<bf16_t*>(y), ldy);
-  DLLAVA_CHECK_LAUNCH("few_finish_gated_kernel");
+  FewEpi ep = few_epilogue(workspace);
+  ep.Y = static_cast<bf16_t*>(y);
+  ep.ldy = ldy;
+  launch_few_fused<kFewGated>(nt, st, X, ldx, static_cast<int>(M), static_cast<int>(d), static_cast<const bf16_t*>(Wg),
+                              static_cast<const bf16_t*>(Wu), nullptr, n_fg, kq, n_fg, ep);
+  DLLAVA_CHECK_LAUNCH("few_fused_kernel");
   return DLLAVA_OK;
 }

@@ -20,7 +20,7 @@ def _H():
     return harness
 
 
-@pytest.mark.parametrize("M,d", [(50, 64), (33, 4096), (7, 5120), (9, 8192), (5, 520)])
+@pytest.mark.parametrize("M,d", [(50, 64), (33, 4096), (7, 5120), (9, 8192), (5, 520), (1500, 264), (1030, 8192)])
 def test_rms_norm_layer(M, d):
     h = _H()
     x = W.store(rng.normal(d, "x", (M, d)) * 2 + 0.3, "bf16")
@@ -123,10 +123,16 @@ def test_linear_layer_on_few_rows(M, K, N, act, res):
         rd = y
     elif res:
         rd = h.to_dev(r, "bf16")
-    ws = torch.full((P.dllava_linear_few_workspace(N, K),), 0x44, dtype=torch.uint8, device=h.DEV)
+    ws = _few_workspace(P.dllava_linear_few_workspace(N, K), 0x44)
     P.dllava_linear_few(h.to_dev(x, "bf16"), K, M, K, h.to_dev(Wm, "bf16"), torch.from_numpy(b).to(h.DEV), N, act, rd, y, N,
                         P.BF16, ws)
     _assert_same_rounding(h.bits(y), ref, f"linear on few rows {M}x{K}x{N}")
+    _counters_back_at_zero(ws)
+    if res != "inplace":    # the same workspace serves the next call: bit-identical result
+        y1 = torch.zeros_like(y)
+        P.dllava_linear_few(h.to_dev(x, "bf16"), K, M, K, h.to_dev(Wm, "bf16"), torch.from_numpy(b).to(h.DEV), N, act, rd, y1,
+                            N, P.BF16, ws)
+        assert torch.equal(y1.view(torch.int16), y.view(torch.int16))
     # the tile kernel computes the same layer: the two agree to the rounding of the output
     y2 = torch.zeros((M, N), dtype=torch.bfloat16, device=h.DEV)
     if res == "inplace":
@@ -134,6 +140,17 @@ def test_linear_layer_on_few_rows(M, K, N, act, res):
     P.dllava_linear(h.to_dev(x, "bf16"), K, M, K, h.to_dev(Wm, "bf16"), torch.from_numpy(b).to(h.DEV), N, act,
                     y2 if res == "inplace" else rd, y2, N, P.BF16)
     _assert_same_rounding(h.bits(y2), ref, "the tile kernel on the same rows")
+
+
+def _few_workspace(nbytes: int, fill: int):
+    """Workspace of a few-rows layer: zero-filled once where its counters live (the first 4096 bytes), junk elsewhere."""
+    ws = torch.full((nbytes,), fill, dtype=torch.uint8, device=_H().DEV)
+    ws[:4096] = 0
+    return ws
+
+
+def _counters_back_at_zero(ws):
+    assert int(ws[:4096].to(torch.int32).sum().item()) == 0, "the counters of the workspace return to zero"
 
 
 def test_rope_in_place():
@@ -214,14 +231,18 @@ def test_fused_qkv_of_a_decode_step(M, d, H, Dh):
     q, k, v = ((xs @ R.widen(Wm, "bf16").T).reshape(M, H, Dh) for Wm in Ws)
     q, k = R.rope_rotate(q, pos, DR.ROPE_BASE), R.rope_rotate(k, pos, DR.ROPE_BASE)
     out = [torch.zeros((M, H, Dh), dtype=torch.bfloat16, device=h.DEV) for _ in range(3)]
-    ws = torch.full((P.dllava_decode_proj_workspace(3 * H * Dh, d),), 0x21, dtype=torch.uint8, device=h.DEV)
-    P.dllava_qkv_few(h.to_dev(x, "bf16"), d, M, d, *(h.to_dev(Wm, "bf16") for Wm in Ws), H, Dh, torch.from_numpy(pos).to(h.DEV),
-                     DR.ROPE_BASE, *out, P.BF16, ws)
-    for got, ref, name in zip(out, (q, k, v), "qkv"):
-        _assert_same_rounding(h.bits(got), ref, f"fused {name}")
+    ws = _few_workspace(P.dllava_decode_proj_workspace(3 * H * Dh, d), 0x21)
+    for _ in range(2):      # the second call finds the workspace as the first one left it
+        for o in out:
+            o.zero_()
+        P.dllava_qkv_few(h.to_dev(x, "bf16"), d, M, d, *(h.to_dev(Wm, "bf16") for Wm in Ws), H, Dh,
+                         torch.from_numpy(pos).to(h.DEV), DR.ROPE_BASE, *out, P.BF16, ws)
+        for got, ref, name in zip(out, (q, k, v), "qkv"):
+            _assert_same_rounding(h.bits(got), ref, f"fused {name}")
+        _counters_back_at_zero(ws)
 
 
-@pytest.mark.parametrize("M,d,F", [(16, 4096, 11008), (3, 128, 96)])
+@pytest.mark.parametrize("M,d,F", [(16, 4096, 11008), (3, 128, 96), (37, 512, 64)])
 def test_fused_gated_layer_of_a_decode_step(M, d, F):
     h = _H()
     seed = 5000 + M + d
@@ -232,8 +253,9 @@ def test_fused_gated_layer_of_a_decode_step(M, d, F):
     gate = R.widen(R.narrow(xs @ R.widen(Wg, "bf16").T, "bf16"), "bf16")          # the gate as if it had been stored
     ref = DR.silu(gate) * (xs @ R.widen(Wu, "bf16").T)
     y = torch.zeros((M, F), dtype=torch.bfloat16, device=h.DEV)
-    ws = torch.full((P.dllava_decode_proj_workspace(2 * F, d),), 0x21, dtype=torch.uint8, device=h.DEV)
+    ws = _few_workspace(P.dllava_decode_proj_workspace(2 * F, d), 0x21)
     P.dllava_gated_few(h.to_dev(x, "bf16"), d, M, d, h.to_dev(Wg, "bf16"), h.to_dev(Wu, "bf16"), F, y, F, P.BF16, ws)
+    _counters_back_at_zero(ws)
     # where the GPU's float32 gate sum rounds to the other neighbour, the product moves by the gate's step times the
     # slope of SiLU: allowed as a one-step difference of the gate, counted with the other one-step differences
     got = R.widen(h.bits(y), "bf16")

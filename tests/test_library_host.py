@@ -289,6 +289,7 @@ def test_fused_decode_projections_validate_on_the_host(lib):
     _expect(lib, ESHAPE, L.dllava_qkv_few, *qkv(M=65))
     _expect(lib, ESHAPE, L.dllava_qkv_few, *qkv(d=100))
     _expect(lib, ESHAPE, L.dllava_qkv_few, *qkv(Dh=12))
+    _expect(lib, ESHAPE, L.dllava_qkv_few, *qkv(Dh=48))
     _expect(lib, EINVAL, L.dllava_qkv_few, *qkv(base=0.0))
     _expect(lib, ENULL, L.dllava_qkv_few, *qkv(pos=None))
     _expect(lib, EDTYPE, L.dllava_qkv_few, *qkv(dtype=0))
