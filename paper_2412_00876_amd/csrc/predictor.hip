@@ -274,7 +274,7 @@ __device__ __forceinline__ void want_now(const uint4& v) { asm volatile("" ::"v"
 // (8 * (lane % 8) elements into a 128-byte line) of weight row 8j + lane/8 of the block's 32 features and of input
 // row 8j + lane/8 of row tile tt; lines lbeg .. lend-1 of the input width, LB lines of every row requested together.
 // Result: acc[tt] register i of lane = feature 8*(i/4) + 4*(lane/32) + i%4 of input row 32*tt + lane%32.
-template <int NT, int LB>
+template <int NT, int LB, bool HALF = false>  // HALF: only weight rows 0..15 exist (features 16..31 of the result are junk)
 __device__ __forceinline__ void few_accumulate(const bf16_t* const (&wrow)[4], const bf16_t* const (&xrow)[NT][4], int lbeg,
                                                int lend, bf16_t* sw, int lane, f32x16 (&acc)[NT]) {
   const int r = lane & 31, g = lane >> 5;
@@ -283,13 +283,14 @@ __device__ __forceinline__ void few_accumulate(const bf16_t* const (&wrow)[4], c
   const int st_off = lr8 * 64 + ((lc ^ ((lr8 >> 1) & 3)) * 8);  // row 8j + lane/8: ((8j + lr8) / 2) % 8 = 4*(j%2) + lr8/2
   const int fr_off = r * 64 + ((g ^ ((r >> 1) & 7)) * 8);       // row r, chunk 2*step + g
   for (int l0 = lbeg; l0 < lend; l0 += LB) {
-    uint4 wf[LB][4], xf[NT][LB][4];  // [line of the batch][row group j]
+    constexpr int JW = HALF ? 2 : 4;
+    uint4 wf[LB][JW], xf[NT][LB][4];  // [line of the batch][row group j]
 #pragma unroll
     for (int c = 0; c < LB; ++c) {  // all loads of the batch first (past the end: the last line again, unused)
       const int line = l0 + c < lend ? l0 + c : lend - 1;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        wf[c][j] = *reinterpret_cast<const uint4*>(wrow[j] + 64 * line);
+        if (j < JW) wf[c][j] = *reinterpret_cast<const uint4*>(wrow[j] + 64 * line);
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) xf[tt][c][j] = *reinterpret_cast<const uint4*>(xrow[tt][j] + 64 * line);
       }
@@ -298,7 +299,7 @@ __device__ __forceinline__ void few_accumulate(const bf16_t* const (&wrow)[4], c
     for (int c = 0; c < LB; ++c)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        want_now(wf[c][j]);
+        if (j < JW) want_now(wf[c][j]);
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) want_now(xf[tt][c][j]);
       }
@@ -309,7 +310,7 @@ __device__ __forceinline__ void few_accumulate(const bf16_t* const (&wrow)[4], c
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int o = 8 * j * 64 + (st_off ^ ((j & 1) * 32));
-          *reinterpret_cast<uint4*>(sw + o) = wf[c][j];
+          if (j < JW) *reinterpret_cast<uint4*>(sw + o) = wf[c][j];
 #pragma unroll
           for (int tt = 0; tt < NT; ++tt) *reinterpret_cast<uint4*>(sx + tt * 32 * 64 + o) = xf[tt][c][j];
         }
@@ -411,7 +412,10 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
 //   kFewGated  y = (x Wu^T) * SiLU(x Wg^T): a block takes 16 gate features and the same 16 up features.
 // In all three a thread of the epilogue owns block-local features 8*q4 + 4*g + e ("lo") and 16 + the same ("hi"),
 // e = 0..3, of one row.
-enum { kFewPlain = 0, kFewQkv = 1, kFewGated = 2 };
+//   kFewPlainHalf  kFewPlain with 16 features per block and 8 waves along the input width: for a narrow output
+//              (N of a few thousand) there are then enough blocks without cutting the input width across blocks,
+//              whose hand-over costs about 5 us; the upper half of the matrix-core tile idles, which costs nothing here.
+enum { kFewPlain = 0, kFewQkv = 1, kFewGated = 2, kFewPlainHalf = 3 };
 constexpr int kFewBatch = 2;     // 128-byte lines per row in flight per wave (2: 101 registers; 4 measured 7 % slower)
 constexpr int kFewBlocks = 384;  // blocks aimed at (more measured slower: the launch is bound by its ramp and memory)
 constexpr size_t kFewCounterBytes = 4096;
@@ -431,18 +435,21 @@ struct FewEpi {
 };
 
 template <int NT, int EPI>
-__global__ __launch_bounds__(256) void few_fused_kernel(const bf16_t* __restrict__ X, int64_t ldx, int M, int K,
+__global__ __launch_bounds__(EPI == kFewPlainHalf ? 512 : 256) void few_fused_kernel(const bf16_t* __restrict__ X, int64_t ldx, int M, int K,
                                                         const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
                                                         const bf16_t* __restrict__ W2, int n_fg, int KQ, int fg_each,
                                                         FewEpi ep) {
-  __shared__ __align__(16) bf16_t stage[4][(1 + NT) * 32 * 64];
+  constexpr bool HALF = EPI == kFewPlainHalf;
+  constexpr int NW = HALF ? 8 : 4;   // waves of the block, each with its own part of the input width
+  constexpr int FB = HALF ? 16 : 32; // features of a block
+  __shared__ __align__(16) bf16_t stage[NW][(1 + NT) * 32 * 64];
   __shared__ int sm_last;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
   const int fg = blockIdx.x % n_fg, kq = blockIdx.x / n_fg;
   const int lr8 = lane >> 3, lc = lane & 7;
   const int total = K / 64;
-  const int per = (total + 4 * KQ - 1) / (4 * KQ);
-  const int lbeg = (kq * 4 + w) * per;
+  const int per = (total + NW * KQ - 1) / (NW * KQ);
+  const int lbeg = (kq * NW + w) * per;
   const int lend = lbeg + per < total ? lbeg + per : total;
   // which matrix and which of its rows the block's 32 features are
   const int which = EPI == kFewQkv ? fg / fg_each : 0, lf = EPI == kFewQkv ? fg % fg_each : fg;
@@ -455,7 +462,9 @@ __global__ __launch_bounds__(256) void few_fused_kernel(const bf16_t* __restrict
     const int f = 8 * j + lr8;
     const bf16_t* Wm = W0;
     int64_t row = 32 * static_cast<int64_t>(fg) + f;
-    if (EPI == kFewQkv) {
+    if (HALF) {
+      row = 16 * static_cast<int64_t>(fg) + (f & 15);
+    } else if (EPI == kFewQkv) {
       Wm = which == 0 ? W0 : (which == 1 ? W1 : W2);
       row = which < 2 ? static_cast<int64_t>(head) * ep.Dh + 16 * t16 + (f & 15) + (f >> 4) * half
                       : 32 * static_cast<int64_t>(lf) + f;
@@ -476,7 +485,7 @@ __global__ __launch_bounds__(256) void few_fused_kernel(const bf16_t* __restrict
   for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[tt][i] = 0.f;
-  few_accumulate<NT, kFewBatch>(wrow, xrow, lbeg, lend, stage[w], lane, acc);
+  few_accumulate<NT, kFewBatch, HALF>(wrow, xrow, lbeg, lend, stage[w], lane, acc);
   few_leave_sums<NT>(acc, stage[w], lane);
   __syncthreads();
 
@@ -489,21 +498,22 @@ __global__ __launch_bounds__(256) void few_fused_kernel(const bf16_t* __restrict
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int o = (tt * 16 + 4 * q4 + e) * kWave + g * 32 + r;
-    const float* s0 = reinterpret_cast<const float*>(stage[0]);
-    const float* s1 = reinterpret_cast<const float*>(stage[1]);
-    const float* s2 = reinterpret_cast<const float*>(stage[2]);
-    const float* s3 = reinterpret_cast<const float*>(stage[3]);
-    lo[e] = ((s0[o] + s1[o]) + s2[o]) + s3[o];
-    hi[e] = ((s0[o + 8 * kWave] + s1[o + 8 * kWave]) + s2[o + 8 * kWave]) + s3[o + 8 * kWave];
+    lo[e] = hi[e] = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) {  // wave order
+      const float* sums = reinterpret_cast<const float*>(stage[ww]);
+      lo[e] += sums[o];
+      if (!HALF) hi[e] += sums[o + 8 * kWave];
+    }
   }
   if (KQ > 1) {  // uniform over the launch
-    const int64_t cols = 32 * static_cast<int64_t>(n_fg);
-    float* mine = ep.partial + (static_cast<int64_t>(kq) * (32 * NT) + m) * cols + 32 * fg + f0;
+    const int64_t cols = FB * static_cast<int64_t>(n_fg);
+    float* mine = ep.partial + (static_cast<int64_t>(kq) * (32 * NT) + m) * cols + FB * fg + f0;
     if (live) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         st_agent(mine + e, lo[e]);
-        st_agent(mine + 16 + e, hi[e]);
+        if (!HALF) st_agent(mine + 16 + e, hi[e]);
       }
     }
     block_publish();
@@ -514,11 +524,11 @@ __global__ __launch_bounds__(256) void few_fused_kernel(const bf16_t* __restrict
 #pragma unroll
       for (int e = 0; e < 4; ++e) lo[e] = hi[e] = 0.f;
       for (int p = 0; p < KQ; ++p) {
-        const float* src = ep.partial + (static_cast<int64_t>(p) * (32 * NT) + m) * cols + 32 * fg + f0;
+        const float* src = ep.partial + (static_cast<int64_t>(p) * (32 * NT) + m) * cols + FB * fg + f0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           lo[e] += ld_agent(src + e);
-          hi[e] += ld_agent(src + 16 + e);
+          if (!HALF) hi[e] += ld_agent(src + 16 + e);
         }
       }
     }
@@ -526,11 +536,11 @@ __global__ __launch_bounds__(256) void few_fused_kernel(const bf16_t* __restrict
   }
   if (!live) return;
 
-  if (EPI == kFewPlain) {
+  if (EPI == kFewPlain || HALF) {
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
+    for (int hf = 0; hf < (HALF ? 1 : 2); ++hf) {
       float* v = hf ? hi : lo;
-      const int64_t f = 32 * static_cast<int64_t>(fg) + 16 * hf + f0;
+      const int64_t f = FB * static_cast<int64_t>(fg) + 16 * hf + f0;
       if (ep.bias) {
         const float4 bb = *reinterpret_cast<const float4*>(ep.bias + f);
         v[0] += bb.x; v[1] += bb.y; v[2] += bb.z; v[3] += bb.w;
@@ -600,7 +610,7 @@ __global__ __launch_bounds__(256) void few_fused_kernel(const bf16_t* __restrict
 template <int EPI>
 void launch_few_fused(int nt, hipStream_t st, const bf16_t* X, int64_t ldx, int M, int K, const bf16_t* W0, const bf16_t* W1,
                       const bf16_t* W2, int n_fg, int KQ, int fg_each, const FewEpi& ep) {
-  const dim3 grid(static_cast<unsigned>(n_fg) * static_cast<unsigned>(KQ)), block(256);
+  const dim3 grid(static_cast<unsigned>(n_fg) * static_cast<unsigned>(KQ)), block(EPI == kFewPlainHalf ? 512 : 256);
   if (nt == 1)
     hipLaunchKernelGGL((few_fused_kernel<1, EPI>), grid, block, 0, st, X, ldx, M, K, W0, W1, W2, n_fg, KQ, fg_each, ep);
   else
@@ -1121,12 +1131,28 @@ extern "C" int dllava_rms_norm(const void* x, int64_t ldx, int64_t M, int64_t d,
 // ---- linear layer on few rows (one row per sequence of a decode step) ----------------------------------------------
 
 namespace {
-int few_parts(int64_t N, int64_t K) {  // parts of the input width across blocks: about kFewBlocks blocks in all
-  const int64_t n_fg = N / 32, lines = K / 64;
-  int64_t kq = (kFewBlocks + n_fg - 1) / n_fg;
+// parts of the input width across blocks for n_groups feature groups, nw waves per block, about `aim` blocks in all
+int few_parts_of(int64_t n_groups, int64_t K, int nw, int aim) {
+  const int64_t lines = K / 64;
+  int64_t kq = (aim + n_groups - 1) / n_groups;
   if (kq > 8) kq = 8;
-  if (kq * 4 > lines) kq = (lines + 3) / 4;
+  if (kq * nw > lines) kq = (lines + nw - 1) / nw;
   return static_cast<int>(kq < 1 ? 1 : kq);
+}
+int few_parts(int64_t N, int64_t K) { return few_parts_of(N / 32, K, 4, kFewBlocks); }
+// A plain layer whose 32-feature groups are too few takes 16-feature groups with 8 waves each instead.
+struct FewPlan {
+  bool half;
+  int n_fg, kq;
+  int64_t cols;  // width of one row of handed-over sums
+};
+FewPlan few_plan_plain(int64_t N, int64_t K) {
+  FewPlan p;
+  p.half = few_parts(N, K) > 1;
+  p.n_fg = static_cast<int>(p.half ? N / 16 : N / 32);
+  p.kq = p.half ? few_parts_of(p.n_fg, K, 8, 256) : 1;
+  p.cols = N;
+  return p;
 }
 // counters, then the sums that the blocks of one feature group hand over (none when the input width is not cut)
 FewEpi few_epilogue(void* workspace) {
@@ -1139,8 +1165,8 @@ FewEpi few_epilogue(void* workspace) {
 
 extern "C" size_t dllava_linear_few_workspace(int64_t N, int64_t K) {
   if (N <= 0 || K <= 0) return kFewCounterBytes;
-  const int kq = few_parts(N, K);
-  const size_t sums = kq > 1 ? static_cast<size_t>(kq) * kSmallRows * static_cast<size_t>(N) * sizeof(float) : 0;
+  const FewPlan p = few_plan_plain(N, K);
+  const size_t sums = p.kq > 1 ? static_cast<size_t>(p.kq) * kSmallRows * static_cast<size_t>(p.cols) * sizeof(float) : 0;
   return kFewCounterBytes + round_up(sums, 256);
 }
 
@@ -1165,7 +1191,8 @@ extern "C" int dllava_linear_few(const void* x, int64_t ldx, int64_t M, int64_t 
   DLLAVA_REQUIRE(workspace && aligned(workspace, 256) && workspace_bytes >= need, DLLAVA_EWORKSPACE,
                  "linear_few: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int kq = few_parts(N, K), n_fg = static_cast<int>(N / 32), nt = M <= 32 ? 1 : 2;
+  const FewPlan plan = few_plan_plain(N, K);
+  const int nt = M <= 32 ? 1 : 2;
   const bf16_t* X = static_cast<const bf16_t*>(x);
   const bf16_t* Wb = static_cast<const bf16_t*>(W);
   FewEpi ep = few_epilogue(workspace);
@@ -1174,7 +1201,12 @@ extern "C" int dllava_linear_few(const void* x, int64_t ldx, int64_t M, int64_t 
   ep.R = static_cast<const bf16_t*>(residual);
   ep.Y = static_cast<bf16_t*>(y);
   ep.ldy = ldy;
-  launch_few_fused<kFewPlain>(nt, st, X, ldx, static_cast<int>(M), static_cast<int>(K), Wb, nullptr, nullptr, n_fg, kq, n_fg, ep);
+  if (plan.half)
+    launch_few_fused<kFewPlainHalf>(nt, st, X, ldx, static_cast<int>(M), static_cast<int>(K), Wb, nullptr, nullptr, plan.n_fg,
+                                    plan.kq, plan.n_fg, ep);
+  else
+    launch_few_fused<kFewPlain>(nt, st, X, ldx, static_cast<int>(M), static_cast<int>(K), Wb, nullptr, nullptr, plan.n_fg,
+                                plan.kq, plan.n_fg, ep);
   DLLAVA_CHECK_LAUNCH("few_fused_kernel");
   return DLLAVA_OK;
 }
@@ -1197,7 +1229,12 @@ extern "C" int dllava_rope(void* x, const int32_t* pos, int64_t rows, int32_t H,
 
 // ---- fused forms for a decode step: q|k|v with rotary rotation, gate|up with the gating ---------------------------
 
-extern "C" size_t dllava_decode_proj_workspace(int64_t N_total, int64_t K) { return dllava_linear_few_workspace(N_total, K); }
+extern "C" size_t dllava_decode_proj_workspace(int64_t N_total, int64_t K) {
+  if (N_total <= 0 || K <= 0) return kFewCounterBytes;
+  const int kq = few_parts(N_total, K);
+  const size_t sums = kq > 1 ? static_cast<size_t>(kq) * kSmallRows * static_cast<size_t>(N_total) * sizeof(float) : 0;
+  return kFewCounterBytes + round_up(sums, 256);
+}
 
 extern "C" int dllava_qkv_few(const void* x, int64_t ldx, int64_t M, int64_t d, const void* Wq, const void* Wk,
                               const void* Wv, int32_t H, int32_t Dh, const int32_t* pos, float rope_base, void* q, void* k,
@@ -1215,7 +1252,7 @@ extern "C" int dllava_qkv_few(const void* x, int64_t ldx, int64_t M, int64_t d, 
                      aligned(v, 16),
                  DLLAVA_EINVAL, "qkv_few: tensors must be 16-byte aligned");
   const int64_t HD = static_cast<int64_t>(H) * Dh, N = 3 * HD;
-  const size_t need = dllava_linear_few_workspace(N, d);
+  const size_t need = dllava_decode_proj_workspace(N, d);
   DLLAVA_REQUIRE(workspace && aligned(workspace, 256) && workspace_bytes >= need, DLLAVA_EWORKSPACE,
                  "qkv_few: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -1251,7 +1288,7 @@ extern "C" int dllava_gated_few(const void* x, int64_t ldx, int64_t M, int64_t d
   DLLAVA_REQUIRE(aligned(x, 16) && aligned(Wg, 16) && aligned(Wu, 16) && aligned(y, 16), DLLAVA_EINVAL,
                  "gated_few: tensors must be 16-byte aligned");
   const int64_t N = 2 * F;
-  const size_t need = dllava_linear_few_workspace(N, d);
+  const size_t need = dllava_decode_proj_workspace(N, d);
   DLLAVA_REQUIRE(workspace && aligned(workspace, 256) && workspace_bytes >= need, DLLAVA_EWORKSPACE,
                  "gated_few: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(stream);

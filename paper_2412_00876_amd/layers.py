@@ -126,8 +126,8 @@ class DecoderStack:
         self.logits_d = torch.zeros((B, 2), dtype=torch.float32, device=device)
         self.keep_d = torch.zeros(B, dtype=torch.uint8, device=device)
         zb = lambda n: torch.zeros(n, dtype=torch.uint8, device=device)
-        self.ws_few = zb(max(P.dllava_linear_few_workspace(n, k)
-                             for n, k in ((3 * H * Dh, d), (d, H * Dh), (2 * d_ff, d), (d, d_ff))))
+        self.ws_few = zb(max(P.dllava_decode_proj_workspace(3 * H * Dh, d), P.dllava_decode_proj_workspace(2 * d_ff, d),
+                             P.dllava_linear_few_workspace(d, H * Dh), P.dllava_linear_few_workspace(d, d_ff)))
         self.ws_decode = zb(P.dllava_decode_workspace(B, H, Dh, self.caches[0].max_pages_per_seq))
 
     def decode_step(self, x_new, pos, theta: float, predictor):

@@ -101,7 +101,8 @@ def test_decoder_stack_with_one_time_reduction(n_layers, l):
 
 
 @pytest.mark.parametrize("M,K,N,act,res", [(16, 4096, 4096, 0, "inplace"), (8, 4096, 11008, 2, "gate"), (40, 11008, 4096, 0, None),
-                                            (1, 64, 32, 1, None), (64, 320, 96, 0, "other")])
+                                            (1, 64, 32, 1, None), (64, 320, 96, 0, "other"), (20, 2048, 64, 1, "other"),
+                                            (33, 4096, 128, 0, "inplace")])
 def test_linear_layer_on_few_rows(M, K, N, act, res):
     h = _H()
     seed = 3000 + M + K + N
