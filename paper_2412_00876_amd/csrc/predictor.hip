@@ -10,8 +10,15 @@
 //  * attention         prefill_mfma_kernel without the causal mask, 8 heads of 64, one "sequence" per span.
 //  * head_out_kernel   the last layer 128 -> 2, one wave per row.
 //  * small_in_kernel, small_head_kernel   the whole text form on at most 64 rows (a decode step), see below.
-// Every output element is produced by one thread summing in a fixed order (the small-batch path adds its four
-// partial sums in a fixed order too), so the results are bit-reproducible.
+// The same file holds the remaining layers of a LLaMA-family decoder layer (Eq. 2-3 of the paper name only W^Q, W^K,
+// W^V, W^O and an FFN; RMSNorm, rotary positions and the gated FFN are the family's):
+//  * rms_norm_kernel, rms_norm_row_kernel   RMSNorm, one wave or (few rows) one block per row.
+//  * rope_kernel       rotary rotation in place.
+//  * few_fused_kernel  a linear layer on at most 64 rows in one launch (the weights are the traffic), with the
+//                      epilogues of a decode step: bias / GELU / residual / gate, q|k|v with rotary rotation,
+//                      gate|up with the gating.
+// Every output element is produced by one thread summing in a fixed order (sums that cross waves or blocks are
+// added in wave / part order), so the results are bit-reproducible.
 #include <cmath>
 
 #include "gemm_tile.h"
