@@ -264,3 +264,53 @@ def test_fused_gated_layer_of_a_decode_step(M, d, F):
     up = np.abs(xs @ R.widen(Wu, "bf16").T)
     assert (err <= 2.0 ** -7 * np.abs(ref) + 1.2 * 2.0 ** -8 * np.abs(gate) * up + 1e-6).all()
     assert (h.bits(y) != R.narrow(ref, "bf16")).mean() <= 0.03
+
+
+def test_few_rows_layers_replay_from_a_hip_graph():
+    """RMSNorm -> q|k|v -> W_O with residual -> gate|up -> down-projection on few rows, with shapes whose blocks hand
+    sums over through the workspace counters, captured once and replayed: every replay reproduces the eager result
+    bit for bit and leaves the counters at zero."""
+    h = _H()
+    M, d, H, Dh, F, wide = 9, 512, 4, 32, 64, 2048
+    HD = H * Dh
+    dev = lambda name, shape, s=1.0: h.to_dev(W.store(W._normal_big(77, name, shape) * s, "bf16"), "bf16")
+    x = dev("x", (M, d))
+    Wq, Wk, Wv = (dev(n, (HD, d), d ** -0.5) for n in "qkv")
+    Wo, Wg, Wu, Wd = dev("o", (d, HD), HD ** -0.5), dev("g", (F, d), d ** -0.5), dev("u", (F, d), d ** -0.5), dev("d", (d, F), F ** -0.5)
+    Ww, xw = dev("w", (64, wide), wide ** -0.5), dev("xw", (M, wide))
+    gam = torch.from_numpy(rng.uniform(77, "gam", (d,), 0.5, 1.5).astype(np.float32)).to(h.DEV)
+    pos = torch.arange(100, 100 + M, dtype=torch.int32, device=h.DEV)
+    z = lambda *s: torch.zeros(s, dtype=torch.bfloat16, device=h.DEV)
+    y, q, k, v, x1, f, x2, yw = z(M, d), z(M, H, Dh), z(M, H, Dh), z(M, H, Dh), z(M, d), z(M, F), z(M, d), z(M, 64)
+    ws = _few_workspace(max(P.dllava_decode_proj_workspace(3 * HD, d), P.dllava_decode_proj_workspace(2 * F, d),
+                            P.dllava_linear_few_workspace(d, HD), P.dllava_linear_few_workspace(d, F),
+                            P.dllava_linear_few_workspace(64, wide)), 0x5a)
+
+    def chain():
+        P.dllava_rms_norm(x, d, M, d, gam, 1e-5, y, d, P.BF16)
+        P.dllava_qkv_few(y, d, M, d, Wq, Wk, Wv, H, Dh, pos, 10000.0, q, k, v, P.BF16, ws)
+        P.dllava_linear_few(q, HD, M, HD, Wo, None, d, 0, x, x1, d, P.BF16, ws)
+        P.dllava_gated_few(x1, d, M, d, Wg, Wu, F, f, F, P.BF16, ws)
+        P.dllava_linear_few(f, F, M, F, Wd, None, d, 0, x1, x2, d, P.BF16, ws)
+        P.dllava_linear_few(xw, wide, M, wide, Ww, None, 64, 1, None, yw, 64, P.BF16, ws)
+
+    outs = (y, q, k, v, x1, f, x2, yw)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        chain()
+        st.synchronize()
+        ref = [t.clone() for t in outs]
+        assert all(bool(t.float().abs().sum() > 0) for t in ref)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            chain()
+        for rep in range(3):
+            for t in outs:
+                t.zero_()                                      # eager work between replays
+            ws[4096:].fill_(rep + 1)
+            st.synchronize()
+            graph.replay()
+            st.synchronize()
+            for i, (a, b) in enumerate(zip(ref, outs)):
+                assert torch.equal(a.view(torch.int16), b.view(torch.int16)), (rep, i)
+            _counters_back_at_zero(ws)
