@@ -353,7 +353,8 @@ def cpu_baseline(path, seconds):
 
 def pmc_probe(path, torch, L):
     """Dispatches whose hardware counters are read with `rocprofv3 --pmc ...`: a plain device-to-device copy of known
-    size (the scale of the byte counters), one dispatch of every prefill kernel, then the decode kernel three times."""
+    size (the scale of the byte counters), one dispatch of every prefill kernel, the decode kernel three times, then one
+    dispatch of each few-rows layer of a decode step through a decoder layer."""
     w = path.w
     cap = path.cache.max_pages_per_seq * 16
     if L > cap:
@@ -384,9 +385,32 @@ def pmc_probe(path, torch, L):
                                   path.err, path.ws_step)
     torch.cuda.synchronize()
     es = 2 if w.dtype == "bf16" else 4
+    few = None
+    if w.dtype == "bf16":
+        # the few-rows layers of a decode step through a decoder layer (7B feed-forward width), one dispatch each:
+        # RMSNorm, q|k|v + rotary, W_O + residual, gate|up + gating, down-projection + residual
+        P, d, HD, F, B = path.P, w.d, w.H * w.Dh, 11008, w.B
+        rnd = lambda *shape: (torch.randn(*shape, device="cuda:0") * 0.02).to(torch.bfloat16)
+        Wq, Wk, Wv, Wo, Wg, Wu, Wd = rnd(HD, d), rnd(HD, d), rnd(HD, d), rnd(d, HD), rnd(F, d), rnd(F, d), rnd(d, F)
+        xs, gam = rnd(B, d), torch.ones(d, device="cuda:0")
+        zz = lambda *shape: torch.zeros(*shape, dtype=torch.bfloat16, device="cuda:0")
+        y, q3, k3, v3, x1, f, x2 = zz(B, d), zz(B, HD), zz(B, HD), zz(B, HD), zz(B, d), zz(B, F), zz(B, d)
+        pos = torch.arange(B, dtype=torch.int32, device="cuda:0")
+        ws = torch.zeros(max(P.dllava_decode_proj_workspace(3 * HD, d), P.dllava_decode_proj_workspace(2 * F, d),
+                             P.dllava_linear_few_workspace(d, HD), P.dllava_linear_few_workspace(d, F)),
+                         dtype=torch.uint8, device="cuda:0")
+        torch.cuda.synchronize()
+        P.dllava_rms_norm(xs, d, B, d, gam, 1e-5, y, d, path.code)
+        P.dllava_qkv_few(y, d, B, d, Wq, Wk, Wv, w.H, w.Dh, pos, 10000.0, q3, k3, v3, path.code, ws)
+        P.dllava_linear_few(q3, HD, B, HD, Wo, None, d, 0, xs, x1, d, path.code, ws)
+        P.dllava_gated_few(x1, d, B, d, Wg, Wu, F, f, F, path.code, ws)
+        P.dllava_linear_few(f, F, B, F, Wd, None, d, 0, x1, x2, d, path.code, ws)
+        torch.cuda.synchronize()
+        few = {"rows": B, "qkv_weight_bytes": 3 * HD * d * es, "wo_weight_bytes": d * HD * es,
+               "gate_up_weight_bytes": 2 * F * d * es, "down_weight_bytes": d * F * es}
     rows = int(path.out_off[-1].item())
     n_kept = [int(v) for v in (path.out_off[1:] - path.out_off[:-1]).tolist()]
-    print(json.dumps({"pmc_probe": True, "copy_bytes_read": n, "copy_bytes_written": n, "cache_len": L,
+    print(json.dumps({"pmc_probe": True, "few_rows_layers": few, "copy_bytes_read": n, "copy_bytes_written": n, "cache_len": L,
                       "decode_algorithmic_bytes_per_launch": w.B * L * 2 * w.H * w.Dh * es,
                       "decode_step_algorithmic_bytes_per_launch": w.B * L * 2 * w.H * w.Dh * es + (w.d * w.dh + w.B * w.d) * es,
                       "score_vision_flops": 2.0 * path.M_vis * w.d * w.dh,
