@@ -283,7 +283,9 @@ __device__ __forceinline__ void want_now(const uint4& v) { asm volatile("" ::"v"
 // Result: acc[tt] register i of lane = feature 8*(i/4) + 4*(lane/32) + i%4 of input row 32*tt + lane%32.
 template <int NT, int LB, bool HALF = false>  // HALF: only weight rows 0..15 exist (features 16..31 of the result are junk)
 __device__ __forceinline__ void few_accumulate(const bf16_t* const (&wrow)[4], const bf16_t* const (&xrow)[NT][4], int lbeg,
-                                               int lend, bf16_t* sw, int lane, f32x16 (&acc)[NT]) {
+                                               int lend, bf16_t* sw, int lane, f32x16 (&acc)[NT], int jx = 4) {
+  // jx (uniform): row groups of 8 of the LAST row tile that hold input rows; the others are neither loaded nor
+  // staged, and the result rows they would feed (junk from stale LDS) are rows past M, which the callers drop
   const int r = lane & 31, g = lane >> 5;
   const int lr8 = lane >> 3, lc = lane & 7;
   bf16_t* sx = sw + 32 * 64;
@@ -299,7 +301,8 @@ __device__ __forceinline__ void few_accumulate(const bf16_t* const (&wrow)[4], c
       for (int j = 0; j < 4; ++j) {
         if (j < JW) wf[c][j] = *reinterpret_cast<const uint4*>(wrow[j] + 64 * line);
 #pragma unroll
-        for (int tt = 0; tt < NT; ++tt) xf[tt][c][j] = *reinterpret_cast<const uint4*>(xrow[tt][j] + 64 * line);
+        for (int tt = 0; tt < NT; ++tt)
+          xf[tt][c][j] = (tt < NT - 1 || j < jx) ? *reinterpret_cast<const uint4*>(xrow[tt][j] + 64 * line) : uint4{0u, 0u, 0u, 0u};
       }
     }
 #pragma unroll
@@ -319,7 +322,8 @@ __device__ __forceinline__ void few_accumulate(const bf16_t* const (&wrow)[4], c
           const int o = 8 * j * 64 + (st_off ^ ((j & 1) * 32));
           if (j < JW) *reinterpret_cast<uint4*>(sw + o) = wf[c][j];
 #pragma unroll
-          for (int tt = 0; tt < NT; ++tt) *reinterpret_cast<uint4*>(sx + tt * 32 * 64 + o) = xf[tt][c][j];
+          for (int tt = 0; tt < NT; ++tt)
+            if (tt < NT - 1 || j < jx) *reinterpret_cast<uint4*>(sx + tt * 32 * 64 + o) = xf[tt][c][j];
         }
         wave_lds_order();
 #pragma unroll
@@ -495,7 +499,7 @@ __global__ __launch_bounds__(64 * few_waves<EPI>()) void few_fused_kernel(const 
   for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[tt][i] = 0.f;
-  few_accumulate<NT, kFewBatch, HALF>(wrow, xrow, lbeg, lend, stage[w], lane, acc);
+  few_accumulate<NT, kFewBatch, HALF>(wrow, xrow, lbeg, lend, stage[w], lane, acc, (M - 32 * (NT - 1) + 7) / 8);
   few_leave_sums<NT>(acc, stage[w], lane);
   __syncthreads();
 
