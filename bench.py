@@ -52,8 +52,9 @@ def parse():
     ap.add_argument("--no-stack", action="store_true", help="skip the decoder-stack prefill stage (3.2 GB of random weights)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--pmc-probe", type=int, default=0, metavar="L",
-                    help="counter probe for rocprofv3 --pmc: one 256 MiB device copy (calibration), then 3 decode "
-                         "launches at cache length L with appends disabled; prints the algorithmic bytes and exits")
+                    help="counter probe for rocprofv3 --pmc: one 256 MiB device copy (calibration), the prefill kernels, "
+                         "3 decode launches at cache length L with appends disabled, one dispatch of each few-rows "
+                         "layer of a decode step; prints the algorithmic bytes and exits")
     return ap.parse_args()
 
 

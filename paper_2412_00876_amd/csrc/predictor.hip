@@ -281,16 +281,24 @@ __device__ __forceinline__ void want_now(const uint4& v) { asm volatile("" ::"v"
 // (8 * (lane % 8) elements into a 128-byte line) of weight row 8j + lane/8 of the block's 32 features and of input
 // row 8j + lane/8 of row tile tt; lines lbeg .. lend-1 of the input width, LB lines of every row requested together.
 // Result: acc[tt] register i of lane = feature 8*(i/4) + 4*(lane/32) + i%4 of input row 32*tt + lane%32.
-template <int NT, int LB, bool HALF = false>  // HALF: only weight rows 0..15 exist (features 16..31 of the result are junk)
+template <int NT, int LB, bool HALF = false>  // HALF: only weight rows 0..15 exist (features 16..31 of the result are zero)
 __device__ __forceinline__ void few_accumulate(const bf16_t* const (&wrow)[4], const bf16_t* const (&xrow)[NT][4], int lbeg,
                                                int lend, bf16_t* sw, int lane, f32x16 (&acc)[NT], int jx = 4) {
   // jx (uniform): row groups of 8 of the LAST row tile that hold input rows; the others are neither loaded nor
-  // staged, and the result rows they would feed (junk from stale LDS) are rows past M, which the callers drop
+  // staged: they are zeroed once, like the absent weight rows of HALF, and feed result entries nobody reads
   const int r = lane & 31, g = lane >> 5;
   const int lr8 = lane >> 3, lc = lane & 7;
   bf16_t* sx = sw + 32 * 64;
   const int st_off = lr8 * 64 + ((lc ^ ((lr8 >> 1) & 3)) * 8);  // row 8j + lane/8: ((8j + lr8) / 2) % 8 = 4*(j%2) + lr8/2
   const int fr_off = r * 64 + ((g ^ ((r >> 1) & 7)) * 8);       // row r, chunk 2*step + g
+  if (HALF || jx < 4) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int o = 8 * j * 64 + (st_off ^ ((j & 1) * 32));
+      if (HALF && j >= 2) *reinterpret_cast<uint4*>(sw + o) = uint4{0u, 0u, 0u, 0u};
+      if (j >= jx) *reinterpret_cast<uint4*>(sx + (NT - 1) * 32 * 64 + o) = uint4{0u, 0u, 0u, 0u};
+    }
+  }
   for (int l0 = lbeg; l0 < lend; l0 += LB) {
     constexpr int JW = HALF ? 2 : 4;
     uint4 wf[LB][JW], xf[NT][LB][4];  // [line of the batch][row group j]
