@@ -432,9 +432,11 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
 // In all three a thread of the epilogue owns block-local features 8*q4 + 4*g + e ("lo") and 16 + the same ("hi"),
 // e = 0..3, of one row.
 //   kFewPlainHalf  kFewPlain with 16 features per block and 8 waves along the input width: for a narrow output
-//              (N of a few thousand) there are then enough blocks without cutting the input width across blocks,
-//              whose hand-over costs about 5 us; the upper half of the matrix-core tile idles, which costs nothing here.
-enum { kFewPlain = 0, kFewQkv = 1, kFewGated = 2, kFewPlainHalf = 3 };
+//              (N up to 4096: at most one such block per compute unit) there are then enough blocks without cutting
+//              the input width across blocks, whose hand-over costs about 5 us; the upper half of the matrix-core
+//              tile idles, which costs nothing here, but every block reads all input rows: twice the input traffic.
+//   kFewPlain8 kFewPlain with 8 waves along the input width: the outputs between those and the wide ones.
+enum { kFewPlain = 0, kFewQkv = 1, kFewGated = 2, kFewPlainHalf = 3, kFewPlain8 = 4 };
 constexpr int kFewBatch = 2;     // 128-byte lines per row in flight per wave (2: 101 registers; 4 measured 7 % slower)
 constexpr int kFewBlocks = 384;  // blocks aimed at (more measured slower: the launch is bound by its ramp and memory)
 constexpr size_t kFewCounterBytes = 4096;
@@ -455,7 +457,7 @@ struct FewEpi {
 
 // waves of a block, each with its own part of the input width (8 for q|k|v or gate|up measured 3-10 % slower than 4)
 template <int EPI>
-constexpr int few_waves() { return EPI == kFewPlainHalf ? 8 : 4; }
+constexpr int few_waves() { return (EPI == kFewPlainHalf || EPI == kFewPlain8) ? 8 : 4; }
 template <int NT, int EPI>
 __global__ __launch_bounds__(64 * few_waves<EPI>()) void few_fused_kernel(const bf16_t* __restrict__ X, int64_t ldx, int M, int K,
                                                         const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
@@ -558,7 +560,7 @@ __global__ __launch_bounds__(64 * few_waves<EPI>()) void few_fused_kernel(const 
   }
   if (!live) return;
 
-  if (EPI == kFewPlain || HALF) {
+  if (EPI == kFewPlain || EPI == kFewPlain8 || HALF) {
 #pragma unroll
     for (int hf = 0; hf < (HALF ? 1 : 2); ++hf) {
       float* v = hf ? hi : lo;
@@ -1162,18 +1164,24 @@ int few_parts_of(int64_t n_groups, int64_t K, int nw, int aim) {
   return static_cast<int>(kq < 1 ? 1 : kq);
 }
 int few_parts(int64_t N, int64_t K) { return few_parts_of(N / 32, K, 4, kFewBlocks); }
-// A plain layer whose 32-feature groups are too few takes 16-feature groups with 8 waves each instead.
+// A plain layer whose 32-feature groups are too few for blocks of 4 waves takes 8 waves per block instead, and
+// 16-feature groups when those still fit one block per compute unit (measured at d = 4096 / 5120, 16 and 32 rows:
+// W_O 10 / 17 us against 13 / 20 the other way round, down-projection 22.5 / 34 against 28.5 / 44).
 struct FewPlan {
-  bool half;
+  int kind;  // kFewPlain, kFewPlainHalf or kFewPlain8
   int n_fg, kq;
   int64_t cols;  // width of one row of handed-over sums
 };
 FewPlan few_plan_plain(int64_t N, int64_t K) {
   FewPlan p;
-  p.half = few_parts(N, K) > 1;
-  p.n_fg = static_cast<int>(p.half ? N / 16 : N / 32);
-  p.kq = p.half ? few_parts_of(p.n_fg, K, 8, 256) : 1;
   p.cols = N;
+  if (few_parts(N, K) == 1) {
+    p.kind = kFewPlain, p.n_fg = static_cast<int>(N / 32), p.kq = 1;
+  } else if (N / 16 <= 256) {
+    p.kind = kFewPlainHalf, p.n_fg = static_cast<int>(N / 16), p.kq = few_parts_of(p.n_fg, K, 8, 256);
+  } else {
+    p.kind = kFewPlain8, p.n_fg = static_cast<int>(N / 32), p.kq = 1;
+  }
   return p;
 }
 // counters, then the sums that the blocks of one feature group hand over (none when the input width is not cut)
@@ -1223,7 +1231,10 @@ extern "C" int dllava_linear_few(const void* x, int64_t ldx, int64_t M, int64_t 
   ep.R = static_cast<const bf16_t*>(residual);
   ep.Y = static_cast<bf16_t*>(y);
   ep.ldy = ldy;
-  if (plan.half)
+  if (plan.kind == kFewPlain8)
+    launch_few_fused<kFewPlain8>(nt, st, X, ldx, static_cast<int>(M), static_cast<int>(K), Wb, nullptr, nullptr, plan.n_fg,
+                                 plan.kq, plan.n_fg, ep);
+  else if (plan.kind == kFewPlainHalf)
     launch_few_fused<kFewPlainHalf>(nt, st, X, ldx, static_cast<int>(M), static_cast<int>(K), Wb, nullptr, nullptr, plan.n_fg,
                                     plan.kq, plan.n_fg, ep);
   else
