@@ -422,22 +422,22 @@ __global__ __launch_bounds__(256) void small_in_kernel(const bf16_t* __restrict_
 
 // ---- a linear layer of the decoder on few rows (one row per sequence of a decode step), whole in one launch --------
 // The weights are the traffic (the rows are few): block = 32 output features x part kq of the input width, cut again
-// over the block's 4 waves, every weight byte read once.  The four waves' sums meet in LDS; with KQ > 1 the blocks
+// over the block's 4 or 8 waves, every weight byte read once.  The waves' sums meet in LDS; with KQ > 1 the blocks
 // of one feature group hand their sums over through the workspace and a device-scope counter, and the last one to
 // arrive adds them in part order (fixed order: bit-reproducible), so the epilogue runs in the same launch:
 //   kFewPlain  y = act(x W^T + bias) (+ residual | * SiLU(gate rows));
 //   kFewQkv    [q | k | v] = x [Wq | Wk | Wv]^T with the rotary rotation of q and k: a q/k block takes 16 features of
 //              the lower half of a head and their 16 partners of the upper half, so a pair sits in one thread;
 //   kFewGated  y = (x Wu^T) * SiLU(x Wg^T): a block takes 16 gate features and the same 16 up features.
-// In all three a thread of the epilogue owns block-local features 8*q4 + 4*g + e ("lo") and 16 + the same ("hi"),
-// e = 0..3, of one row.
 //   kFewPlainHalf  kFewPlain with 16 features per block and 8 waves along the input width: for a narrow output
 //              (N up to 4096: at most one such block per compute unit) there are then enough blocks without cutting
 //              the input width across blocks, whose hand-over costs about 5 us; the upper half of the matrix-core
 //              tile idles, which costs nothing here, but every block reads all input rows: twice the input traffic.
 //   kFewPlain8 kFewPlain with 8 waves along the input width: the outputs between those and the wide ones.
+// In all of them a thread of the epilogue owns block-local features 8*q4 + 4*g + e ("lo") and 16 + the same ("hi",
+// absent in kFewPlainHalf), e = 0..3, of one row.
 enum { kFewPlain = 0, kFewQkv = 1, kFewGated = 2, kFewPlainHalf = 3, kFewPlain8 = 4 };
-constexpr int kFewBatch = 2;     // 128-byte lines per row in flight per wave (2: 101 registers; 4 measured 7 % slower)
+constexpr int kFewBatch = 2;     // 128-byte lines per row in flight per wave (2: about 110 registers; 4 measured 7 % slower)
 constexpr int kFewBlocks = 384;  // blocks aimed at (more measured slower: the launch is bound by its ramp and memory)
 constexpr size_t kFewCounterBytes = 4096;
 
