@@ -302,3 +302,19 @@ def test_fused_decode_projections_validate_on_the_host(lib):
     _expect(lib, EWORKSPACE, L.dllava_gated_few, *gated(wsb=32))
     assert lib.dllava_decode_proj_workspace(3 * 4096, 4096) >= 4096 and lib.dllava_decode_proj_workspace(3 * 4096, 4096) % 256 == 0
     assert lib.dllava_decode_proj_workspace(96, 4096) >= 4096 + 2 * 64 * 96 * 4
+
+
+def test_few_rows_workspaces_over_a_sweep_of_shapes(lib):
+    """Counters first (4096 bytes), then at most 8 parts of 64 rows of float32 sums; 256-byte multiples; wide outputs,
+    whose input width is not cut across blocks, need the counters only."""
+    L = lib.lib()
+    for K in (64, 512, 4096, 5120, 11008, 13824):
+        for N in list(range(32, 1025, 32)) + [2048, 4096, 5120, 8192, 11008, 12288, 15360, 22016, 27648]:
+            for q in (L.dllava_linear_few_workspace, L.dllava_decode_proj_workspace):
+                b = q(N, K)
+                assert b % 256 == 0 and 4096 <= b <= 4096 + 8 * 64 * N * 4 + 256, (N, K, b)
+    assert L.dllava_linear_few_workspace(4096, 4096) == 4096        # 256 blocks of 16 features, 8 waves along K
+    assert L.dllava_linear_few_workspace(5120, 13824) == 4096       # 160 blocks of 32 features, 8 waves along K
+    assert L.dllava_decode_proj_workspace(3 * 4096, 4096) == 4096   # 384 blocks of 32 features
+    assert L.dllava_decode_proj_workspace(2 * 11008, 4096) == 4096
+    assert L.dllava_linear_few_workspace(0, 4096) == 4096 and L.dllava_decode_proj_workspace(64, 0) == 4096
