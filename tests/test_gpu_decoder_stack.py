@@ -322,3 +322,37 @@ def test_few_rows_layers_replay_from_a_hip_graph():
             for i, (a, b) in enumerate(zip(ref, outs)):
                 assert torch.equal(a.view(torch.int16), b.view(torch.int16)), (rep, i)
             _counters_back_at_zero(ws)
+
+
+@pytest.mark.parametrize("M,K,N", [(7, 512, 4096), (20, 2048, 64), (40, 4096, 12288)])
+def test_few_rows_layers_with_padded_rows(M, K, N):
+    """Input rows with a stride larger than K and output / residual rows with a stride larger than N: the padding is
+    neither read into the result nor written."""
+    h = _H()
+    seed = 7000 + M + K + N
+    ldx, ldy = K + 64, N + 40
+    x = W.store(rng.normal(seed, "x", (M, K)), "bf16")
+    Wm = W.store(W._normal_big(seed, "W", (N, K)) / np.sqrt(K), "bf16")
+    r = W.store(rng.normal(seed, "r", (M, N)), "bf16")
+    ref = R.widen(x, "bf16") @ R.widen(Wm, "bf16").T + R.widen(r, "bf16")
+    xp = torch.full((M, ldx), float("nan"), dtype=torch.bfloat16, device=h.DEV)
+    xp[:, :K] = h.to_dev(x, "bf16")
+    rp = torch.full((M, ldy), float("nan"), dtype=torch.bfloat16, device=h.DEV)
+    rp[:, :N] = h.to_dev(r, "bf16")
+    y = torch.full((M, ldy), 7.0, dtype=torch.bfloat16, device=h.DEV)
+    ws = _few_workspace(P.dllava_linear_few_workspace(N, K), 0x11)
+    P.dllava_linear_few(xp, ldx, M, K, h.to_dev(Wm, "bf16"), None, N, 0, rp, y, ldy, P.BF16, ws)
+    got = h.bits(y)
+    _assert_same_rounding(got[:, :N], ref, f"padded rows {M}x{K}x{N}")
+    assert bool((y[:, N:] == 7.0).all()), "columns past N are left alone"
+    _counters_back_at_zero(ws)
+    if N % 3 == 0 and (N // 3) % 32 == 0:        # the same input through the fused q|k|v layer (rotation at position 0: none)
+        H, Dh = N // 3 // 32, 32
+        outs = [torch.zeros((M, H, Dh), dtype=torch.bfloat16, device=h.DEV) for _ in range(3)]
+        Wd = h.to_dev(Wm, "bf16")
+        ws2 = _few_workspace(P.dllava_decode_proj_workspace(N, K), 0x12)
+        P.dllava_qkv_few(xp, ldx, M, K, Wd[:N // 3], Wd[N // 3:2 * N // 3], Wd[2 * N // 3:], H, Dh,
+                         torch.zeros(M, dtype=torch.int32, device=h.DEV), 10000.0, *outs, P.BF16, ws2)
+        plain = R.widen(x, "bf16") @ R.widen(Wm, "bf16").T
+        for i, o in enumerate(outs):
+            _assert_same_rounding(h.bits(o).reshape(M, -1), plain[:, i * N // 3:(i + 1) * N // 3], f"q|k|v part {i} from padded rows")
