@@ -356,3 +356,48 @@ def test_few_rows_layers_with_padded_rows(M, K, N):
         plain = R.widen(x, "bf16") @ R.widen(Wm, "bf16").T
         for i, o in enumerate(outs):
             _assert_same_rounding(h.bits(o).reshape(M, -1), plain[:, i * N // 3:(i + 1) * N // 3], f"q|k|v part {i} from padded rows")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_few_rows_layers_on_random_shapes(seed):
+    """Seeded random shapes through the three few-rows entry points (all block shapes and hand-over paths are reached
+    over the seeds), each against the float64 product to the rounding of its output."""
+    h = _H()
+    u = lambda name, lo, hi: int(lo + rng.uniform01(9000 + seed, name, 0, 1)[0] * (hi - lo + 0.999))
+    M = [1, 3, 16, 17, 32, 33, 50, 64][u("M", 0, 7)]
+    K = 64 * u("K", 1, 40)
+    N = 32 * u("N", 1, 48)
+    x = W.store(rng.normal(seed, "x", (M, K)), "bf16")
+    xs = R.widen(x, "bf16")
+    Wm = W.store(W._normal_big(seed, "W", (N, K)) / np.sqrt(K), "bf16")
+    b = rng.uniform(seed, "b", (N,), -0.5, 0.5).astype(np.float32)
+    y = torch.zeros((M, N), dtype=torch.bfloat16, device=h.DEV)
+    ws = _few_workspace(P.dllava_linear_few_workspace(N, K), 0x3c)
+    P.dllava_linear_few(h.to_dev(x, "bf16"), K, M, K, h.to_dev(Wm, "bf16"), torch.from_numpy(b).to(h.DEV), N, 1, None, y, N,
+                        P.BF16, ws)
+    _assert_same_rounding(h.bits(y), R.gelu(xs @ R.widen(Wm, "bf16").T + b), f"linear {M}x{K}x{N}")
+    _counters_back_at_zero(ws)
+    # gate|up with F = N and q|k|v with H heads of 32 or 64 (H * Dh = N when that divides)
+    Wu = W.store(W._normal_big(seed, "U", (N, K)) / np.sqrt(K), "bf16")
+    f = torch.zeros((M, N), dtype=torch.bfloat16, device=h.DEV)
+    ws2 = _few_workspace(P.dllava_decode_proj_workspace(2 * N, K), 0x3d)
+    P.dllava_gated_few(h.to_dev(x, "bf16"), K, M, K, h.to_dev(Wm, "bf16"), h.to_dev(Wu, "bf16"), N, f, N, P.BF16, ws2)
+    gate = R.widen(R.narrow(xs @ R.widen(Wm, "bf16").T, "bf16"), "bf16")
+    up = xs @ R.widen(Wu, "bf16").T
+    ref = DR.silu(gate) * up
+    err = np.abs(R.widen(h.bits(f), "bf16") - ref)
+    assert (err <= 2.0 ** -7 * np.abs(ref) + 1.2 * 2.0 ** -8 * np.abs(gate) * np.abs(up) + 1e-6).all()
+    _counters_back_at_zero(ws2)
+    Dh = 64 if N % 64 == 0 and seed % 2 else 32
+    H = N // Dh
+    pos = (rng.uniform01(seed, "p", 0, M) * 4000).astype(np.int32)
+    outs = [torch.zeros((M, H, Dh), dtype=torch.bfloat16, device=h.DEV) for _ in range(3)]
+    Wv = W.store(W._normal_big(seed, "V", (N, K)) / np.sqrt(K), "bf16")
+    ws3 = _few_workspace(P.dllava_decode_proj_workspace(3 * N, K), 0x3e)
+    P.dllava_qkv_few(h.to_dev(x, "bf16"), K, M, K, h.to_dev(Wm, "bf16"), h.to_dev(Wu, "bf16"), h.to_dev(Wv, "bf16"), H, Dh,
+                     torch.from_numpy(pos).to(h.DEV), DR.ROPE_BASE, *outs, P.BF16, ws3)
+    q, k, v = ((xs @ R.widen(m_, "bf16").T).reshape(M, H, Dh) for m_ in (Wm, Wu, Wv))
+    q, k = R.rope_rotate(q, pos, DR.ROPE_BASE), R.rope_rotate(k, pos, DR.ROPE_BASE)
+    for got, want, name in zip(outs, (q, k, v), "qkv"):
+        _assert_same_rounding(h.bits(got), want, f"fused {name} {M}x{K}x{N}")
+    _counters_back_at_zero(ws3)
