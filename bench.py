@@ -11,8 +11,10 @@ inputs resident in HBM before the timed region.  The step is recorded once into 
 `--no-graph` times the same calls issued eagerly from Python instead.
 
 Prints ONE JSON line: metric / value / unit, the roofline object of the decode launch (algorithmic bytes per launch over
-its measured duration, against the HBM peak), cpu_baseline (the oracle timed on the host on a bounded sample), and
-per-stage figures under "stages".
+its measured duration, against the HBM peak), cpu_baseline (the oracle timed on the host on a bounded sample, per stage,
+on one thread and on all cores), per-stage figures under "stages", and -- in the default run -- the same step and its
+stages on the 13B (c4) and high-resolution (c5) workloads, where the matrix-core and compaction stages have their
+largest shapes, and on the batch-1 prompt (batch_1).
 """
 from __future__ import annotations
 
@@ -49,8 +51,16 @@ def parse():
                     help="decode with dllava_score + dllava_decode_attn_append (two dependent launches per step) "
                          "instead of dllava_decode_step (one launch, append deferred by one step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-stack", action="store_true", help="skip the decoder-stack prefill stage (3.2 GB of random weights)")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--stack", action="store_true",
+                    help="also time a prefill and decode steps through 8 whole decoder layers (norms, projections, "
+                         "feed-forward; 3.2 GB of random weights): outside the sparsify-then-attend path, off by default")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the stages outside the timed step (appendix-form predictors, Eq. 7 attention, decoding "
+                         "without KV cache, the two-launch decode form)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="headline workload only: no c4 / c5 / batch_1 objects")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0,
+                    help="budget of EACH of the two oracle timings (one thread, all cores)")
     ap.add_argument("--pmc-probe", type=int, default=0, metavar="L",
                     help="counter probe for rocprofv3 --pmc: one 256 MiB device copy (calibration), the prefill kernels, "
                          "3 decode launches at cache length L with appends disabled, one dispatch of each few-rows "
@@ -58,11 +68,18 @@ def parse():
     return ap.parse_args()
 
 
+def to_dev(a: np.ndarray, dtype: str):
+    """Stored numpy form (uint16 bit patterns for bfloat16) -> device tensor; plumbing only."""
+    import torch
+    if dtype == "bf16" and a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16).copy()).to("cuda:0").view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
 class Path:
     """The whole hot path for one workload, resident on the GPU."""
 
     def __init__(self, w, torch, P, W):
-        from tests.harness import to_dev  # plumbing only (numpy -> device tensor)
         self.to_dev = to_dev
         self.w, self.torch, self.P = w, torch, P
         dev = "cuda:0"

@@ -93,6 +93,24 @@ int dllava_version(void);
 const char* dllava_last_error(void);
 
 /*
+ * Launch shapes.  The library picks the launch shape of its kernels from the problem size alone; results do not depend
+ * on the shape (attention outputs agree to rounding, integer outputs exactly).  This call forces one of them for
+ * the whole process, so that a test can run every kernel variant on one input; value 0 restores the automatic
+ * choice, values a knob does not support are ignored.  Host, no GPU work; not meant for production callers.
+ *   DLLAVA_LAUNCH_DECODE_WAVES   waves per block of the decode-attention kernels: 4 or 8
+ *   DLLAVA_LAUNCH_DECODE_SPLITS  blocks per (sequence, head) of the decode-attention kernels: 1 .. 16
+ *   DLLAVA_LAUNCH_PREFILL_WAVES  waves (of 32 queries each) per block of the matrix-core attention kernel: 1, 2 or 4
+ * The library reads no environment variables.
+ */
+typedef enum {
+  DLLAVA_LAUNCH_DECODE_WAVES = 0,
+  DLLAVA_LAUNCH_DECODE_SPLITS = 1,
+  DLLAVA_LAUNCH_PREFILL_WAVES = 2,
+  DLLAVA_LAUNCH_KNOBS = 3
+} dllava_launch_knob;
+int dllava_set_launch_override(int knob, int value);
+
+/*
  * Predictor scoring, D = P(S_l) (Eq. 5 line 1; Eq. 11 line 1), with the two-layer predictor
  *     h = GELU(x W1^T + b1)   (exact erf GELU),     D = h W2^T + b2,
  * one row per token, rows independent.  Column 0 of D is the "drop" logit, column 1 the "keep"

@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 
 F32, BF16 = 0, 1
 MODE_TOPK, MODE_THRESHOLD, MODE_THRESHOLD_KEEP_LAST = 0, 1, 2
+LAUNCH_DECODE_WAVES, LAUNCH_DECODE_SPLITS, LAUNCH_PREFILL_WAVES = 0, 1, 2
 PAGE_SIZE = 16
 
 
@@ -57,6 +58,8 @@ def _load() -> C.CDLL:
     lib.dllava_version.argtypes = []
     lib.dllava_last_error.restype = C.c_char_p
     lib.dllava_last_error.argtypes = []
+    lib.dllava_set_launch_override.restype = C.c_int
+    lib.dllava_set_launch_override.argtypes = [C.c_int, C.c_int]
     lib.dllava_score.restype = C.c_int
     lib.dllava_score.argtypes = [vp, i64, i64, i32, vp, vp, vp, i64, i64, vp, vp, vp, vp, C.c_int, vp, vp, sz, vp]
     lib.dllava_score_workspace.restype = sz
@@ -117,7 +120,7 @@ def _load() -> C.CDLL:
 
 
 _lib = _load()
-EXPORTS = ("dllava_version", "dllava_last_error", "dllava_score", "dllava_score_workspace",
+EXPORTS = ("dllava_version", "dllava_last_error", "dllava_set_launch_override", "dllava_score", "dllava_score_workspace",
            "dllava_select_compact", "dllava_select_compact_workspace", "dllava_prefill_attn",
            "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_qkv_project",
            "dllava_decode_step", "dllava_decode_step_workspace", "dllava_decode_commit",
@@ -280,6 +283,10 @@ def dllava_version() -> int:
     return _lib.dllava_version()
 
 
+def dllava_set_launch_override(knob: int, value: int) -> None:
+    _check(_lib.dllava_set_launch_override(knob, value))
+
+
 def dllava_score_workspace(M: int, d: int, dh: int, dtype: int) -> int:
     return _lib.dllava_score_workspace(M, d, dh, dtype)
 
@@ -347,4 +354,5 @@ def dllava_decode_attn_append(q, k_new, v_new, B, logits, threshold, keep_overri
     _check(_lib.dllava_decode_attn_append(_p(q), _p(k_new), _p(v_new), B, _p(logits), threshold,
                                           _p(keep_override), cache.ref, scale, _p(o), _p(keep_out),
                                           _p(err_flag), wp, wb, _stream(stream)))
+
 

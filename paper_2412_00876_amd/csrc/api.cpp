@@ -3,6 +3,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "dllava.h"
 
 namespace dllava {
@@ -15,6 +17,10 @@ void set_error(const char* fmt, ...) {
   vsnprintf(g_err, sizeof(g_err), fmt, ap);
   va_end(ap);
 }
+
+static std::atomic<int> g_override[DLLAVA_LAUNCH_KNOBS];
+
+int launch_override(int knob) { return g_override[knob].load(std::memory_order_relaxed); }
 
 int check_cache(const dllava_kv_cache* c, const char* who) {
   if (!c) { set_error("%s: cache is NULL", who); return DLLAVA_ENULL; }
@@ -41,3 +47,16 @@ int check_cache(const dllava_kv_cache* c, const char* who) {
 extern "C" int dllava_version(void) { return 100; }
 
 extern "C" const char* dllava_last_error(void) { return dllava::g_err; }
+
+extern "C" int dllava_set_launch_override(int knob, int value) {
+  if (knob < 0 || knob >= DLLAVA_LAUNCH_KNOBS) {
+    dllava::set_error("set_launch_override: unknown knob %d", knob);
+    return DLLAVA_EINVAL;
+  }
+  if (value < 0) {
+    dllava::set_error("set_launch_override: value %d < 0", value);
+    return DLLAVA_EINVAL;
+  }
+  dllava::g_override[knob].store(value, std::memory_order_relaxed);
+  return DLLAVA_OK;
+}

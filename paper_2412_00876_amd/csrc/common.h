@@ -38,6 +38,7 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t dtype_size(int dtype) { return dtype == DLLAVA_F32 ? 4 : 2; }
 int check_cache(const dllava_kv_cache* c, const char* who);  // host validation of the struct
+int launch_override(int knob);  // value set through dllava_set_launch_override, 0 = automatic
 
 // ---- bfloat16 <-> float32 on the device ------------------------------------------------------
 typedef uint16_t bf16_t;  // raw bit pattern

@@ -244,13 +244,14 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
   const size_t vofs = static_cast<size_t>(H) * tile;    // from a K tile to the V tile of the same page/head
 
   // Pages are dealt round-robin to the S*NW waves that serve (b, h): wave g takes pages g, g+S*NW, ...
-  // Its first page index does not depend on cache_len, so the page-id load and (with one split) the
-  // first K/V loads are issued without waiting for the length: every block-table entry names an
+  // The indices of a wave's first two pages do not depend on cache_len, so their page-id loads and (with one
+  // split) the first K/V loads are issued without waiting for the length: every block-table entry names an
   // allocated page, so the loads are in bounds even if the page turns out to lie beyond the end.
   const int stride = S * NW;
   int p = s * NW + w;
-  int pg = bt[p < a.max_pages ? p : a.max_pages - 1];
-  int L = a.cache_len[b];
+  const int last_entry = a.max_pages - 1;
+  int pg = bt[p < last_entry ? p : last_entry];
+  int pg_next = bt[p + stride < last_entry ? p + stride : last_entry];
   const bool keep_prev = DEFER ? keep_prev_token(a, b) : false;  // block-uniform
   PageRegs<T, DH> cur;
   const bool spec = (S == 1);
@@ -258,10 +259,31 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
     const T* kt = pages + (static_cast<size_t>(pg) * 2 * H + h) * tile;
     load_page<T, DH>(cur, kt, kt + vofs);
   }
-  // Thread 0 announces that this block has read cache_len[b].  The increment depends on the loaded value, so
-  // it cannot be issued before the load has returned; its own latency hides behind the page stream.
+  // ONE thread of the block reads cache_len[b] and then announces the read with a ticket; the other waves take the
+  // length from LDS after the barrier below.  The block that draws a sequence's last ticket may move cache_len[b]
+  // at once, so no wave may read the length from memory after its block's ticket is out: a wave that did would
+  // count slot L (the token being appended) as cached.  The increment depends on the loaded value, so it cannot
+  // be issued before the load has returned; its own latency hides behind the page stream.
+  __shared__ int sm_len, sm_flag, sm_commit;
   int ticket = 0;
-  if (tid == 0) ticket = add_agent(S == 1 ? &a.cnt_b[b * kCnt] : &a.cnt_bh[bh * kCnt], 1 + (L == INT32_MIN));
+  if (tid == 0) {
+    // (an atomic load so that it is performed exactly once; the value was written by an earlier launch, so the
+    // narrowest scope -- an ordinary cached load -- is enough)
+    const int L0 = __hip_atomic_load(&a.cache_len[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    ticket = add_agent(S == 1 ? &a.cnt_b[b * kCnt] : &a.cnt_bh[bh * kCnt], 1 + (L0 == INT32_MIN));
+    sm_len = L0;
+    // With one block per (b, h) the block that drew the last ticket of sequence b already knows that every block
+    // of b has read cache_len[b]: it appends and advances the length NOW, while its first page is still on its
+    // way, instead of at its end, where the work would lengthen the tail of the launch.  Slot cache_len[b] lies
+    // beyond what any block of this launch uses (rows past the length are masked by position, whatever they hold).
+    if (S == 1) {
+      const int commit = (ticket == H - 1);
+      if (commit) zero_agent(&a.cnt_b[b * kCnt]);
+      sm_commit = commit;
+    }
+  }
+  __syncthreads();
+  int L = sm_len;
   const bool append_prev = DEFER && keep_prev && L >= 0 && L < cap;  // the previous token goes to slot L
   L = L < 0 ? 0 : (L > cap ? cap : L);
   const int P = (L + kPage - 1) / kPage;
@@ -269,24 +291,9 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
     const T* kt = pages + (static_cast<size_t>(pg) * 2 * H + h) * tile;
     load_page<T, DH>(cur, kt, kt + vofs);
   }
-  int pg_next = (p + stride < P) ? bt[p + stride] : 0;
-
-  // With one block per (b, h) the block that drew the last ticket of sequence b already knows that every block of
-  // b has read cache_len[b]: it appends and advances the length NOW, while its first page is still on its way,
-  // instead of at its end, where the work would lengthen the tail of the launch.  Slot cache_len[b] lies beyond
-  // what any block of this launch uses (rows past the length are masked by position, whatever they hold).
-  __shared__ int sm_flag, sm_commit;
-  if (S == 1) {
-    if (tid == 0) {
-      const int commit = (ticket == H - 1);
-      if (commit) zero_agent(&a.cnt_b[b * kCnt]);
-      sm_commit = commit;
-    }
-    __syncthreads();
-    if (sm_commit) {
-      if (DEFER) commit_length(a, b, keep_prev);
-      else commit_sequence<T, DH>(a, b);
-    }
+  if (S == 1 && sm_commit) {
+    if (DEFER) commit_length(a, b, keep_prev);
+    else commit_sequence<T, DH>(a, b);
   }
 
   LaneDot<T> qd;
@@ -308,7 +315,7 @@ __device__ __forceinline__ void attn_block(const DecodeArgs& a, int s, int h, in
       const T* vp = static_cast<const T*>(a.v_prev) + bh * DH;
       const uint4 kr2 = *reinterpret_cast<const uint4*>(kp + (lane % C::G) * C::E);
       const uint4 vr2 = *reinterpret_cast<const uint4*>(vp + (lane % C::G) * C::E);
-      const int pgL = bt[L / kPage];  // L is the unclamped length here (append_prev implies 0 <= L < cap)
+      const int pgL = bt[L / kPage];  // the clamp left L as it was (append_prev implies 0 <= L < cap)
       T* dstk = const_cast<T*>(pages) + (static_cast<size_t>(pgL) * 2 * H + h) * tile + static_cast<size_t>(L % kPage) * DH;
       if (lane < C::G) {
         *reinterpret_cast<uint4*>(dstk + lane * C::E) = kr2;
@@ -481,11 +488,6 @@ struct DecodeShape {
   int n_split;  // blocks per (sequence, head)
 };
 
-int env_int(const char* name) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : 0;
-}
-
 // Launch shape from host-known sizes only (cache lengths live on the device).  Measured on MI355X: about
 // 16 waves per CU (4096 in all) already saturate the memory pipeline, and a single split per (b, h) wins
 // whenever that many waves are available, because every further split adds a round trip through memory
@@ -500,9 +502,9 @@ DecodeShape pick_shape(int64_t n_bh, int max_pages) {
   if (S > max_useful) S = max_useful;
   if (S < 1) S = 1;
   sh.n_split = static_cast<int>(S);
-  // tuning overrides
-  if (int v = env_int("DLLAVA_DECODE_WAVES")) sh.nw = (v == 4 || v == 8) ? v : sh.nw;
-  if (int v = env_int("DLLAVA_DECODE_SPLITS")) sh.n_split = v > kMaxSplit ? kMaxSplit : (v < 1 ? 1 : v);
+  // shapes forced through dllava_set_launch_override (tests reach every kernel variant that way)
+  if (int v = launch_override(DLLAVA_LAUNCH_DECODE_WAVES)) sh.nw = (v == 4 || v == 8) ? v : sh.nw;
+  if (int v = launch_override(DLLAVA_LAUNCH_DECODE_SPLITS)) sh.n_split = v > kMaxSplit ? kMaxSplit : v;
   return sh;
 }
 
@@ -526,10 +528,11 @@ size_t partial_bytes(int64_t B, int64_t H, int64_t Dh) {
 }
 
 // host validation shared by the two entry points; fills `a` and the launch shape
+// partial_offset: where the partial results of split launches start in the workspace (0 = right after the counters)
 int prepare(const char* who, const void* q, const void* k_new, const void* v_new, int32_t B, const float* logits,
             float threshold, const uint8_t* keep_override, const dllava_kv_cache* cache, float scale, void* o,
             uint8_t* keep_out, int32_t* err_flag, void* workspace, size_t workspace_bytes, size_t need,
-            DecodeArgs& a, DecodeShape& sh) {
+            DecodeArgs& a, DecodeShape& sh, size_t partial_offset = 0) {
   DLLAVA_REQUIRE(q && k_new && v_new && o, DLLAVA_ENULL, "%s: q, k_new, v_new and o are required", who);
   DLLAVA_REQUIRE(threshold == threshold, DLLAVA_EINVAL, "%s: threshold is NaN", who);
   DLLAVA_REQUIRE(scale == scale && scale > 0.f && scale < INFINITY, DLLAVA_EINVAL, "%s: bad scale", who);
@@ -546,12 +549,13 @@ int prepare(const char* who, const void* q, const void* k_new, const void* v_new
   a.max_pages = cache->max_pages_per_seq; a.H = cache->H; a.B = B;
   sh = pick_shape(static_cast<int64_t>(B) * cache->H, cache->max_pages_per_seq);
   a.n_split = sh.n_split;
-  const size_t n = static_cast<size_t>(B) * cache->H * kMaxSplit;
+  // partial results are indexed (b*H + h) * n_split + s: a region laid out for kMaxSplit serves every split count
+  const size_t n = static_cast<size_t>(B) * cache->H * (partial_offset ? sh.n_split : kMaxSplit);
   char* ws = static_cast<char*>(workspace);
   a.cnt_bh = reinterpret_cast<int32_t*>(ws);
   a.cnt_done = a.cnt_bh + static_cast<size_t>(B) * cache->H * kCnt;
   a.cnt_b = a.cnt_done + static_cast<size_t>(B) * cache->H * kCnt;
-  ws += counter_bytes(B, cache->H);
+  ws += partial_offset ? partial_offset : counter_bytes(B, cache->H);
   a.part_acc = reinterpret_cast<float*>(ws);
   a.part_ml = reinterpret_cast<float*>(ws + round_up(n * cache->Dh * sizeof(float), 256));
   a.o = o; a.keep_out = keep_out; a.err_flag = err_flag;

@@ -45,7 +45,10 @@ __global__ __launch_bounds__(kThreads) void prefill_generic_kernel(PrefillArgs a
       vb = static_cast<const T*>(a.V) + o;
       stride = static_cast<size_t>(H) * DH;
     } else {
-      const int pg = a.block_table[static_cast<size_t>(b) * a.max_pages + c0 / kPage];
+      // clamped to the block table: beyond the capacity (flagged by the call that filled the cache) the reads stay
+      // inside allocated pages
+      const int pi = c0 / kPage < a.max_pages - 1 ? c0 / kPage : a.max_pages - 1;
+      const int pg = a.block_table[static_cast<size_t>(b) * a.max_pages + pi];
       kb = static_cast<const T*>(a.pages) + (static_cast<size_t>(pg) * 2 * H + h) * tile;
       vb = kb + static_cast<size_t>(H) * tile;
       stride = DH;

@@ -331,7 +331,9 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
 
   const bool paged = a.K == nullptr;  // block-uniform
   const int32_t* bt = a.block_table + static_cast<size_t>(b) * a.max_pages;
-  const int last_page = last_key / kPage;
+  // clamped to the block table: a sequence longer than the cache capacity (flagged by the call that filled the
+  // cache) then reads allocated pages, not whatever follows its row of the table
+  const int last_page = last_key / kPage < a.max_pages - 1 ? last_key / kPage : a.max_pages - 1;
   const size_t tl = static_cast<size_t>(kPage) * DH;           // one head's K (or V) rows of a page
   const uint32_t v_off = static_cast<uint32_t>(H * tl);        // from a page's K block to its V block
   const uint32_t row_stride = static_cast<uint32_t>(H) * DH;   // between consecutive rows of K / V
@@ -449,8 +451,7 @@ int prefill_mfma_launch(const PrefillArgs& a, int64_t rows, int Dh, hipStream_t 
   // measured: 2 waves win for the 7B batch-1 prefill (214 rows x 32 heads), 4 waves from batch 2 upwards
   const int64_t work = rows * a.H;  // query rows x heads
   int nwq = work >= 8 * 1024 ? 4 : (work >= 1024 ? 2 : 1);
-  if (const char* e = getenv("DLLAVA_PREFILL_WAVES")) {  // tuning override
-    const int v = atoi(e);
+  if (const int v = launch_override(DLLAVA_LAUNCH_PREFILL_WAVES)) {  // forced through dllava_set_launch_override
     if (v == 1 || v == 2 || v == 4) nwq = v;
   }
   if (Dh == 128) {

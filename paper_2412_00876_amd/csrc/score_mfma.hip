@@ -15,8 +15,9 @@
 //    partials in tile order and the bias.
 //  * score_splitk_kernel (M <= 64, decode: one row per sequence): W1 read once, cut over units and d; see
 //    score_splitk.h.
-// All reductions run in a fixed order: results are bit-reproducible.  Counters live at the start of the
-// workspace, start at zero and are returned to zero by the block that consumes them.
+// All reductions run in a fixed order: results are bit-reproducible.  The counters of the two forms live in
+// disjoint regions at the start of the workspace (layout in score_splitk.h), start at zero and are returned to
+// zero by the block that consumes them, so one workspace serves calls of either form in any order.
 #include "gemm_tile.h"
 #include "score_splitk.h"
 
@@ -26,8 +27,7 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr size_t kCounterBytes = 4096;  // up to 1024 int32 counters at the start of the workspace
-constexpr int kMaxCounters = 1024;
+constexpr int kMaxCounters = static_cast<int>(kGemmCntBytes / sizeof(int32_t));  // one per token tile
 
 // ------------------------------------------------------------------------------------------------
 // GEMM: 128 units x 128 tokens per block
@@ -154,15 +154,15 @@ size_t score_mfma_workspace(int64_t M, int64_t d, int64_t dh) {
   const size_t small = round_up(split_workspace(M < 64 ? M : 64, d, dh), 256);
   if (M <= 64) return small;
   const size_t part = static_cast<size_t>(ceil_div(dh, kTU)) * M * 2 * sizeof(float);
-  const size_t gemm = kCounterBytes + round_up(part, 256);
+  const size_t gemm = kScoreScratchOffset + round_up(part, 256);
   return gemm > small ? gemm : small;
 }
 
 // returns 1 if the shape is not handled here
 int score_mfma_launch(const ScoreArgs& a, hipStream_t st) {
   if (a.d % 64 != 0 || a.ldx % 8 != 0) return 1;
-  int32_t* counters = static_cast<int32_t*>(a.workspace);
-  float* partial = reinterpret_cast<float*>(static_cast<char*>(a.workspace) + kCounterBytes);
+  int32_t* counters = reinterpret_cast<int32_t*>(static_cast<char*>(a.workspace) + kSpAccBytes + kSpCntBytes);
+  float* partial = reinterpret_cast<float*>(static_cast<char*>(a.workspace) + kScoreScratchOffset);
   if (a.M <= 64) {
     if (a.seq_off) return 1;  // span gathering is only wired into the GEMM path
     const SplitPlan p = split_plan(a.d, a.dh);

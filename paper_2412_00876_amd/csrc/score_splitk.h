@@ -37,6 +37,14 @@ constexpr int kSpAccStride = 32;   // in 8-byte words
 constexpr int kSpCntStride = 64;   // in 4-byte words
 constexpr size_t kSpAccBytes = static_cast<size_t>(2 * 64) * kSpAccStride * 8;      // 2 logits x up to 64 tokens
 constexpr size_t kSpCntBytes = static_cast<size_t>(kSpMaxGroups + 1) * kSpCntStride * 4;
+// Workspace layout of dllava_score, shared by its two bfloat16 forms so that one buffer serves both in any order:
+//   [0, kSpAccBytes)                 logit accumulators of the few-rows form      (zero between calls)
+//   [.., + kSpCntBytes)              unit-group tickets of the few-rows form      (zero between calls)
+//   [.., + kGemmCntBytes)            token-tile counters of the GEMM form         (zero between calls)
+//   [kScoreScratchOffset, ...)       partial pre-activation tiles (few rows) or partial logits (GEMM): written
+//                                    before they are read within a call, so either form may leave anything there
+constexpr size_t kGemmCntBytes = 4096;
+constexpr size_t kScoreScratchOffset = kSpAccBytes + kSpCntBytes + kGemmCntBytes;
 
 struct SplitPlan {
   int G;    // unit groups
@@ -61,7 +69,7 @@ inline SplitPlan split_plan(int64_t d, int64_t dh) {
 inline size_t split_workspace(int64_t M, int64_t d, int64_t dh) {
   const SplitPlan p = split_plan(d, dh);
   const size_t mpad = static_cast<size_t>((M + 15) / 16) * 16;
-  return kSpAccBytes + kSpCntBytes + static_cast<size_t>(p.KS) * p.G * kSpUnits * mpad * sizeof(float);
+  return kScoreScratchOffset + static_cast<size_t>(p.KS) * p.G * kSpUnits * mpad * sizeof(float);
 }
 
 __device__ __forceinline__ sp_bf16x8 sp_frag(const uint4& v) {
@@ -72,7 +80,7 @@ __device__ __forceinline__ sp_bf16x8 sp_frag(const uint4& v) {
 
 // The work of block `bid` of the G*KS blocks (threads 0..kSpThreads-1 of the calling block; the function contains
 // block barriers, so the block's other waves, if any, must have ended).
-// NT = 16-token column tiles (M <= 16*NT).  workspace = [accumulators | counters | partial tiles].
+// NT = 16-token column tiles (M <= 16*NT).  workspace = [accumulators | tickets | (GEMM counters) | partial tiles].
 template <int NT>
 __device__ __forceinline__ void score_splitk_block(const ScoreArgs& a, int G, int KS, int ppb, int bid) {
   constexpr int MP = 16 * NT;  // padded token count
@@ -87,7 +95,7 @@ __device__ __forceinline__ void score_splitk_block(const ScoreArgs& a, int G, in
   const bf16_t* X = static_cast<const bf16_t*>(a.x);
   unsigned long long* acc_logit = static_cast<unsigned long long*>(a.workspace);
   int32_t* counters = reinterpret_cast<int32_t*>(static_cast<char*>(a.workspace) + kSpAccBytes);
-  float* partial = reinterpret_cast<float*>(static_cast<char*>(a.workspace) + kSpAccBytes + kSpCntBytes);
+  float* partial = reinterpret_cast<float*>(static_cast<char*>(a.workspace) + kScoreScratchOffset);
   const bf16_t* zero16 = reinterpret_cast<const bf16_t*>(kZeroWords);
 
   // Epilogue operands of the thread's four units (used only by the group's last block), requested first so that

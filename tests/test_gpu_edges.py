@@ -88,6 +88,22 @@ def test_decode_shapes_and_ragged_lengths(B, H, Dh):
     assert np.array_equal(h.bits(g.pages), cache.pages)
 
 
+@pytest.mark.parametrize("waves,splits", [(4, 1), (8, 1), (4, 3), (8, 2), (8, 16)])
+def test_decode_launch_shapes_forced(waves, splits):
+    """Every decode launch shape (waves per block, blocks per (sequence, head)) on the same ragged input, through both
+    forms of the step: the outputs and the cache must not depend on the shape the library would have picked."""
+    from tests.test_gpu_decode_step import _run
+    P.dllava_set_launch_override(P.LAUNCH_DECODE_WAVES, waves)
+    P.dllava_set_launch_override(P.LAUNCH_DECODE_SPLITS, splits)
+    try:
+        test_decode_shapes_and_ragged_lengths(3, 5, 128)
+        w = W.make("forced", "bf16", 256, 3, 128, 5, [70, 1, 16, 0, 33], 0, 0, 1.0, 6, project_qkv=True)
+        _run(w, 6, 0.0, use_override=True)
+    finally:
+        P.dllava_set_launch_override(P.LAUNCH_DECODE_WAVES, 0)
+        P.dllava_set_launch_override(P.LAUNCH_DECODE_SPLITS, 0)
+
+
 @pytest.mark.parametrize("M", [1, 15, 16, 17, 33, 64, 65, 129])
 def test_score_row_counts_around_the_kernel_switches(M):
     h = _H()
@@ -97,6 +113,29 @@ def test_score_row_counts_around_the_kernel_switches(M):
     ref = R.score(pre["hidden"], pred["W1"], pred["b1"], pred["W2"], pred["b2"], "bf16")
     assert np.abs(g.score_rows(g.pre["hidden"]).cpu().numpy() - ref).max() <= TOL
     assert np.abs(g.score_vision().cpu().numpy() - ref).max() <= TOL
+
+
+@pytest.mark.parametrize("first", ["prefill", "decode"])
+def test_score_forms_share_one_workspace(first):
+    """A workspace sized for the largest row count serves every smaller one: the tiled form (576 vision rows) and the
+    few-rows form (16 and 40 rows) alternate on ONE zero-filled buffer at the 7B predictor shape, in both orders."""
+    h = _H()
+    w = W.make("sharews", "bf16", 4096, 1, 128, 1, 0, 576, 0, 1.0, 0)
+    pre, pred = W.prefill_inputs(w), W.predictor(w, random_bias=True)
+    g = h.GpuPath(w, pre, pred)
+    ref = R.score(pre["hidden"], pred["W1"], pred["b1"], pred["W2"], pred["b2"], "bf16")
+    ws = torch.zeros(P.dllava_score_workspace(576, w.d, w.dh, g.code), dtype=torch.uint8, device=h.DEV)
+    p = g.pred
+
+    def run(M):
+        out = torch.full((M, 2), float("nan"), dtype=torch.float32, device=h.DEV)
+        P.dllava_score(g.pre["hidden"], w.d, M, 0, None, None, None, w.d, w.dh, p["W1"], p["b1"], p["W2"], p["b2"],
+                       g.code, out, ws)
+        assert np.abs(out.cpu().numpy() - ref[:M]).max() <= TOL, M
+
+    order = [576, 16, 576, 40, 16, 576] if first == "prefill" else [16, 576, 40, 576, 16]
+    for M in order:
+        run(M)
 
 
 @pytest.mark.parametrize("d", [64, 192, 320])
@@ -114,11 +153,19 @@ def test_score_odd_number_of_pipeline_stages(d):
 
 @pytest.mark.parametrize("waves", [1, 2, 4])
 @pytest.mark.parametrize("from_cache", [False, True])
-def test_prefill_tile_widths(waves, from_cache, monkeypatch):
+def test_prefill_tile_widths(waves, from_cache):
     """The matrix-core prefill kernel with 32, 64 and 128 queries per block (the library picks by problem size;
-    the tuning override forces each), ragged sequence lengths around the tile sizes."""
-    monkeypatch.setenv("DLLAVA_PREFILL_WAVES", str(waves))
+    dllava_set_launch_override forces each), ragged sequence lengths around the tile sizes."""
     h = _H()
+    import paper_2412_00876_amd as P
+    P.dllava_set_launch_override(P.LAUNCH_PREFILL_WAVES, waves)
+    try:
+        _prefill_tile_widths(h, waves, from_cache)
+    finally:
+        P.dllava_set_launch_override(P.LAUNCH_PREFILL_WAVES, 0)
+
+
+def _prefill_tile_widths(h, waves, from_cache):
     B = 6
     w = W.make("widths", "bf16", 512, 4, 128, B, 0, [1, 31, 33, 64, 129, 200], 0, 1.0, 0)
     pre = W.prefill_inputs(w)

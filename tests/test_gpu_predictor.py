@@ -17,11 +17,23 @@ from synth import workloads as W
 # where the float32 sum lands within float32 noise of a rounding boundary, and then one step apart (LAYER_*).  Through
 # the whole predictor a dozen such tensors follow one another, and a one-step difference in one of them moves the
 # next ones off their boundaries too: two correct evaluations settle about one bfloat16 step (2^-8 relative) apart
-# on values of order 1-4, which is also how far the oracle itself moves when its intermediate roundings are switched
-# off (pinned on the CPU).  Logits of the output-text form (three stored tensors) stay within the 2e-2 of the
-# two-layer predictor; for the image form the bound is 5e-2 max-abs with a root-mean-square of at most 8e-3.
+# on values of order 1-4.  Logits of the output-text form (three stored tensors) are held to the 2e-2 stated for
+# predictor logits.  The image form is held to 2e-2 as well wherever the roundings themselves move the result by
+# less than half of that: its bound is derived per case, on the CPU, from the oracle alone -- S = max |oracle with
+# the intermediate roundings - oracle without them| is how far ONE realisation of the roundings lies from the
+# unrounded result, the GPU's evaluation is another realisation of the same roundings (its float32 sums land on the
+# other side of some boundaries), so the two may lie up to 2 S apart: bound = max(2e-2, 2 S), with the
+# root-mean-square held to 8e-3 (S is 1.3e-2 .. 1.8e-2 on the seeded cases, the measured distance 1.4e-2 .. 2.5e-2).
 TOL = 2e-2
-TOL_IMAGE, RMS_IMAGE = 5e-2, 8e-3
+RMS_IMAGE = 8e-3
+
+
+def image_tol(x, span_off, Pw, ref) -> float:
+    """Per-case bound of the image form: max(2e-2, 2 S), S from the oracle alone (see above)."""
+    unrounded = PR.predict(x, span_off, Pw, "bf16", round_intermediates=False)
+    return max(TOL, 2.0 * float(np.abs(ref - unrounded).max()))
+
+
 LAYER_FLIP_FRACTION = 0.02
 
 
@@ -106,7 +118,7 @@ def test_image_predictor_on_ragged_spans(n_vis, d, seed):
     P.dllava_predict(*args, logits, _workspace(h, M, B, 2))
     got = logits.cpu().numpy()
     assert np.isfinite(got).all()
-    assert np.abs(got - ref).max() <= TOL_IMAGE, np.abs(got - ref).max()
+    assert np.abs(got - ref).max() <= image_tol(hidden[rows], span_off, Pw, ref), np.abs(got - ref).max()
     assert np.sqrt(np.mean((got - ref) ** 2)) <= RMS_IMAGE
     # bit-reproducible
     again = torch.zeros_like(logits)
@@ -124,7 +136,7 @@ def test_image_predictor_single_span_without_offsets():
     logits = torch.zeros((M, 2), dtype=torch.float32, device=h.DEV)
     P.dllava_predict(h.to_dev(x, "bf16"), d, M, 0, None, None, None, upload(h, Pw, d), P.BF16, logits,
                      _workspace(h, M, 0, 2))
-    assert np.abs(logits.cpu().numpy() - ref).max() <= TOL_IMAGE
+    assert np.abs(logits.cpu().numpy() - ref).max() <= image_tol(x, np.array([0, M]), Pw, ref)
 
 
 def test_predicted_logits_drive_the_selection():
@@ -144,7 +156,9 @@ def test_predicted_logits_drive_the_selection():
     assert np.array_equal(out["keep_mask"].cpu().numpy(), mask)
     assert np.array_equal(out["out_off"].cpu().numpy(), off)
     ref = PR.predict(pre["hidden"][_span_rows(w)], np.array([0, 100, 160]), Pw, "bf16")
-    assert np.abs(logits.cpu().numpy() - ref).max() <= TOL_IMAGE
+    err = np.abs(logits.cpu().numpy() - ref)
+    assert err.max() <= image_tol(pre["hidden"][_span_rows(w)], np.array([0, 100, 160]), Pw, ref), err.max()
+    assert np.sqrt(np.mean(err ** 2)) <= RMS_IMAGE
 
 
 # ---- the layers one by one, to the rounding of their output -----------------------------------------------------
@@ -251,7 +265,7 @@ def test_image_predictor_at_the_benchmark_shape():
     b = 5
     ref = PR.predict(hidden[off[b]:off[b + 1]], np.array([0, n]), Pw, "bf16")
     err = got[off[b]:off[b + 1]] - ref
-    assert np.abs(err).max() <= TOL_IMAGE, np.abs(err).max()
+    assert np.abs(err).max() <= image_tol(hidden[off[b]:off[b + 1]], np.array([0, n]), Pw, ref), np.abs(err).max()
     assert np.sqrt(np.mean(err ** 2)) <= RMS_IMAGE
     # the sequences differ from one another (no span read another's rows by mistake)
     assert np.abs(got[off[0]:off[1]] - got[off[b]:off[b + 1]]).max() > 0.1

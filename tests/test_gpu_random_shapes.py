@@ -102,7 +102,7 @@ def test_random_shape_whole_path(seed):
                           w.dtype, "masked attention")
         # predictors in the appendix's form: image spans, and the rows of the first decode step
         from oracle import predictor_ref as PR
-        from tests.test_gpu_predictor import TOL_IMAGE, upload
+        from tests.test_gpu_predictor import image_tol, upload
         for nb in (2, 0):
             Pw = W.paper_predictor(w, nb)
             spans = nb == 2
@@ -119,7 +119,8 @@ def test_random_shape_whole_path(seed):
                 P.dllava_predict(h.to_dev(dec["x"][0], "bf16"), w.d, M, 0, None, None, None, upload(h, Pw, w.d), P.BF16,
                                  Dp, wsp)
                 ref = PR.predict(dec["x"][0], None, Pw, "bf16")
-            assert np.abs(Dp.cpu().numpy() - ref).max() <= (TOL_IMAGE if spans else TOL)
+            tol = image_tol(pre["hidden"][vis], np.concatenate([[0], np.cumsum(w.n_vis)]), Pw, ref) if spans else TOL
+            assert np.abs(Dp.cpu().numpy() - ref).max() <= tol
 
     # decode, both forms, with forced decisions (a seeded pattern): outputs close, caches bit-exact
     pattern = W.keep_pattern(w, w.T)
