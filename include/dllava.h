@@ -238,6 +238,24 @@ int dllava_decode_attn_append(const void* q, const void* k_new, const void* v_ne
 size_t dllava_decode_workspace(int32_t B, int32_t H, int32_t Dh, int32_t max_pages_per_seq);
 
 /*
+ * dllava_decode_attn_append for callers that cannot allocate device memory where they run, and so cannot bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and same results as dllava_decode_attn_append, without `workspace`: the counters and partial results
+ * live in a 4 MiB device array that is part of the library's code object (every GPU the library runs on holds its own
+ * copy until the process ends).  The call itself allocates nothing and calls no allocating routine.
+ *   Limits (DLLAVA_ECAPACITY beyond them, nothing launched): 2*B*H + B <= 12288 counters, and at most 1 MiB of
+ *   partial results, B*H*splits*(Dh*4 + 8) bytes for the split count the library picks (none when B*H >= 512).
+ *   The first call on a device resolves the array's device address (hipGetSymbolAddress); make that call outside a
+ *   stream capture.  All calls on one GPU share the array: calls that overlap on one GPU (two streams, two host
+ *   threads) race and must be serialised by the caller.  Between calls the array holds zeros where counters live (each
+ *   launch returns its counters to zero) and stale partial results, which are always written before they are read.
+ */
+int dllava_decode_attn_append_static(const void* q, const void* k_new, const void* v_new, int32_t B,
+                                     const float* logits, float threshold, const uint8_t* keep_override,
+                                     const dllava_kv_cache* cache, float scale,
+                                     void* o, uint8_t* keep_out, int32_t* err_flag, void* stream);
+
+/*
  * The same decode step (Eq. 6) in DEFERRED form: scoring and attention of the current tokens in ONE launch.
  *
  * In dllava_decode_attn_append the append waits for the keep decision, so the predictor must run before the

@@ -74,6 +74,8 @@ def _load() -> C.CDLL:
     lib.dllava_decode_attn_append.restype = C.c_int
     lib.dllava_decode_attn_append.argtypes = [vp, vp, vp, i32, vp, f32, vp, C.POINTER(_KvCache), f32, vp, vp, vp,
                                               vp, sz, vp]
+    lib.dllava_decode_attn_append_static.restype = C.c_int
+    lib.dllava_decode_attn_append_static.argtypes = [vp, vp, vp, i32, vp, f32, vp, C.POINTER(_KvCache), f32, vp, vp, vp, vp]
     lib.dllava_decode_workspace.restype = sz
     lib.dllava_decode_workspace.argtypes = [i32, i32, i32, i32]
     lib.dllava_decode_step.restype = C.c_int
@@ -122,7 +124,7 @@ def _load() -> C.CDLL:
 _lib = _load()
 EXPORTS = ("dllava_version", "dllava_last_error", "dllava_set_launch_override", "dllava_score", "dllava_score_workspace",
            "dllava_select_compact", "dllava_select_compact_workspace", "dllava_prefill_attn",
-           "dllava_decode_attn_append", "dllava_decode_workspace", "dllava_qkv_project",
+           "dllava_decode_attn_append", "dllava_decode_attn_append_static", "dllava_decode_workspace", "dllava_qkv_project",
            "dllava_decode_step", "dllava_decode_step_workspace", "dllava_decode_commit",
            "dllava_predict", "dllava_predict_workspace", "dllava_linear", "dllava_layer_norm", "dllava_span_attn",
            "dllava_masked_attn", "dllava_masked_attn_workspace", "dllava_compact", "dllava_rms_norm", "dllava_linear_few",
@@ -356,3 +358,9 @@ def dllava_decode_attn_append(q, k_new, v_new, B, logits, threshold, keep_overri
                                           _p(err_flag), wp, wb, _stream(stream)))
 
 
+
+def dllava_decode_attn_append_static(q, k_new, v_new, B, logits, threshold, keep_override, cache: KVCache, scale,
+                                     o, keep_out, err_flag, stream=None) -> None:
+    _check(_lib.dllava_decode_attn_append_static(_p(q), _p(k_new), _p(v_new), B, _p(logits), threshold,
+                                                 _p(keep_override), cache.ref, scale, _p(o), _p(keep_out),
+                                                 _p(err_flag), _stream(stream)))

@@ -24,8 +24,16 @@
 //     triples in split order -- a fixed order, so the result is bit-reproducible -- and writes o[b, h].
 #include <limits.h>
 
+#include <mutex>
+
 #include "attend.h"
 #include "score_splitk.h"
+
+// Scratch of dllava_decode_attn_append_static (see there): counters first, then the partial results of split launches.
+constexpr size_t kStaticCounterBytes = size_t{3} << 20;  // counters: (2*B*H + B) * 256 bytes at most this
+constexpr size_t kStaticPartialBytes = size_t{1} << 20;  // partial results of the split count actually launched
+constexpr size_t kStaticScratchBytes = kStaticCounterBytes + kStaticPartialBytes;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace dllava {
 namespace {
@@ -587,6 +595,34 @@ int launch_step(const DecodeArgs& a, const DecodeShape& sh, const ScoreArgs& sa,
   return sh.nw == 8 ? launch_step2<T, DH, 8>(a, sa, p, nt, st) : launch_step2<T, DH, 4>(a, sa, p, nt, st);
 }
 
+// ---- scratch of dllava_decode_attn_append_static ---------------------------------------------------------------
+// For callers that cannot bring a workspace (no allocation possible where they run): the counters and the partial
+// results of split launches live in this array instead.  Every GPU holds its own copy at its own address until the
+// process ends.  In host code the array's NAME is only a stand-in for hipGetSymbolAddress: the kernels get the
+// address that call returned for the current device, as they get the workspace pointer in the other entry point.
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device, resolved at the first call on it
+
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) DLLAVA_FAIL(DLLAVA_ELAUNCH, "decode_static: hipGetDevice: %s", hipGetErrorString(e));
+  DLLAVA_REQUIRE(dev >= 0 && dev < kMaxDevices, DLLAVA_ESHAPE, "decode_static: device %d not supported (at most %d)", dev,
+                 kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      DLLAVA_FAIL(DLLAVA_ELAUNCH, "decode_static: hipGetSymbolAddress on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DLLAVA_OK;
+}
+
 }  // namespace
 }  // namespace dllava
 
@@ -612,6 +648,41 @@ extern "C" int dllava_decode_attn_append(const void* q, const void* k_new, const
   const size_t need = dllava_decode_workspace(B, cache->H, cache->Dh, cache->max_pages_per_seq);
   if (int rc = prepare("decode", q, k_new, v_new, B, logits, threshold, keep_override, cache, scale, o, keep_out,
                        err_flag, workspace, workspace_bytes, need, a, sh))
+    return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool bf = cache->dtype == DLLAVA_BF16;
+  if (cache->Dh == 128) return bf ? launch<bf16_t, 128>(a, sh, st) : launch<float, 128>(a, sh, st);
+  return bf ? launch<bf16_t, 64>(a, sh, st) : launch<float, 64>(a, sh, st);
+}
+
+extern "C" int dllava_decode_attn_append_static(const void* q, const void* k_new, const void* v_new, int32_t B,
+                                                const float* logits, float threshold, const uint8_t* keep_override,
+                                                const dllava_kv_cache* cache, float scale, void* o, uint8_t* keep_out,
+                                                int32_t* err_flag, void* stream) {
+  DLLAVA_REQUIRE(B >= 0, DLLAVA_EINVAL, "decode_static: B = %d < 0", B);
+  if (int rc = check_cache(cache, "decode_static")) return rc;
+  if (B == 0) return DLLAVA_OK;
+  DLLAVA_REQUIRE(logits || keep_override, DLLAVA_ENULL, "decode_static: need logits or keep_override");
+  // sizes first: the array is fixed, so shapes that need more are refused before anything is launched
+  const size_t cnt = counter_bytes(B, cache->H);
+  DLLAVA_REQUIRE(cnt <= kStaticCounterBytes, DLLAVA_ECAPACITY,
+                 "decode_static: 2*B*H + B = %lld counters exceed the %zu the static scratch holds; use "
+                 "dllava_decode_attn_append with a workspace",
+                 2LL * B * cache->H + B, kStaticCounterBytes / (kCnt * sizeof(int32_t)));
+  const DecodeShape want = pick_shape(static_cast<int64_t>(B) * cache->H, cache->max_pages_per_seq);
+  const size_t n = static_cast<size_t>(B) * cache->H * want.n_split;
+  const size_t part =
+      want.n_split > 1 ? round_up(n * cache->Dh * sizeof(float), 256) + round_up(n * 2 * sizeof(float), 256) : 0;
+  DLLAVA_REQUIRE(part <= kStaticPartialBytes, DLLAVA_ECAPACITY,
+                 "decode_static: %zu bytes of partial results (B*H = %lld, %d splits) exceed the %zu the static scratch "
+                 "holds; use dllava_decode_attn_append with a workspace",
+                 part, static_cast<long long>(B) * cache->H, want.n_split, kStaticPartialBytes);
+  void* ptr = nullptr;
+  if (int rc = static_scratch(&ptr)) return rc;
+  DecodeArgs a{};
+  DecodeShape sh;
+  if (int rc = prepare("decode_static", q, k_new, v_new, B, logits, threshold, keep_override, cache, scale, o, keep_out,
+                       err_flag, ptr, kStaticScratchBytes, 0, a, sh, kStaticCounterBytes))
     return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bool bf = cache->dtype == DLLAVA_BF16;
