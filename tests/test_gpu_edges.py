@@ -115,6 +115,33 @@ def test_score_row_counts_around_the_kernel_switches(M):
     assert np.abs(g.score_vision().cpu().numpy() - ref).max() <= TOL
 
 
+@pytest.mark.parametrize("tile", [1, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("d,dh", [(512, 320), (64, 40), (4096, 1024)])
+def test_score_tiles_forced(tile, d, dh):
+    """Every tile shape of the many-rows scoring kernels on the same ragged spans (the library picks by problem size;
+    dllava_set_launch_override forces each): token counts that end inside a tile, unit counts that end inside a unit
+    tile (320 = 256 + 64, 40), one and many stages of d, random biases."""
+    h = _H()
+    w = W.make("tiles", "bf16", d, max(1, d // 128), 128 if d >= 128 else 64, 3, [3, 0, 5], [300, 77, 200], [2, 1, 0], 1.0, 0)
+    w.dh = dh
+    pre, pred = W.prefill_inputs(w), W.predictor(w, random_bias=True)
+    g = h.GpuPath(w, pre, pred)
+    rows = np.concatenate([np.arange(w.seq_off[b] + w.n_sys[b], w.seq_off[b] + w.n_sys[b] + w.n_vis[b])
+                           for b in range(w.B)])
+    ref = R.score(pre["hidden"][rows], pred["W1"], pred["b1"], pred["W2"], pred["b2"], "bf16")
+    P.dllava_set_launch_override(P.LAUNCH_SCORE_TILE, tile)
+    try:
+        got = g.score_vision().cpu().numpy()
+        again = g.score_vision().cpu().numpy()
+        plain = g.score_rows(g.pre["hidden"]).cpu().numpy()
+    finally:
+        P.dllava_set_launch_override(P.LAUNCH_SCORE_TILE, 0)
+    assert np.abs(got - ref).max() <= TOL, np.abs(got - ref).max()
+    assert np.array_equal(got, again)
+    ref_all = R.score(pre["hidden"], pred["W1"], pred["b1"], pred["W2"], pred["b2"], "bf16")
+    assert np.abs(plain - ref_all).max() <= TOL
+
+
 @pytest.mark.parametrize("first", ["prefill", "decode"])
 def test_score_forms_share_one_workspace(first):
     """A workspace sized for the largest row count serves every smaller one: the tiled form (576 vision rows) and the
