@@ -11,8 +11,12 @@
 //    rotation happens in registers.  The tile is then transposed through LDS (chunk-swizzled) so that every
 //    (token, head) row leaves as 256 contiguous bytes.  XCD-aware block order: an XCD owns a group of feature
 //    tiles and walks the token tiles eight at a time, so that its share of W and the x tiles stay in its L2.
+//  * qkv_ring_kernel (bfloat16, Dh = 128, many rows): the same on the large-tile product of gemm_ring.h, one block per
+//    compute unit: 256 features = two heads of Q, K or V against 128 .. 256 compacted rows; wave w holds, of head
+//    w/2, features 32*(w%2) + [0,32) and 64 + 32*(w%2) + [0,32) for all rows of the tile.
 //  * qkv_generic_kernel: any dtype / head size, one thread per rotary pair of one row.
 #include "dllava.h"
+#include "gemm_ring.h"
 #include "gemm_tile.h"
 
 namespace dllava {
@@ -180,6 +184,118 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
   }
 }
 
+// Large-tile form.  Feature tile f of matrix `which` = heads 2f and 2f+1 (the second may not exist when H is odd:
+// its weight rows are clamped and nothing of it is stored).  tok_group: token tiles an XCD keeps in flight per group
+// of its feature tiles (ft_per_xcd * tok_group is about the 32 compute units of an XCD).
+template <int JB>
+__global__ __launch_bounds__(kRingThreads, 1) void qkv_ring_kernel(QkvArgs a, RopeTable rt, int n_ft, int ft_per_xcd,
+                                                                   int tok_group) {
+  constexpr int kTok = 32 * JB;
+  __shared__ __align__(1024) char smem_raw[kRingLdsBytes];
+  DLLAVA_LDS char* smem = (DLLAVA_LDS char*)smem_raw;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int xcd = blockIdx.x % kXcds, jb = blockIdx.x / kXcds;
+  const int per_group = ft_per_xcd * tok_group;
+  const int local = jb % per_group;
+  const int ft = xcd * ft_per_xcd + local % ft_per_xcd;             // feature tile (256 features)
+  const int tt = (jb / per_group) * tok_group + local / ft_per_xcd;  // token tile (kTok compacted rows)
+  const int total = a.off[a.B];
+  const int H = a.H;
+  if (blockIdx.x == 0) set_lengths(a, tid, kRingThreads);
+  if (ft >= n_ft || tt * kTok >= total) return;
+  const int tiles_per_matrix = (H + 1) / 2;
+  const int which = ft / tiles_per_matrix, head0 = 2 * (ft % tiles_per_matrix);
+  const int64_t d = a.d;
+
+  uint32_t ga[kRingALoads], gb[JB];
+#pragma unroll
+  for (int j = 0; j < kRingALoads; ++j) {
+    const int row = ring_load_row(w, j, lane);
+    int64_t f = static_cast<int64_t>(head0) * 128 + row;
+    if (f >= static_cast<int64_t>(H) * 128) f = static_cast<int64_t>(H) * 128 - 1;
+    ga[j] = static_cast<uint32_t>(f * d * 2) + ring_load_chunk_bytes(row, lane);
+  }
+#pragma unroll
+  for (int j = 0; j < JB; ++j) {
+    const int row = ring_load_row(w, j, lane);
+    int r = tt * kTok + row;
+    if (r >= total) r = total - 1;  // such rows are computed and dropped
+    gb[j] = static_cast<uint32_t>(static_cast<int64_t>(r) * a.ldx * 2) + ring_load_chunk_bytes(row, lane);
+  }
+  const int hh = w >> 1, sub = w & 1;  // head of the tile, and which 32 of its rotary pairs
+  ring_f32x16 acc[2][JB];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < JB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  gemm_ring_256<JB, 64, uint32_t>(static_cast<const char*>(a.W[which]), ga, static_cast<const char*>(a.x), gb,
+                                  static_cast<int>(d / kRingBK), smem, w, hh * 128 + sub * 32, acc);
+  __syncthreads();  // the ring memory becomes the transposed output tile
+
+  // where the rows of this tile go: one entry per (head of the tile, token)
+  bf16_t* sO = reinterpret_cast<bf16_t*>(smem_raw);  // [kTok tokens][32 chunks of 8 features], chunk c of token t at c ^ (t % 16)
+  int64_t* sm_dst = reinterpret_cast<int64_t*>(smem_raw + kTok * 512);  // [2][kTok]
+  for (int e = tid; e < 2 * kTok; e += kRingThreads) {
+    const int h2 = e / kTok, t = e % kTok;
+    const int r = tt * kTok + t, head = head0 + h2;
+    int64_t dst = -1;
+    if (r < total && head < H) {
+      if (which == 0) {
+        dst = (static_cast<int64_t>(r) * H + head) * 128;
+      } else {
+        const int b = seq_of_row(a.off, a.B, r);
+        dst = page_slot(a, b, r - a.off[b], head);
+        if (dst >= 0 && which == 2) dst += static_cast<int64_t>(H) * kPage * 128;
+      }
+    }
+    sm_dst[e] = dst;
+  }
+
+  // lane: token column 32*j + lane%32; register r of fragment i: feature 128*hh + 32*sub + 64*i + 8*(r/4) + 4*(lane/32) + r%4
+  const int g = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < JB; ++j) {
+    const int t = 32 * j + (lane & 31);
+    if (which < 2 && a.pos) {
+      int r = tt * kTok + t;
+      if (r >= total) r = total - 1;
+      const float p = static_cast<float>(a.pos[r]);
+#pragma unroll
+      for (int r16 = 0; r16 < 16; ++r16) {
+        const int i = 32 * sub + 8 * (r16 >> 2) + 4 * g + (r16 & 3);  // rotary pair (i, i + 64)
+        const float hi = rt.hi[i];
+        const float ph = p * hi;
+        const float fr = __builtin_amdgcn_fractf(ph) + (__builtin_fmaf(p, hi, -ph) + p * rt.lo[i]);
+        const float sn = __builtin_amdgcn_sinf(fr), cs = __builtin_amdgcn_cosf(fr);
+        const float x0 = acc[0][j][r16], x1 = acc[1][j][r16];
+        acc[0][j][r16] = x0 * cs - x1 * sn;
+        acc[1][j][r16] = x1 * cs + x0 * sn;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int c = (128 * hh + 32 * sub + 64 * i) / 8 + q4;  // chunk of 8 features; this lane's half of it: g
+        uint2 v;
+        v.x = pack_bf16x2(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1]);
+        v.y = pack_bf16x2(acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]);
+        *reinterpret_cast<uint2*>(sO + t * 256 + ((c ^ (t & 15)) * 8) + g * 4) = v;
+      }
+  }
+  __syncthreads();
+  bf16_t* out = static_cast<bf16_t*>(which == 0 ? a.Q_out : a.pages);
+  for (int idx = tid; idx < kTok * 32; idx += kRingThreads) {
+    const int t = idx >> 5, c = idx & 31;
+    const int64_t dst = sm_dst[(c >> 4) * kTok + t];
+    if (dst >= 0)
+      *reinterpret_cast<uint4*>(out + dst + (c & 15) * 8) = *reinterpret_cast<const uint4*>(sO + t * 256 + ((c ^ (t & 15)) * 8));
+  }
+}
+
 // generic path: thread = (compacted row, which of Q/K/V, head, rotary pair i)
 template <typename T>
 __global__ __launch_bounds__(256) void qkv_generic_kernel(QkvArgs a, RopeTableD rt) {
@@ -241,6 +357,41 @@ int launch_mfma(const QkvArgs& a, int64_t rows, double base, hipStream_t st) {
     const double rev = base > 0 ? pow(base, -2.0 * i / 128.0) / two_pi : 0.0;
     rt.hi[i] = static_cast<float>(rev);
     rt.lo[i] = static_cast<float>(rev - static_cast<double>(rt.hi[i]));
+  }
+  // Many rows: the large-tile kernel (one block per compute unit), with the token-tile width that fills the XCDs'
+  // 32 compute units most evenly; DLLAVA_LAUNCH_QKV_TILE forces a width (4..8) or the 128 x 128 kernel (1).
+  {
+    const int n_ft2 = 3 * ((a.H + 1) / 2);
+    const int fpx = static_cast<int>(ceil_div(n_ft2, kXcds));
+    int best = 0;
+    int64_t best_cost = 0;
+    for (int jb = 8; jb >= 4; --jb) {
+      const int64_t per_xcd = ceil_div(rows, 32 * jb) * fpx;
+      if (per_xcd < 24) continue;  // most of the chip would idle
+      const int64_t cost = ceil_div(per_xcd, 32) * (256 * jb + 500);
+      if (!best || cost < best_cost) best = jb, best_cost = cost;
+    }
+    const int forced = launch_override(DLLAVA_LAUNCH_QKV_TILE);
+    if (forced == 1) best = 0;
+    if (forced >= 4 && forced <= 8) best = forced;
+    const bool fits = static_cast<int64_t>(a.H) * 128 * a.d * 2 < (int64_t{1} << 32) && rows * a.ldx * 2 < (int64_t{1} << 32);
+    if (best && fits) {
+      const int tok_group = fpx >= 32 ? 1 : 32 / fpx;
+      const int64_t n_tt2 = ceil_div(rows, 32 * best);
+      const int64_t blocks2 = ceil_div(n_tt2, tok_group) * tok_group * fpx * kXcds;
+      if (blocks2 <= 0x7fffffffLL) {
+        const dim3 grid(static_cast<unsigned>(blocks2)), block(kRingThreads);
+        switch (best) {
+          case 4: hipLaunchKernelGGL(qkv_ring_kernel<4>, grid, block, 0, st, a, rt, n_ft2, fpx, tok_group); break;
+          case 5: hipLaunchKernelGGL(qkv_ring_kernel<5>, grid, block, 0, st, a, rt, n_ft2, fpx, tok_group); break;
+          case 6: hipLaunchKernelGGL(qkv_ring_kernel<6>, grid, block, 0, st, a, rt, n_ft2, fpx, tok_group); break;
+          case 7: hipLaunchKernelGGL(qkv_ring_kernel<7>, grid, block, 0, st, a, rt, n_ft2, fpx, tok_group); break;
+          default: hipLaunchKernelGGL(qkv_ring_kernel<8>, grid, block, 0, st, a, rt, n_ft2, fpx, tok_group); break;
+        }
+        DLLAVA_CHECK_LAUNCH("qkv_ring_kernel");
+        return DLLAVA_OK;
+      }
+    }
   }
   const int n_ft = 3 * a.H;
   const int ft_per_xcd = static_cast<int>(ceil_div(n_ft, kXcds));

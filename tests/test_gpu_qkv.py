@@ -49,6 +49,10 @@ def _project_gpu(h, g, w, x_dev, off_dev, pos_dev, aw, rope_base, rows):
 def test_projection_of_a_ragged_batch(dtype, d, H, Dh, rope_base):
     """select -> compact (hidden states only) -> project: Q rows, K/V in the pages and the cache lengths against
     the oracle, on sequences whose kept lengths straddle the 128-row tiles (and one empty sequence)."""
+    _ragged_batch(dtype, d, H, Dh, rope_base)
+
+
+def _ragged_batch(dtype, d, H, Dh, rope_base, chain=True):
     h = _H()
     w = W.make("qkv", dtype, d, H, Dh, 5, [3, 0, 0, 1, 2], [300, 17, 0, 260, 40], [30, 2, 0, 0, 9], 0.5, 0,
                project_qkv=True)
@@ -78,6 +82,8 @@ def test_projection_of_a_ragged_batch(dtype, d, H, Dh, rope_base):
         _assert_out_close(R.widen(Kg, w.dtype), Kr[off[b]:off[b + 1]], w.dtype, f"K of sequence {b}")
         _assert_out_close(R.widen(Vg, w.dtype), Vr[off[b]:off[b + 1]], w.dtype, f"V of sequence {b}")
 
+    if not chain:
+        return
     # the chain continues: attention over the projected, cached reduced set
     O = g.prefill(Q.contiguous(), out["out_off"])
     Ks, Vs = R.narrow(Kr, w.dtype), R.narrow(Vr, w.dtype)
@@ -85,6 +91,21 @@ def test_projection_of_a_ragged_batch(dtype, d, H, Dh, rope_base):
     err = np.abs(h.as_f64(O[:total]) - O_ref)
     # both sides round Q, K, V to the stored form on their own: a flat bar on the attention outputs
     assert err.max() <= (TOL if dtype == "bf16" else 10 * TOL_F32), float(err.max())
+
+
+@pytest.mark.parametrize("tile", [1, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("H,d", [(3, 256), (4, 4096)])
+def test_projection_tiles_forced(tile, H, d):
+    """Every tile shape of the matrix-core projection kernels on the same ragged batch (the library picks by problem
+    size; dllava_set_launch_override forces each): an odd head count (the last feature tile of the large-tile kernel
+    holds one head only), kept lengths that end inside a token tile, few and many stages of d."""
+    P.dllava_set_launch_override(P.LAUNCH_QKV_TILE, tile)
+    try:
+        # (the attention that follows is left to the small case: with d = 4096 its logits are sharp enough for the two
+        # sides' separately rounded Q and K to move an output by more than the flat bar, whatever kernel projects)
+        _ragged_batch("bf16", d, H, 128, ROPE, chain=d <= 256)
+    finally:
+        P.dllava_set_launch_override(P.LAUNCH_QKV_TILE, 0)
 
 
 def test_projection_large_positions_and_strided_rows():
