@@ -100,6 +100,8 @@ const char* dllava_last_error(void);
  *   DLLAVA_LAUNCH_DECODE_WAVES   waves per block of the decode-attention kernels: 4 or 8
  *   DLLAVA_LAUNCH_DECODE_SPLITS  blocks per (sequence, head) of the decode-attention kernels: 1 .. 16
  *   DLLAVA_LAUNCH_PREFILL_WAVES  waves (of 32 queries each) per block of the matrix-core attention kernel: 1, 2 or 4
+ *   DLLAVA_LAUNCH_PREFILL_BLOCKS blocks of the matrix-core attention kernel's launch (its blocks are persistent and
+ *                                share the work items; by default as many as the chip holds at once): 1 .. 65535
  *   DLLAVA_LAUNCH_SCORE_TILE     tile of the many-rows scoring kernel: 1 = 128 units x 128 tokens, three blocks per
  *                                compute unit; 4 .. 8 = 256 units x 32*value tokens, one block per compute unit
  *   DLLAVA_LAUNCH_QKV_TILE       the same for the projection kernel of dllava_qkv_project
@@ -111,7 +113,8 @@ typedef enum {
   DLLAVA_LAUNCH_PREFILL_WAVES = 2,
   DLLAVA_LAUNCH_SCORE_TILE = 3,
   DLLAVA_LAUNCH_QKV_TILE = 4,
-  DLLAVA_LAUNCH_KNOBS = 5
+  DLLAVA_LAUNCH_PREFILL_BLOCKS = 5,
+  DLLAVA_LAUNCH_KNOBS = 6
 } dllava_launch_knob;
 int dllava_set_launch_override(int knob, int value);
 

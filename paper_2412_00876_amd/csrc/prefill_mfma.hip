@@ -13,6 +13,8 @@
 // registers.  The contraction order of that second product is chosen to match the order in which S^T leaves
 // the keys in a lane; V stays row-major ([key][dim]) in LDS and the matching A fragments (four consecutive keys
 // of one dim per lane) come from the transposing LDS read of this target.
+#include <type_traits>
+
 #include "attend.h"
 #include "prefill_args.h"
 
@@ -222,9 +224,26 @@ __device__ __forceinline__ void tile_step(uint32_t kb, uint32_t vb_in, const uin
   }
 }
 
+// One work item = (sequence, head, tile of NWQ*32 compacted query rows).  Blocks are PERSISTENT: the launch holds as
+// many blocks as fit the chip at once (slots), block p takes every slots-th item and walks their key
+// tiles as ONE stream: the tile loads run two tiles ahead of the arithmetic across item boundaries, the page ids one
+// step further, the queries of the next item are requested (into a second register set) when the current item begins,
+// and an item's outputs are stored after the first tile of the next item has been requested.  A block that starts
+// needs four or five dependent trips to memory before its first tile (offsets, page ids, queries, tile): with one
+// item per block every item paid them (measured: 4-6 us per block against 4-14 us of arithmetic, the compute units
+// idle two thirds of the time); a persistent block pays them once.
+// Items are numbered by DESCENDING query-tile index over all sequences, heads adjacent: a causal item's work grows
+// with its tile index, so every block takes its longest items first and the launch ends with the shortest ones.
 // MASKED: the variant with key masks (a.key_words); the plain kernel carries none of its registers.
 template <int DH, int NWQ, bool MASKED>
-__global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_kernel(PrefillArgs a, int tiles_cap) {
+__global__ __launch_bounds__(NWQ * kWave, (NWQ >= 2 && !MASKED) ? 2 : 1) void prefill_mfma_kernel(PrefillArgs args, int items_cap) {
+  // the arguments as locals (the closures below then capture plain values, which the compiler keeps in registers)
+  const int aB = args.B, aMaxPages = args.max_pages;
+  const float aScale = args.scale_log2;
+  const void* const aK = args.K;
+  const void* const aV = args.V;
+  const void* const aPages = args.pages;
+  void* const aO = args.O;
   constexpr int kBM = NWQ * 32;
   constexpr int kChunks = DH / 8;  // 16-byte chunks per row
   constexpr int kDB = DH / 32;     // 32-dim blocks of the output
@@ -239,86 +258,143 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wq = __builtin_amdgcn_readfirstlane(tid / kWave);
-  const int h = blockIdx.x, H = a.H;
-  // Which (sequence, query tile) is this block?  Causal attention: query tile i of a sequence walks i+1 key-tile
-  // groups, so the work of a block grows with its tile index.  Blocks are therefore numbered by DESCENDING tile
-  // index over all sequences (all heads of a tile adjacent): the launch starts with the longest blocks and its tail
-  // consists of the shortest ones.  (The heads being the fast dimension also puts all query tiles of one
-  // (sequence, head) pair, which read the same K/V, on the same XCD when H is a multiple of 8.)
-  // Every wave works the numbering out for itself: lane = sequence, counting with ballots.
-  int b = 0, tile = 0, n = 0, r0 = 0;
-  if (a.B <= kWave) {
-    const int off_l = lane < a.B ? a.off[lane] : 0, end_l = lane < a.B ? a.off[lane + 1] : 0;
-    const int nb_l = (end_l - off_l + kBM - 1) / kBM;  // tiles of sequence `lane`
-    int total = 0, cnt = 0;
-    for (int i = 0; (cnt = __builtin_popcountll(__ballot(nb_l > i))) != 0; ++i) total += cnt;
-    const int y = total - 1 - static_cast<int>(blockIdx.y);  // position in ASCENDING tile-index order
-    if (y < 0) return;                                       // beyond the last tile
-    int below = 0;  // tiles with a smaller index
-    for (tile = 0;; ++tile) {
-      cnt = __builtin_popcountll(__ballot(nb_l > tile));
-      if (below + cnt > y) break;
-      below += cnt;
-    }
-    // the (y - below)-th sequence, in ascending order, that has a tile of this index
-    const unsigned long long has = __ballot(nb_l > tile);
-    const int before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(has >> 32),
-                                                 __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(has), 0));
-    const unsigned long long me = __ballot(nb_l > tile && before == y - below);
-    b = __builtin_ctzll(me);
-    r0 = __builtin_amdgcn_readlane(off_l, b);  // no second trip to memory for the offsets
-    n = __builtin_amdgcn_readlane(end_l, b) - r0;
-  } else {
-    // many sequences: numbered sequence by sequence, the late (long) tiles of each first
-    tile = blockIdx.y;
-    for (;; ++b) {
-      if (b >= a.B) return;
-      r0 = a.off[b];
-      n = a.off[b + 1] - r0;
-      const int nt = (n + kBM - 1) / kBM;
-      if (tile < nt) {
-        tile = nt - 1 - tile;
-        break;
-      }
-      tile -= nt;
-    }
-  }
-  (void)tiles_cap;
-  const int i0 = tile * kBM;            // first query row of the block (sequence-relative)
-  const int iw = i0 + wq * 32;          // first query row of this wave
+  const int H = args.H;
   const int g = lane >> 5, lq = lane & 31;
-  const bf16_t* Qp = static_cast<const bf16_t*>(a.Q);
+  // Offsets, page table and mask words were written by earlier launches and do not change while this kernel runs:
+  // read through the constant address space, block-uniform indices become scalar loads.  (As plain pointers they
+  // may alias the output, which this kernel now stores inside its loop, and every page id became a vector load
+  // with a full vector-memory wait behind it -- a wait for the tile loads in flight.)
+  typedef const int32_t __attribute__((address_space(4)))* ConstI32;
+  typedef const uint32_t __attribute__((address_space(4)))* ConstU32;
+  const ConstI32 off_c = (ConstI32)args.off;
+  const ConstI32 bt_c = (ConstI32)args.block_table;
+  const ConstU32 kw_c = (ConstU32)args.key_words;
+  const bool full = args.full != 0;  // no causal mask: all keys of the sequence (block-uniform)
+  const bool paged = aK == nullptr;  // block-uniform
+  const int step = static_cast<int>(gridDim.x);
 
-  // Q^T fragments of this wave: lane -> query iw + lq (clamped), 8 consecutive d at 16*ks + 8*g
-  int qi = iw + lq;
-  const bool q_ok = qi < n;
-  if (!q_ok) qi = n - 1;
-  uint4 qf[DH / 16];
-  {
-    const bf16_t* qrow = Qp + (static_cast<size_t>(r0 + qi) * H + h) * DH + 8 * g;
-#pragma unroll
-    for (int ks = 0; ks < DH / 16; ++ks) qf[ks] = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
+  // Which (sequence, query tile) is item k?  With at most 64 sequences every wave keeps the sequences' offsets in
+  // its lanes (lane = sequence; one trip to memory per block) and counts with ballots; with more, the sequences are
+  // walked with scalar loads (then there is one item per block).
+  const bool by_lane = aB <= kWave;
+  int off_l = 0, end_l = 0, nb_l = 0, total = 0;
+  if (by_lane) {
+    off_l = lane < aB ? off_c[lane] : 0;
+    end_l = lane < aB ? off_c[lane + 1] : 0;
+    // The offsets have arrived; the statement also tells the compiler so: it would otherwise order every later use
+    // of them, in loops it cannot see through, behind ALL outstanding vector-memory operations -- the tile loads.
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(off_l), "+v"(end_l));
+    nb_l = (end_l - off_l + kBM - 1) / kBM;  // tiles of sequence `lane`
+    int cnt = 0;
+    for (int i = 0; (cnt = __builtin_popcountll(__ballot(nb_l > i))) != 0; ++i) total += cnt;
   }
+  struct Item {
+    int valid, b, h, tile, r0, n;
+  };
+  auto locate = [&](int k) __attribute__((always_inline)) {
+    Item it{0, 0, 0, 0, 0, 0};
+    if (k >= items_cap) return it;
+    const int yd = k / H;  // position in DESCENDING tile-index order
+    it.h = k - yd * H;
+    if (by_lane) {
+      const int y = total - 1 - yd;  // position in ascending order
+      if (y < 0) return it;
+      int below = 0, tile = 0;  // tiles with a smaller index
+      for (;; ++tile) {
+        const int cnt = __builtin_popcountll(__ballot(nb_l > tile));
+        if (below + cnt > y) break;
+        below += cnt;
+      }
+      // the (y - below)-th sequence, in ascending order, that has a tile of this index
+      const unsigned long long has = __ballot(nb_l > tile);
+      const int before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(has >> 32),
+                                                   __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(has), 0));
+      const unsigned long long me = __ballot(nb_l > tile && before == y - below);
+      it.b = __builtin_ctzll(me);
+      it.tile = tile;
+      it.r0 = __builtin_amdgcn_readlane(off_l, it.b);
+      it.n = __builtin_amdgcn_readlane(end_l, it.b) - it.r0;
+      it.valid = 1;
+    } else {
+      // many sequences: numbered sequence by sequence, the late (long) tiles of each first
+      int tile = yd;
+      for (int b = 0; b < aB; ++b) {
+        const int r0 = off_c[b], n = off_c[b + 1] - r0;
+        const int nt = (n + kBM - 1) / kBM;
+        if (tile < nt) {
+          it.b = b; it.tile = nt - 1 - tile; it.r0 = r0; it.n = n; it.valid = 1;
+          break;
+        }
+        tile -= nt;
+      }
+    }
+    return it;
+  };
+  // keys 0..last_key of its sequence are needed by an item
+  auto last_key_of = [&](const Item& it) __attribute__((always_inline)) { return (!full && it.tile * kBM + kBM < it.n ? it.tile * kBM + kBM : it.n) - 1; };
 
-  // key-mask words of this sequence: word t in lane t % 64 of register t / 64 (requested with the queries)
-  const uint32_t* kw = MASKED ? a.key_words + (r0 >> 5) + b : nullptr;  // block-uniform
-  uint32_t kwr[4] = {~0u, ~0u, ~0u, ~0u};
-  if (MASKED) {
-    const int nw = (n + 31) >> 5;
+  // Round j of block p takes item p + j*step, in odd rounds (step-1-p) + j*step: the rounds run through the items
+  // (sorted by descending work) in alternating directions, so a block that got a longer item in one round gets a
+  // shorter one in the next and the blocks' totals stay close (C5 shape: 40..42 tiles per block instead of 36..46).
+  const int pblk = static_cast<int>(blockIdx.x);
+  auto item_of = [&](int j) __attribute__((always_inline)) { return ((j & 1) ? step - 1 - pblk : pblk) + j * step; };
+  int jC = 0;
+  Item C = locate(item_of(0));
+  if (!C.valid) return;
+  Item nextC = locate(item_of(1));
+
+  // ---- per-wave state of the item being computed -------------------------------------------------------------------
+  const bf16_t* Qp = static_cast<const bf16_t*>(args.Q);
+  uint4 qf[DH / 16];       // Q^T fragments: lane -> query iw + lq (clamped), 8 consecutive d at 16*ks + 8*g
+  uint4 qn[DH / 16];       // the same for the block's NEXT item, requested a whole item ahead
+  auto load_queries = [&](const Item& it, uint4 (&dst)[DH / 16]) __attribute__((always_inline)) {
+    int q = it.tile * kBM + wq * 32 + lq;
+    if (q >= it.n) q = it.n - 1;
+    const bf16_t* qrow = Qp + (static_cast<size_t>(it.r0 + q) * H + it.h) * DH + 8 * g;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) kwr[k] = kw[64 * k + lane < nw ? 64 * k + lane : nw - 1];
-  }
+    for (int ks = 0; ks < DH / 16; ++ks) dst[ks] = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
+  };
+  load_queries(C, qn);
+  // key-mask word of a tile: a block-uniform scalar load, fetched one tile before it is used
+  uint32_t kmask_next = ~0u;
+  auto mask_word = [&](const Item& it, int t) __attribute__((always_inline)) {
+    return MASKED ? kw_c[(it.r0 >> 5) + it.b + t] : ~0u;
+  };
+  kmask_next = mask_word(C, 0);
 
   f32x16 o_acc[kDB];
-#pragma unroll
-  for (int nb = 0; nb < kDB; ++nb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o_acc[nb][r] = 0.f;
   float m_ref = -1e30f, l_run = 0.f;  // finite floor, not -inf: see tile_step
-
-  const bool full = a.full != 0;  // no causal mask: all keys of the sequence (block-uniform)
-  const int last_key = (!full && i0 + kBM < n ? i0 + kBM : n) - 1;  // keys 0..last_key are needed by this block
-  const int n_tiles = last_key / kBN + 1;
+  int iw = 0, qi = 0;                 // first query row of this wave; this lane's query (clamped)
+  bf16_t* orow = nullptr;             // where this lane's query goes; null for a lane without a query
+  auto begin_item = [&](const Item& it) __attribute__((always_inline)) {
+#pragma unroll
+    for (int nb = 0; nb < kDB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o_acc[nb][r] = 0.f;
+    m_ref = -1e30f;
+    l_run = 0.f;
+    iw = it.tile * kBM + wq * 32;
+    qi = iw + lq;
+    const bool q_ok = qi < it.n;
+    if (!q_ok) qi = it.n - 1;
+    orow = q_ok ? static_cast<bf16_t*>(aO) + (static_cast<size_t>(it.r0 + qi) * H + it.h) * DH : nullptr;
+  };
+  auto store_item = [&]() __attribute__((always_inline)) {
+    // l is split between the two lanes of a query
+    l_run += __shfl_xor(l_run, 32, kWave);
+    if (orow) {
+      const float inv = 1.f / l_run;
+#pragma unroll
+      for (int nb = 0; nb < kDB; ++nb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {  // dims nb*32 + 8*q4 + 4*g + 0..3
+          uint2 w2;
+          w2.x = pack_bf16x2(o_acc[nb][4 * q4] * inv, o_acc[nb][4 * q4 + 1] * inv);
+          w2.y = pack_bf16x2(o_acc[nb][4 * q4 + 2] * inv, o_acc[nb][4 * q4 + 3] * inv);
+          *reinterpret_cast<uint2*>(orow + nb * 32 + 8 * q4 + 4 * g) = w2;
+        }
+    }
+  };
 
   // Fragment addresses (LDS bytes, stage 0).  K: row lq, logical chunk 2*ks + g, stored at chunk ^ (lq mod chunks):
   // the step ks enters as an exclusive-or with 32*ks.  V: the transposing read of 16 lanes (j = lane mod 16) returns
@@ -329,115 +405,157 @@ __global__ __launch_bounds__(NWQ * kWave, NWQ >= 2 ? 2 : 1) void prefill_mfma_ke
   const uint32_t vb0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((DLLAVA_LDS bf16_t*)sV)) +
                        (4 * g + (j >> 2)) * kRowBytes + ((j >> 2) % (kChunks / 4)) * 64 + lqh * 32 + (j & 3) * 8;
 
-  const bool paged = a.K == nullptr;  // block-uniform
-  const int32_t* bt = a.block_table + static_cast<size_t>(b) * a.max_pages;
-  // clamped to the block table: a sequence longer than the cache capacity (flagged by the call that filled the
-  // cache) then reads allocated pages, not whatever follows its row of the table
-  const int last_page = last_key / kPage < a.max_pages - 1 ? last_key / kPage : a.max_pages - 1;
   const size_t tl = static_cast<size_t>(kPage) * DH;           // one head's K (or V) rows of a page
   const uint32_t v_off = static_cast<uint32_t>(H * tl);        // from a page's K block to its V block
   const uint32_t row_stride = static_cast<uint32_t>(H) * DH;   // between consecutive rows of K / V
-  // page ids of a tile: block-uniform indices, so these are scalar loads; fetched one step before they are used
+
+  // ---- the stream of tile loads: item P, its tile tP is the next one to request ---------------------------------------
+  int jP = 0, tP = 0;
+  Item P = C;
+  int lastP = last_key_of(P);
+  // Page ids of a tile are block-uniform scalar loads, fetched one step before the tile is requested.  The index is
+  // clamped to the block table: a sequence longer than the cache capacity (flagged by the call that filled the
+  // cache) then reads allocated pages, not whatever follows its row of the table.
   int pg_lo = 0, pg_hi = 0;
-#define PAGE_IDS(t)                                                                    \
-  if (paged) {                                                                         \
-    const int p_lo = 2 * (t) < last_page ? 2 * (t) : last_page;                        \
-    const int p_hi = 2 * (t) + 1 < last_page ? 2 * (t) + 1 : last_page;                \
-    pg_lo = bt[p_lo];                                                                  \
-    pg_hi = bt[p_hi];                                                                  \
-  }
-#define ISSUE(t, stage)                                                                                        \
-  {                                                                                                            \
-    const int lim = last_key - (t) * kBN;                                                                      \
-    bf16_t* dk = sK + (stage) * kTileElems;                                                                    \
-    bf16_t* dv = sV + (stage) * kTileElems;                                                                    \
-    if (paged) {                                                                                               \
-      const bf16_t* pages = static_cast<const bf16_t*>(a.pages);                                               \
-      D::paged(dk, dv, pages + (static_cast<size_t>(pg_lo) * 2 * H + h) * tl,                                  \
-               pages + (static_cast<size_t>(pg_hi) * 2 * H + h) * tl, v_off, lim, wq, lane);                   \
-    } else {                                                                                                   \
-      const size_t o = (static_cast<size_t>(r0 + (t) * kBN) * H + h) * DH;                                     \
-      D::rows(dk, dv, static_cast<const bf16_t*>(a.K) + o, static_cast<const bf16_t*>(a.V) + o, row_stride,    \
-              lim, wq, lane);                                                                                  \
-    }                                                                                                          \
-  }
+  auto fetch_page_ids = [&]() __attribute__((always_inline)) {  // for tile tP of item P
+    if (paged && P.valid) {
+      const ConstI32 bt = bt_c + static_cast<size_t>(P.b) * aMaxPages;
+      const int last_page = lastP / kPage < aMaxPages - 1 ? lastP / kPage : aMaxPages - 1;
+      const int p_lo = 2 * tP < last_page ? 2 * tP : last_page;
+      const int p_hi = 2 * tP + 1 < last_page ? 2 * tP + 1 : last_page;
+      pg_lo = bt[p_lo];
+      pg_hi = bt[p_hi];
+    }
+  };
+  auto request_tile = [&](int stage) __attribute__((always_inline)) {  // tile tP of item P into `stage`, then on to the next tile of the stream
+    const int lim = lastP - tP * kBN;
+    bf16_t* dk = sK + stage * kTileElems;
+    bf16_t* dv = sV + stage * kTileElems;
+    if (paged) {
+      const bf16_t* pages = static_cast<const bf16_t*>(aPages);
+      D::paged(dk, dv, pages + (static_cast<size_t>(pg_lo) * 2 * H + P.h) * tl,
+               pages + (static_cast<size_t>(pg_hi) * 2 * H + P.h) * tl, v_off, lim, wq, lane);
+    } else {
+      const size_t o = (static_cast<size_t>(P.r0 + tP * kBN) * H + P.h) * DH;
+      D::rows(dk, dv, static_cast<const bf16_t*>(aK) + o, static_cast<const bf16_t*>(aV) + o, row_stride, lim, wq, lane);
+    }
+    if (++tP > lastP / kBN) {  // the item's last tile: the stream goes on with the block's next item
+      ++jP;
+      P = locate(item_of(jP));
+      tP = 0;
+      lastP = P.valid ? last_key_of(P) : 0;
+    }
+    fetch_page_ids();
+  };
 
-  PAGE_IDS(0);
-  ISSUE(0, 0);
-  if (n_tiles > 1) {
-    PAGE_IDS(1);
-    ISSUE(1, 1);
+  fetch_page_ids();
+  request_tile(0);
+  int ahead = 0;  // tiles requested beyond the one the arithmetic is at
+  if (P.valid) {
+    request_tile(1);
+    ahead = 1;
   }
-  PAGE_IDS(2);
-  // the query fragments have arrived before the loop starts (the tiles requested after them may still be on their way)
-#pragma unroll
-  for (int ks = 0; ks < DH / 16; ++ks) asm volatile("" ::"v"(qf[ks].x), "v"(qf[ks].y), "v"(qf[ks].z), "v"(qf[ks].w));
-  if (MASKED) asm volatile("" ::"v"(kwr[0]), "v"(kwr[1]), "v"(kwr[2]), "v"(kwr[3]));  // and so have the mask words
-
-  int cur = 0;  // stage of tile t
-  for (int t = 0; t < n_tiles; ++t) {
-    // This wave's own loads of tile t are waited for (those of tile t+1, issued later, may stay in flight), then
-    // the barrier makes every wave's part of the tile visible and says that all waves have left tile t-1.
-    // The count assumes that the tile loads are the only vector-memory operations issued inside the loop: the
-    // kernel must not spill registers (scratch traffic would be counted too); the build's resource report is
-    // checked for that by the tests.
-    if (t + 1 < n_tiles)
+  int cur = 0;       // stage of the tile the arithmetic is at
+  int nC = last_key_of(C) / kBN + 1;
+  bool have_prev = false;  // an item's outputs are still to be stored
+  // One tile of the stream.  FIRST: it is the first tile of item C -- its queries (requested when the previous item
+  // ended) must have arrived, and the previous item's outputs leave behind this tile's request.  (A separate
+  // instantiation rather than a flag: the compiler places its own waits for the query loads by what MAY be
+  // outstanding on any path, and would wait for the tile loads just requested in every iteration.)
+  auto tile_iteration = [&](auto first_tag, const int tC) __attribute__((always_inline)) {
+    constexpr bool FIRST = decltype(first_tag)::value;
+    // This wave's own loads of the tile are waited for (those of the next tile, requested later, may stay in flight),
+    // then the barrier makes every wave's part of the tile visible and says that all waves have left the tile before.
+    // The count assumes that nothing but the tile loads of the NEXT tile was issued after this tile's loads; whatever
+    // else is in flight (queries of a new item, an item's output stores, mask words) only makes the wait longer.
+    // The kernel must not spill registers (scratch traffic would count too): the tests check the build's resource report.
+    if (ahead > 0)
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * D::kLoads) : "memory");
     else
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (FIRST) {
+      // the item's queries were requested a whole item ago (the first item's: before the first tiles); they move into
+      // the registers the products read, and the next item's are requested into the other set
+#pragma unroll
+      for (int ks = 0; ks < DH / 16; ++ks) qf[ks] = qn[ks];
+#pragma unroll
+      for (int ks = 0; ks < DH / 16; ++ks) asm volatile("" : "+v"(qf[ks].x), "+v"(qf[ks].y), "+v"(qf[ks].z), "+v"(qf[ks].w));
+    }
     __builtin_amdgcn_s_barrier();
-    const int prv = cur == 0 ? kStages - 1 : cur - 1;  // the stage tile t-1 used: free now, tile t+2 goes there
-    if (t + 2 < n_tiles) {
-      ISSUE(t + 2, prv);
-      PAGE_IDS(t + 3);
+    const int prv = cur == 0 ? kStages - 1 : cur - 1;  // the stage of the tile before: free now
+    if (P.valid) {
+      request_tile(prv);
+      ++ahead;
     }
-    const int j0 = t * kBN;
-    uint32_t kmask = ~0u;  // wave-uniform
-    if (MASKED) {
-      const uint32_t sel = t < 64 ? kwr[0] : (t < 128 ? kwr[1] : (t < 192 ? kwr[2] : kwr[3]));
-      kmask = t < 256 ? static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(sel), t & 63)) : kw[t];
+    if (FIRST) {
+      if (have_prev) store_item();  // the previous item's outputs, behind the tile request
+      begin_item(C);
+      if (nextC.valid) load_queries(nextC, qn);
     }
+    const int j0 = tC * kBN;
+    const uint32_t kmask = kmask_next;  // wave-uniform
+    if (MASKED && tC + 1 < nC) kmask_next = mask_word(C, tC + 1);
     // skipped (wave-uniform): the tile lies entirely above this wave's diagonal, the wave has no query, or every key
     // of the tile is masked and none of them is a query of this wave
-    if ((full || j0 <= iw + 31) && iw < n && !(kmask == 0u && j0 + kBN - 1 < iw)) {
+    if ((full || j0 <= iw + 31) && iw < C.n && !(kmask == 0u && j0 + kBN - 1 < iw)) {
       const uint32_t kb = kb0 + cur * (kTileElems * 2), vb = vb0 + cur * (kTileElems * 2);
       // masking needed: some key of the tile may exceed some query of the wave (causal) or the end of the sequence
       // (full), or is hidden by its mask bit
-      tile_step<DH, MASKED>(kb, vb, qf, o_acc, m_ref, l_run, a.scale_log2, j0, full ? n - 1 : qi, g,
-                            j0 + kBN - 1 > (full ? n - 1 : iw) || kmask != ~0u, kmask, qi);
+      tile_step<DH, MASKED>(kb, vb, qf, o_acc, m_ref, l_run, aScale, j0, full ? C.n - 1 : qi, g,
+                            j0 + kBN - 1 > (full ? C.n - 1 : iw) || kmask != ~0u, kmask, qi);
     }
     cur = cur == kStages - 1 ? 0 : cur + 1;
+    --ahead;
+  };
+  for (;;) {
+    tile_iteration(std::true_type{}, 0);
+    for (int t = 1; t < nC; ++t) tile_iteration(std::false_type{}, t);
+    have_prev = true;
+    if (!nextC.valid) break;
+    // next item (its queries were requested when this one began)
+    ++jC;
+    C = nextC;
+    nextC = locate(item_of(jC + 1));
+    nC = last_key_of(C) / kBN + 1;
+    kmask_next = mask_word(C, 0);
   }
-#undef ISSUE
-#undef PAGE_IDS
+  store_item();
+}
 
-  // l is split between the two lanes of a query
-  l_run += __shfl_xor(l_run, 32, kWave);
-  if (!q_ok) return;
-  const float inv = 1.f / l_run;
-  bf16_t* orow = static_cast<bf16_t*>(a.O) + (static_cast<size_t>(r0 + qi) * H + h) * DH;
-#pragma unroll
-  for (int nb = 0; nb < kDB; ++nb)
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {  // dims nb*32 + 8*q4 + 4*g + 0..3
-      uint2 w2;
-      w2.x = pack_bf16x2(o_acc[nb][4 * q4] * inv, o_acc[nb][4 * q4 + 1] * inv);
-      w2.y = pack_bf16x2(o_acc[nb][4 * q4 + 2] * inv, o_acc[nb][4 * q4 + 3] * inv);
-      *reinterpret_cast<uint2*>(orow + nb * 32 + 8 * q4 + 4 * g) = w2;
-    }
+// blocks that fit the chip at once (persistent launch): compute units x blocks per compute unit, found once per kernel
+template <int DH, int NWQ, bool MASKED>
+int64_t resident_blocks() {
+  static int64_t cached = 0;  // the same value whichever thread gets here first
+  if (cached) return cached;
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    cus = 256;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, prefill_mfma_kernel<DH, NWQ, MASKED>, NWQ * kWave, 0) != hipSuccess ||
+      per_cu <= 0)
+    per_cu = 2;
+  cached = static_cast<int64_t>(cus) * per_cu;
+  return cached;
 }
 
 template <int DH, int NWQ>
 int launch(const PrefillArgs& a, int64_t rows, hipStream_t st) {
   constexpr int kBM = NWQ * 32;
   const int64_t tiles = ceil_div(rows, kBM) + a.B;  // upper bound on sum_b ceil(n_b / kBM)
-  if (tiles > 0x7fffffffLL) return 1;
-  if (tiles > 65535) return 1;
-  dim3 grid(static_cast<unsigned>(a.H), static_cast<unsigned>(tiles));
-  if (a.key_words)
-    hipLaunchKernelGGL((prefill_mfma_kernel<DH, NWQ, true>), grid, dim3(NWQ * kWave), 0, st, a, static_cast<int>(tiles));
-  else
-    hipLaunchKernelGGL((prefill_mfma_kernel<DH, NWQ, false>), grid, dim3(NWQ * kWave), 0, st, a, static_cast<int>(tiles));
+  const int64_t items = tiles * a.H;
+  if (items > 0x7fffffffLL) return 1;
+  // one item per block when the sequences are too many to be numbered in a wave's lanes (see the kernel)
+  const bool persistent = a.B <= kWave;
+  const int forced = persistent ? launch_override(DLLAVA_LAUNCH_PREFILL_BLOCKS) : 0;  // tests: few blocks, many items each
+  if (a.key_words) {
+    const int64_t slots = forced ? forced : (persistent ? resident_blocks<DH, NWQ, true>() : items);
+    const dim3 grid(static_cast<unsigned>(items < slots ? items : slots));
+    hipLaunchKernelGGL((prefill_mfma_kernel<DH, NWQ, true>), grid, dim3(NWQ * kWave), 0, st, a, static_cast<int>(items));
+  } else {
+    const int64_t slots = forced ? forced : (persistent ? resident_blocks<DH, NWQ, false>() : items);
+    const dim3 grid(static_cast<unsigned>(items < slots ? items : slots));
+    hipLaunchKernelGGL((prefill_mfma_kernel<DH, NWQ, false>), grid, dim3(NWQ * kWave), 0, st, a, static_cast<int>(items));
+  }
   DLLAVA_CHECK_LAUNCH("prefill_mfma_kernel");
   return DLLAVA_OK;
 }

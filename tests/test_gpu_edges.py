@@ -237,6 +237,56 @@ def test_prefill_block_numbering(B, Dh, lens, from_cache):
     _assert_out_close(h.as_f64(O), ref, w.dtype, f"prefill numbering B={B} Dh={Dh}")
 
 
+@pytest.mark.parametrize("blocks", [1, 3, 7])
+@pytest.mark.parametrize("waves", [1, 2, 4])
+@pytest.mark.parametrize("from_cache", [False, True])
+def test_prefill_persistent_blocks_walk_many_items(blocks, waves, from_cache):
+    """The blocks of the matrix-core prefill kernel are persistent: each takes every `blocks`-th work item and streams
+    their key tiles across the item boundaries (tile loads two tiles ahead, the next item's queries requested during
+    the current item's last tile, outputs stored one tile late).  With 1, 3 or 7 blocks forced, every block walks
+    many items of all lengths: one-tile items, an empty sequence, sequences that end inside a tile."""
+    h = _H()
+    lens = [300, 1, 129, 0, 257, 40, 128, 33, 64, 5]
+    P.dllava_set_launch_override(P.LAUNCH_PREFILL_BLOCKS, blocks)
+    P.dllava_set_launch_override(P.LAUNCH_PREFILL_WAVES, waves)
+    try:
+        w = W.make("persistent", "bf16", 384, 3, 128, len(lens), 0, lens, 0, 1.0, 0)
+        pre = W.prefill_inputs(w)
+        g = h.GpuPath(w, pre, None)
+        D = rng.normal(w.seed, "w.D", (int(sum(w.n_vis)), 2)).astype(np.float32)
+        out = g.select_compact(torch.from_numpy(D).to(h.DEV), with_hidden=False)
+        off = np.asarray(w.seq_off, np.int32)
+        ref = R.prefill_attn(pre["Q"], pre["K"], pre["V"], off, g.scale, w.dtype)
+        Qc = out["Q_out"].contiguous()
+        O = g.prefill(Qc, out["out_off"]) if from_cache else g.prefill(Qc, out["out_off"], g.pre["K"], g.pre["V"])
+        again = g.prefill(Qc, out["out_off"]) if from_cache else g.prefill(Qc, out["out_off"], g.pre["K"], g.pre["V"])
+    finally:
+        P.dllava_set_launch_override(P.LAUNCH_PREFILL_BLOCKS, 0)
+        P.dllava_set_launch_override(P.LAUNCH_PREFILL_WAVES, 0)
+    _assert_out_close(h.as_f64(O), ref, w.dtype, f"prefill {blocks} blocks, {waves} waves")
+    assert torch.equal(O.view(torch.int16), again.view(torch.int16))
+
+
+def test_prefill_long_sequences_from_pages():
+    """Sequences of more than 1024 keys (more than 64 pages each) read from the paged cache: the result must equal, bit
+    for bit, the one computed from plain K/V rows, and match the oracle (the context a decoding step without KV cache
+    reaches: reduced prompt plus a thousand generated tokens)."""
+    h = _H()
+    lens = [1238, 1030, 70]
+    w = W.make("longpaged", "bf16", 256, 2, 128, len(lens), 0, lens, 0, 1.0, 0)
+    pre = W.prefill_inputs(w)
+    g = h.GpuPath(w, pre, None)
+    D = rng.normal(w.seed, "w.D", (int(sum(w.n_vis)), 2)).astype(np.float32)
+    out = g.select_compact(torch.from_numpy(D).to(h.DEV), with_hidden=False)
+    off = np.asarray(w.seq_off, np.int32)
+    Qc = out["Q_out"].contiguous()
+    O_pages = g.prefill(Qc, out["out_off"])
+    O_rows = g.prefill(Qc, out["out_off"], g.pre["K"], g.pre["V"])
+    assert torch.equal(O_pages.view(torch.int16), O_rows.view(torch.int16))
+    ref = R.prefill_attn(pre["Q"], pre["K"], pre["V"], off, g.scale, w.dtype)
+    _assert_out_close(h.as_f64(O_pages), ref, w.dtype, "long sequences from pages")
+
+
 @pytest.mark.parametrize("theta", [0.0, 0.4, float("inf"), float("-inf")])
 def test_decode_step_without_kv_cache(theta):
     """Decoding without KV cache (Sec. 3.3.2, Eq. 12): every sequence is its reduced prompt followed by all output
