@@ -330,43 +330,94 @@ def timed_events(torch, fn, n=1):
     return a.elapsed_time(b) / n  # ms
 
 
-def cpu_baseline(path, seconds):
-    """The oracle, as it stands, on a bounded sample of the same workload (host cores of this machine)."""
-    import psutil
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def _oracle_pass(path, seconds, L_t):
+    """One timing pass of the oracle over a bounded sample of the workload; seconds per stage, scaled to the whole step.
+
+    Sample: the prefill stages on the first nb sequences (scaled by B / nb); the decode loop on those sequences at every
+    `stride`-th step with the cache set to the EXACT length the step has in the timed run (L_t, from the GPU run's keep
+    decisions; the oracle's cost depends on the lengths only), scaled by the sum of L_t over all steps."""
     from oracle import dllava_ref as R
-    from synth import workloads as W
     w, host = path.w, path.host
     pre, dec, pred = host["pre"], host["dec"], host["pred"]
-    nb = min(w.B, 2)                                   # sample: the first nb sequences of the batch
-    proc = psutil.Process()
-    c0, t0 = proc.cpu_times(), time.perf_counter()
+    nb = min(w.B, 2)
+    st = {}
+    t0 = time.perf_counter()
     r1 = int(w.seq_off[nb])
     rows = np.concatenate([np.arange(w.seq_off[b] + w.n_sys[b], w.seq_off[b] + w.n_sys[b] + w.n_vis[b]) for b in range(nb)])
     D = R.score(pre["hidden"][rows], pred["W1"], pred["b1"], pred["W2"], pred["b2"], w.dtype)
+    t1 = time.perf_counter()
     mask, idx, off = R.select(D, w.seq_off[:nb + 1], w.vis_start[:nb], w.vis_len[:nb], R.TOPK, w.keep_ratio, 0.0)
+    t2 = time.perf_counter()
     cache = R.PagedCache(path.pages.shape[0], path.bt_np[:nb], w.H, w.Dh, w.dtype)
     _, Qc = R.compact(idx, off, w.seq_off[:nb + 1], hidden=pre["hidden"][:r1], Q=pre["Q"][:r1], K=pre["K"][:r1],
                       V=pre["V"][:r1], cache=cache)
+    t3 = time.perf_counter()
     src = np.concatenate([w.seq_off[b] + idx[off[b]:off[b + 1]] for b in range(nb)])
     R.prefill_attn(Qc, pre["K"][src], pre["V"][src], off, path.scale, w.dtype)
-    t_pre = time.perf_counter() - t0
-    steps = 0
-    while steps < w.T and (steps < 4 or time.perf_counter() - t0 < seconds):
-        t = steps
+    t4 = time.perf_counter()
+    scale_pre = w.B / nb
+    st["score_vision"] = (t1 - t0) * scale_pre
+    st["select"] = (t2 - t1) * scale_pre
+    st["compact"] = (t3 - t2) * scale_pre
+    st["prefill_attn"] = (t4 - t3) * scale_pre
+    # decode: the cache pages hold the prefill rows, the slots beyond them zeros (the oracle's cost does not depend on
+    # the values); the lengths are set per sampled step
+    T = w.T
+    stride = max(1, T // 16)
+    budget = max(1.0, seconds - (t4 - t0))
+    t_score = t_attn = 0.0
+    sampled, sum_L_sampled = [], 0
+    for t in list(range(0, T, stride)):
+        if sampled and t_score + t_attn > budget:
+            break
+        a0 = time.perf_counter()
         Dt = R.score(dec["x"][t, :nb], pred["W1"], pred["b1"], pred["W2"], pred["b2"], w.dtype)
         keep = R.decode_keep(Dt, w.theta)
+        a1 = time.perf_counter()
+        cache.cache_len[...] = L_t[t, :nb]
         R.decode_attn_append(dec["q"][t, :nb], dec["k"][t, :nb], dec["v"][t, :nb], keep, cache, path.scale)
-        steps += 1
-    wall = time.perf_counter() - t0
-    c1 = proc.cpu_times()
-    cpu = (c1.user + c1.system) - (c0.user + c0.system)
-    # scale the sample to a whole step of the workload: prefill cost is per sequence, decode cost per token
-    t_dec_tok = (wall - t_pre) / (steps * nb)
-    est_step = t_pre / nb * w.B + t_dec_tok * w.B * w.T
-    return {"value": (w.B * w.T) / est_step, "unit": "tokens/s", "cores": max(1, int(round(cpu / wall))),
-            "kind": "oracle",
-            "sample": f"first {nb} of {w.B} sequences: full prefill path + first {steps} of {w.T} decode steps "
-                      f"({wall:.1f} s wall), extrapolated per sequence / per token to the whole step"}
+        a2 = time.perf_counter()
+        t_score += a1 - a0
+        t_attn += a2 - a1
+        sampled.append(t)
+        sum_L_sampled += int(L_t[t, :nb].sum())
+    st["decode_score"] = t_score / (len(sampled) * nb) * (w.B * T)            # per row
+    st["decode_attn_append"] = t_attn / max(1, sum_L_sampled) * float(L_t.sum())  # per cached token attended
+    st["_sample"] = (nb, len(sampled), stride)
+    return st
+
+
+def cpu_baseline(path, seconds, L_t):
+    """The oracle, as it stands, timed per stage on a bounded sample of the same workload on this machine's host cores:
+    one pass limited to ONE thread, one on all cores (the oracle is numpy: its threads are the BLAS pool's)."""
+    from threadpoolctl import threadpool_info, threadpool_limits
+    w = path.w
+    with threadpool_limits(limits=1):
+        one = _oracle_pass(path, seconds, L_t)
+    allc = _oracle_pass(path, seconds, L_t)
+    threads = max([int(i.get("num_threads", 1)) for i in threadpool_info()] or [1])
+    nb, n_steps, stride = allc.pop("_sample")
+    one.pop("_sample")
+    total_all, total_one = sum(allc.values()), sum(one.values())
+    return {"value": (w.B * w.T) / total_all, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {nb} of {w.B} sequences: all prefill stages (scaled by {w.B}/{nb}); decode at every {stride}th of "
+                      f"{w.T} steps ({n_steps} steps) with the cache at the exact length of that step, scoring scaled per row, "
+                      f"attention scaled by cached tokens attended; float64 numpy",
+            "cpu_model": _cpu_model(), "nproc": os.cpu_count(),
+            "all_cores": {"threads": threads, "stage_seconds": allc, "step_seconds": total_all,
+                          "tokens_per_s": (w.B * w.T) / total_all},
+            "one_thread": {"threads": 1, "stage_seconds": one, "step_seconds": total_one,
+                           "tokens_per_s": (w.B * w.T) / total_one}}
 
 
 def pmc_probe(path, torch, L):
@@ -436,24 +487,11 @@ def pmc_probe(path, torch, L):
                       "compact_algorithmic_bytes": 2 * rows * (2 * w.d + 6 * w.H * w.Dh) * es // 2}))
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by sequence, or by head, with no exchange "
-              "between GPUs, so N GPUs would run N independent copies of this benchmark); run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    import torch
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    import paper_2412_00876_amd as P
-    from synth import workloads as W
-
-    ci = int(args.workload[1]) - 1
+def run_workload(ci, args, torch, P, W, light=False):
+    """Times the whole step and its stages on workload ci.  light: the timed step and the stages of the path only."""
     w = W.config(ci)
     if args.decode_steps:
         w.T = args.decode_steps
-    torch.cuda.set_device(0)
     path = Path(w, torch, P, W)
     path.two_launch = args.two_launch_decode
     B, T, H, Dh = w.B, w.T, w.H, w.Dh
@@ -463,7 +501,7 @@ def main():
     graph = None
     if args.pmc_probe:
         pmc_probe(path, torch, args.pmc_probe)
-        return
+        return None
     path.calibrate_theta()
     with torch.cuda.stream(stream):
         path.step()                                     # eager once: validates arguments, warms caches
@@ -516,11 +554,14 @@ def main():
         path.qkv_project()                                              # (weights to the device, outside the graph)
         ms_qkv = stage_ms(lambda i: path.qkv_project(), 3)              # overwrites Q_out and the pages ...
         ms_select = stage_ms(lambda i: path.select_compact(), 5)       # ... which this restores
-        nc = NoCacheStep(path)
-        ms_nc = stage_ms(lambda i: nc.run(), 3)
-        nc_kept = [int(v) for v in (nc.out_off[1:] - nc.out_off[:-1]).tolist()]
+        extras = not light and not args.no_extras
+        nc = ms_nc = nc_kept = None
+        if extras:
+            nc = NoCacheStep(path)
+            ms_nc = stage_ms(lambda i: nc.run(), 3)
+            nc_kept = [int(v) for v in (nc.out_off[1:] - nc.out_off[:-1]).tolist()]
         ms_pp_image = ms_pp_text = None
-        if w.dtype == "bf16":
+        if extras and w.dtype == "bf16":
             pp = PaperPredictors(path, W)
             ms_pp_image = stage_ms(lambda i: pp.run_image(), 3)
             ms_pp_text = stage_ms(pp.run_text, min(T, 64))
@@ -544,14 +585,14 @@ def main():
                 stream.wait_stream(side)          # the next step's attention needs these logits
             ms_pp_par = stage_ms(par_loop, Tp, before=path.select_compact)
         ms_masked = None
-        if w.dtype == "bf16":   # the training form of the same attention (Eq. 7): full token set, mask inside the softmax
+        if extras and w.dtype == "bf16":   # the training form of the same attention (Eq. 7): full token set, mask inside the softmax
             O_full = torch.zeros_like(path.pre["Q"])
             ws_m = torch.zeros(P.dllava_masked_attn_workspace(w.sumN, B), dtype=torch.uint8, device="cuda:0")
             ms_masked = stage_ms(lambda i: P.dllava_masked_attn(path.pre["Q"], path.pre["K"], path.pre["V"], B, path.seq_off,
                                                                 w.sumN, H, Dh, path.scale, path.keep_mask, O_full, path.code,
                                                                 ws_m), 3)
         stack = None
-        if w.dtype == "bf16" and not args.no_stack:
+        if not light and w.dtype == "bf16" and args.stack:
             # Prefill through 8 LLaMA-family decoder layers of this shape (random weights, feed-forward width 2.6875 d)
             # with the one-time token reduction after layer 2 (Sec. 3.3), against the same 8 layers without reduction
             from paper_2412_00876_amd.layers import DecoderStack
@@ -603,9 +644,11 @@ def main():
             stack["kv_gb_after_decode"] = kv_dec
             del wts
         ms_prefill = stage_ms(lambda i: path.prefill_attn(), 5)
-        ms_sd = stage_ms(path.score_decode, T)                          # logits of all steps: inputs of the next line
-        ms_da = stage_ms(path.decode_attn, T, before=path.select_compact)  # cache reset, then T attention launches
-        assert np.array_equal(path.keep_dec.cpu().numpy(), keep), "decode replay diverged from the timed run"
+        ms_sd = ms_da = None
+        if extras or args.two_launch_decode:
+            ms_sd = stage_ms(path.score_decode, T)                          # logits of all steps: inputs of the next line
+            ms_da = stage_ms(path.decode_attn, T, before=path.select_compact)  # cache reset, then T attention launches
+            assert np.array_equal(path.keep_dec.cpu().numpy(), keep), "decode replay diverged from the timed run"
         ms_ds = stage_ms(path.decode_step, T, before=path.select_compact)  # cache reset, then T one-launch steps
 
     tokens = B * T
@@ -613,7 +656,7 @@ def main():
     # dominant kernel: the decode launch.  Algorithmic bytes per launch: the cached K+V of every sequence, and for the
     # one-launch step also what its scoring half must read once (W1 and the B hidden rows).
     pred_bytes = (w.d * w.dh + B * w.d) * es
-    if args.two_launch_decode:
+    if args.two_launch_decode and ms_da is not None:
         kernel_name, avg_ms, avg_bytes = "decode_attn_kernel (dllava_decode_attn_append)", float(ms_da), float(kv_bytes_t.mean())
         traffic_factor = DECODE_TRAFFIC_PER_ALGORITHMIC_BYTE
     else:
@@ -634,8 +677,9 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: LLaVA-1.5-7B shape x batch {B}: prefill {w.n_sys[0]}|{w.n_vis[0]}|{w.n_prompt[0]} "
                                f"tokens -> {w.kept_len[0]} kept (r={w.keep_ratio}), {T} decode steps, 16-token pages"
-                               if ci == 2 else w.name,
-                   "B": B, "H": H, "Dh": Dh, "d": w.d, "decode_steps": T, "hip_graph": graph is not None,
+                               if ci == 2 else f"{w.name}: {B} sequences, prefill {w.n_sys[0]}|{w.n_vis[0]}|{w.n_prompt[0]} tokens -> "
+                               f"{w.kept_len[0]} kept (r={w.keep_ratio}), {T} decode steps, H={H}, d={w.d}",
+                   "decode_steps": T, "hip_graph": graph is not None,
                    "text_keep_fraction": float(keep.mean()), "theta": w.theta},
         "roofline": {"kernel": kernel_name, "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -655,7 +699,7 @@ def main():
                             "flops_dense_counterfactual": 2.0 * w.sumN * w.d * 3 * H * Dh},
             # the paper's other decoding mode, also outside the timed step: one step without KV cache at the end of
             # the generation (re-mask all output tokens, compact, causal attention over prompt* + kept outputs)
-            "decode_step_without_cache": {"ms": ms_nc, "rows_in": nc.sumN, "rows_kept": int(sum(nc_kept)),
+            "decode_step_without_cache": None if ms_nc is None else {"ms": ms_nc, "rows_in": nc.sumN, "rows_kept": int(sum(nc_kept)),
                                           "attn_tflops": sum(4.0 * H * Dh * n * (n + 1) / 2 for n in nc_kept) / (ms_nc * 1e-3) / 1e12,
                                           "attn_flops_dense_counterfactual": float(sum(4.0 * H * Dh * n * (n + 1) / 2
                                                                                        for n in (np.asarray(w.seq_len) + T)))},
@@ -682,14 +726,60 @@ def main():
                 int(np.sum(w.kept_len)) + int(keep.sum())),
             "decode_step": {"avg_us": float(ms_ds * 1e3), "gbs": (float(kv_bytes_t.mean()) + pred_bytes) / (ms_ds * 1e-3) / 1e9,
                             "note": "one launch per step: scoring + attention, append deferred by one step"},
-            "decode_score": {"avg_us": float(ms_sd * 1e3)},
-            "decode_attn": {"avg_us": float(ms_da * 1e3), "gbs": float(kv_bytes_t.mean()) / (ms_da * 1e-3) / 1e9,
-                            "kv_mb_first_step": float(kv_bytes_t[0] / 1e6), "kv_mb_last_step": float(kv_bytes_t[-1] / 1e6)},
+            "decode_score": None if ms_sd is None else {"avg_us": float(ms_sd * 1e3)},
+            "decode_attn": None if ms_da is None else {"avg_us": float(ms_da * 1e3), "gbs": float(kv_bytes_t.mean()) / (ms_da * 1e-3) / 1e9},
+            "kv_mb_first_step": float(kv_bytes_t[0] / 1e6), "kv_mb_last_step": float(kv_bytes_t[-1] / 1e6),
             "kv_bytes_total": float(kv_bytes_t.sum()), "kv_bytes_dense_counterfactual": float(dense_L.sum()),
         },
         "input_generation_s": path.gen_seconds,
     }
-    if ci == 2 and not args.decode_steps:
+    out["_L_t"] = L_t
+    out["_path"] = path
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by sequence, or by head, with no exchange "
+              "between GPUs, so N GPUs would run N independent copies of this benchmark); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    import paper_2412_00876_amd as P
+    from synth import workloads as W
+
+    torch.cuda.set_device(0)
+    ci = int(args.workload[1]) - 1
+    out = run_workload(ci, args, torch, P, W)
+    if out is None:
+        return
+    L_t, path = out.pop("_L_t"), out.pop("_path")
+    w = path.w
+    stream = torch.cuda.Stream()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(path, args.cpu_seconds, L_t)
+    del path
+    torch.cuda.empty_cache()
+    if ci == 2 and not args.decode_steps and not args.no_other_workloads:
+        # The same step and its stages on the workloads where the matrix-core and compaction stages have their largest
+        # shapes (13B: 32 sequences; high resolution: 2880 vision tokens per sequence), each on the driver's clock too.
+        for name, cj in (("c4", 3), ("c5", 4)):
+            r = run_workload(cj, args, torch, P, W, light=True)
+            r.pop("_L_t")
+            r.pop("_path")
+            torch.cuda.empty_cache()
+            st = r["stages"]
+            out[name] = {"workload": r["config"]["workload"], "tokens_per_s": r["value"], "ms_per_step": r["ms_per_step"],
+                         "text_keep_fraction": r["config"]["text_keep_fraction"],
+                         "decode_step": {"avg_us": r["roofline"]["avg_launch_us"], "gbs": r["roofline"]["achieved"],
+                                         "frac_hbm_peak": r["roofline"]["frac"],
+                                         "avg_bytes_per_launch": r["roofline"]["avg_bytes_per_launch"]},
+                         "score_vision": st["score_vision"], "select_compact": st["select_compact"],
+                         "prefill_attn": st["prefill_attn"], "qkv_project": st["qkv_project"]}
+    if ci == 2 and not args.decode_steps and not args.no_other_workloads:
         # The same step on the batch-1 prompt this workload batches (configs[1]: 35 | 576 | 64 tokens, 256 decode steps):
         # 3.5-5.6 MB of K/V per decode launch, so every launch is latency, not bandwidth.  Reported beside the headline.
         w1 = W.config(1)
@@ -711,8 +801,6 @@ def main():
             ms1 = (time.perf_counter() - t0) * 1e3 / 20
         out["batch_1"] = {"workload": w1.name, "tokens_per_s": w1.B * w1.T / (ms1 * 1e-3), "ms_per_step": ms1,
                           "decode_steps": w1.T, "us_per_decode_step": (ms1 * 1e3) / w1.T}
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(path, args.cpu_seconds)
     print(json.dumps(out))
 
 
