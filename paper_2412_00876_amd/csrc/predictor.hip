@@ -74,6 +74,10 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
   if (static_cast<int64_t>(mt) * 128 >= M) return;
 
   const int lc = tid & 7, lr = tid >> 3;
+  static_assert(sizeof(SpanTable) <= sizeof(sAB), "the span table borrows the tiles' memory");
+  SpanTable* spans = reinterpret_cast<SpanTable*>(sAB);
+  const bool use_table = a.seq_off != nullptr && a.B > 0 && a.B <= kSpanLdsMax;
+  if (use_table) span_table_build<kGThreads>(spans, a.seq_off, a.vis_start, a.vis_len, a.B);
   const bf16_t *ga[4], *gb[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -82,10 +86,11 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
     ga[j] = a.W + static_cast<int64_t>(u) * K + lc * 8;
     int64_t m = static_cast<int64_t>(mt) * 128 + lr + 32 * j;
     if (m >= M) m = M - 1;
-    int64_t sr = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m);
+    int64_t sr = use_table ? span_table_row(spans, a.B, m) : score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m);
     if (sr < 0) sr = 0;
     gb[j] = a.X + sr * a.ldx + lc * 8;
   }
+  if (use_table) __syncthreads();  // the tile loads overwrite the table
   const int wu = (w >> 1) * 64, wm = (w & 1) * 64;  // this wave's 64 features x 64 tokens
   f32x16 acc[2][2];
 #pragma unroll

@@ -58,6 +58,11 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
 
   // staging thread: 16-byte chunk lc of rows lr + 32*j of both tiles (see gemm_tile.h)
   const int lc = tid & 7, lr = tid >> 3;
+  static_assert(sizeof(SpanTable) <= sizeof(sA), "the span table borrows the W1 tile's memory");
+  SpanTable* spans = reinterpret_cast<SpanTable*>(sA);
+  const bool use_table = a.seq_off != nullptr && a.B > 0 && a.B <= kSpanLdsMax;
+  if (use_table) span_table_build<kGThreads>(spans, a.seq_off, a.vis_start, a.vis_len, a.B);
+  const int64_t rows_in_spans = use_table ? spans->prefix[a.B] : -1;
   const bf16_t *gA0, *gA1, *gA2, *gA3, *gB0, *gB1, *gB2, *gB3;
   {
     const bf16_t* ga[4];
@@ -69,13 +74,14 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
       ga[j] = W1 + u * d + lc * 8;
       int64_t m = static_cast<int64_t>(mt) * kTM + lr + 32 * j;
       if (m >= M) m = M - 1;
-      int64_t sr = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m);
+      int64_t sr = use_table ? span_table_row(spans, a.B, m) : score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m);
       if (sr < 0) sr = 0;
       gb[j] = X + sr * a.ldx + lc * 8;
     }
     gA0 = ga[0]; gA1 = ga[1]; gA2 = ga[2]; gA3 = ga[3];
     gB0 = gb[0]; gB1 = gb[1]; gB2 = gb[2]; gB3 = gb[3];
   }
+  if (use_table) __syncthreads();  // the tile loads overwrite the table
   const int nk = static_cast<int>(d / kBK);
   const int wu = (w >> 1) * 64, wm = (w & 1) * 64;  // this wave's 64 units x 64 tokens
   f32x16 acc[2][2];
@@ -131,7 +137,8 @@ __global__ __launch_bounds__(kGThreads) __attribute__((amdgpu_waves_per_eu(3, 4)
   {
     const int tok = tid >> 1, c = tid & 1;
     const int64_t m = static_cast<int64_t>(mt) * kTM + tok;
-    if (m < M && score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m) >= 0) {
+    const bool in_spans = use_table ? m < rows_in_spans : score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m) >= 0;
+    if (m < M && in_spans) {
       float s = a.b2 ? a.b2[c] : 0.f;
       for (int t0 = 0; t0 < n_ut; t0 += 16) {  // 16 independent loads in flight, then a fixed-order sum
         float v[16];
@@ -180,15 +187,21 @@ __global__ __launch_bounds__(kRingThreads, 1) void score_ring_kernel(ScoreArgs a
     if (u >= dh) u = dh - 1;
     ga[j] = static_cast<uint32_t>(u * d * 2) + ring_load_chunk_bytes(row, lane);
   }
+  // gathered spans: the row mapping from a table in the (not yet used) ring memory
+  SpanTable* spans = reinterpret_cast<SpanTable*>(smem_raw);
+  const bool use_table = a.seq_off != nullptr && a.B > 0 && a.B <= kSpanLdsMax;
+  if (use_table) span_table_build<kRingThreads>(spans, a.seq_off, a.vis_start, a.vis_len, a.B);
+  const int64_t rows_in_spans = use_table ? spans->prefix[a.B] : -1;
 #pragma unroll
   for (int j = 0; j < JB; ++j) {
     const int row = ring_load_row(w, j, lane);
     int64_t m = static_cast<int64_t>(mt) * kTok + row;
     if (m >= M) m = M - 1;
-    int64_t sr = score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m);
+    int64_t sr = use_table ? span_table_row(spans, a.B, m) : score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m);
     if (sr < 0) sr = 0;
     gb[j] = sr * a.ldx * 2 + ring_load_chunk_bytes(row, lane);
   }
+  if (use_table) __syncthreads();  // the tile loads overwrite the table
   ring_f32x16 acc[2][JB];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -253,7 +266,8 @@ __global__ __launch_bounds__(kRingThreads, 1) void score_ring_kernel(ScoreArgs a
   for (int t = tid; t < 2 * kTok; t += kRingThreads) {
     const int tok = t >> 1, c = t & 1;
     const int64_t m = static_cast<int64_t>(mt) * kTok + tok;
-    if (m < M && score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m) >= 0) {
+    const bool in_spans = use_table ? m < rows_in_spans : score_src_row(a.seq_off, a.vis_start, a.vis_len, a.B, m) >= 0;
+    if (m < M && in_spans) {
       float s = a.b2 ? a.b2[c] : 0.f;
       for (int t0 = 0; t0 < n_ut; t0 += 8) {  // independent loads in flight, then a fixed-order sum
         float v[8];

@@ -142,6 +142,35 @@ def test_score_tiles_forced(tile, d, dh):
     assert np.abs(plain - ref_all).max() <= TOL
 
 
+@pytest.mark.parametrize("B", [300, 1024, 1100])
+@pytest.mark.parametrize("tile", [1, 4])
+def test_score_many_short_spans(B, tile):
+    """The block-level row mapping (span table in LDS): hundreds of sequences with spans of 0..9 vision tokens, so
+    one token tile gathers rows from dozens of spans, some empty; 1024 sequences fill the table exactly and 1100
+    exceed it (the per-row search serves those).  Both many-rows kernels."""
+    h = _H()
+    rs = np.random.RandomState(B)
+    n_vis = [int(v) for v in rs.randint(0, 10, size=B)]
+    n_vis[0] = 0
+    n_vis[-1] = 0
+    n_sys = [int(v) for v in rs.randint(0, 3, size=B)]
+    n_txt = [int(v) for v in rs.randint(0, 3, size=B)]
+    w = W.make("spans", "bf16", 128, 1, 128, B, n_sys, n_vis, n_txt, 1.0, 0)
+    w.dh = 320
+    pre, pred = W.prefill_inputs(w), W.predictor(w, random_bias=True)
+    g = h.GpuPath(w, pre, pred)
+    rows = np.concatenate([np.arange(w.seq_off[b] + w.n_sys[b], w.seq_off[b] + w.n_sys[b] + w.n_vis[b])
+                           for b in range(w.B)])
+    assert len(rows) > 1000
+    ref = R.score(pre["hidden"][rows], pred["W1"], pred["b1"], pred["W2"], pred["b2"], "bf16")
+    P.dllava_set_launch_override(P.LAUNCH_SCORE_TILE, tile)
+    try:
+        got = g.score_vision().cpu().numpy()
+    finally:
+        P.dllava_set_launch_override(P.LAUNCH_SCORE_TILE, 0)
+    assert np.abs(got - ref).max() <= TOL, np.abs(got - ref).max()
+
+
 @pytest.mark.parametrize("first", ["prefill", "decode"])
 def test_score_forms_share_one_workspace(first):
     """A workspace sized for the largest row count serves every smaller one: the tiled form (576 vision rows) and the
