@@ -105,6 +105,8 @@ const char* dllava_last_error(void);
  *   DLLAVA_LAUNCH_SCORE_TILE     tile of the many-rows scoring kernel: 1 = 128 units x 128 tokens, three blocks per
  *                                compute unit; 4 .. 8 = 256 units x 32*value tokens, one block per compute unit
  *   DLLAVA_LAUNCH_QKV_TILE       the same for the projection kernel of dllava_qkv_project
+ *   DLLAVA_LAUNCH_SELECT_LAUNCHES 1 = dllava_select_compact in top-k mode as one launch (selection and copies side by
+ *                                side; what it picks for up to 256 sequences), 2 = selection, then the copies
  * The library reads no environment variables.
  */
 typedef enum {
@@ -114,7 +116,8 @@ typedef enum {
   DLLAVA_LAUNCH_SCORE_TILE = 3,
   DLLAVA_LAUNCH_QKV_TILE = 4,
   DLLAVA_LAUNCH_PREFILL_BLOCKS = 5,
-  DLLAVA_LAUNCH_KNOBS = 6
+  DLLAVA_LAUNCH_SELECT_LAUNCHES = 6,
+  DLLAVA_LAUNCH_KNOBS = 7
 } dllava_launch_knob;
 int dllava_set_launch_override(int knob, int value);
 
@@ -177,6 +180,11 @@ size_t dllava_score_workspace(int64_t M, int64_t d, int64_t dh, int dtype);
  *   err_flag   device int32, may be NULL: set to 1 if some N*(b) exceeds the cache capacity
  *              max_pages_per_seq * page_size; the rows beyond capacity are then not written
  *              and cache_len[b] is clamped to the capacity.  Never cleared by the library.
+ *              (2 if a copying block gave up waiting for its sequence's selection, which no dispatch order
+ *              should produce: that row is then not written)
+ *   workspace  device memory, 256-byte aligned, at least dllava_select_compact_workspace(B, sumN) bytes,
+ *              zero-filled once by the caller before its first use: the library keeps hand-off words in it
+ *              and leaves them zero at the end of every call.  Calls that share a workspace must not overlap.
  * Output buffers hidden_out / Q_out need capacity for sum N* rows (sumN always suffices).
  * Errors: keep_ratio outside [0,1] or NaN, NaN threshold, d*sizeof(dtype) % 16 != 0.
  */

@@ -10,7 +10,8 @@ _BINDING_NAMES = ("BF16", "F32", "MODE_THRESHOLD", "MODE_THRESHOLD_KEEP_LAST", "
                   "dllava_decode_commit", "dllava_predict", "dllava_predict_workspace", "Predictor", "dllava_linear", "dllava_layer_norm",
                   "dllava_span_attn", "dllava_masked_attn", "dllava_masked_attn_workspace", "dllava_compact", "dllava_rms_norm", "dllava_linear_few", "dllava_linear_few_workspace", "dllava_rope", "dllava_qkv_few", "dllava_gated_few", "dllava_decode_proj_workspace",
                   "dllava_select_compact", "dllava_select_compact_workspace", "dllava_version", "lib",
-                  "dllava_set_launch_override", "dllava_decode_attn_append_static", "LAUNCH_DECODE_WAVES", "LAUNCH_DECODE_SPLITS", "LAUNCH_PREFILL_WAVES", "LAUNCH_SCORE_TILE", "LAUNCH_QKV_TILE", "LAUNCH_PREFILL_BLOCKS")
+                  "dllava_set_launch_override", "dllava_decode_attn_append_static", "LAUNCH_DECODE_WAVES", "LAUNCH_DECODE_SPLITS", "LAUNCH_PREFILL_WAVES", "LAUNCH_SCORE_TILE", "LAUNCH_QKV_TILE", "LAUNCH_PREFILL_BLOCKS",
+                  "LAUNCH_SELECT_LAUNCHES")
 
 
 def __getattr__(name):

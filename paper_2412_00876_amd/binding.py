@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 F32, BF16 = 0, 1
 MODE_TOPK, MODE_THRESHOLD, MODE_THRESHOLD_KEEP_LAST = 0, 1, 2
 LAUNCH_DECODE_WAVES, LAUNCH_DECODE_SPLITS, LAUNCH_PREFILL_WAVES, LAUNCH_SCORE_TILE, LAUNCH_QKV_TILE, LAUNCH_PREFILL_BLOCKS = 0, 1, 2, 3, 4, 5
+LAUNCH_SELECT_LAUNCHES = 6
 PAGE_SIZE = 16
 
 

@@ -12,6 +12,7 @@ import torch
 
 pytestmark = pytest.mark.gpu
 
+import paper_2412_00876_amd as P
 from oracle import dllava_ref as R
 from synth import rng
 from synth import workloads as W
@@ -140,6 +141,48 @@ def test_select_large_and_degenerate_segments(n_vis, ratio):
     D = np.round(D * 64) / 64
     _check_select_compact(g, w, pre, D, R.TOPK, ratio, 0.0)
     _check_select_compact(g, w, pre, D, R.THRESHOLD, ratio, 0.1)
+
+
+@pytest.mark.parametrize("launches", [1, 2])
+def test_select_compact_arrangements(launches):
+    """Both arrangements of the top-k path forced on the same inputs (selection and copies in one launch, or one
+    after the other), many calls in a row on one workspace: a span longer than the one-launch selection holds in
+    registers, ragged and empty spans, every ratio from nothing to everything, ties."""
+    h = _H()
+    w = W.make("arr", "bf16", 128, 2, 64, 5, [3, 0, 0, 1, 2], [300, 4200, 0, 17, 513], [30, 2, 5, 0, 9], 0.2, 0)
+    pre = W.prefill_inputs(w)
+    g = h.GpuPath(w, pre, None, extra_tokens=max(w.seq_len))
+    D = rng.normal(launches, "arr.D", (int(sum(w.n_vis)), 2)).astype(np.float32)
+    Dt = np.round(D * 2) / 2
+    P.dllava_set_launch_override(P.LAUNCH_SELECT_LAUNCHES, launches)
+    try:
+        for ratio in (0.2, 0.0, 1.0, 0.5, 0.013, 0.999):
+            _check_select_compact(g, w, pre, D, R.TOPK, ratio, 0.0)
+            _check_select_compact(g, w, pre, Dt, R.TOPK, ratio, 0.0)
+    finally:
+        P.dllava_set_launch_override(P.LAUNCH_SELECT_LAUNCHES, 0)
+
+
+@pytest.mark.parametrize("B", [255, 256, 257, 300])
+def test_select_compact_many_sequences(B):
+    """Top-k over more and fewer sequences than the arrangement with analytic offsets takes (256): short ragged
+    sequences, spans anywhere in them (none, at the start, at the end, the whole sequence), ties among the scores."""
+    h = _H()
+    rs = np.random.RandomState(B)
+    n_sys = [int(v) for v in rs.randint(0, 4, size=B)]
+    n_vis = [int(v) for v in rs.randint(0, 23, size=B)]
+    n_txt = [int(v) for v in rs.randint(0, 4, size=B)]
+    n_sys[0], n_vis[0], n_txt[0] = 0, 0, 0            # an empty sequence first
+    n_sys[1], n_txt[1] = 0, 0                         # a sequence that is all vision tokens
+    n_vis[-1] = 0                                     # the last one keeps everything it has
+    w = W.make("manyseq", "bf16", 64, 1, 64, B, n_sys, n_vis, n_txt, 0.3, 0)
+    pre = W.prefill_inputs(w)
+    g = h.GpuPath(w, pre, None, extra_tokens=32)     # room for every row at ratio 1
+    D = rng.normal(B, "many.D", (int(sum(w.n_vis)), 2)).astype(np.float32)
+    D = np.round(D * 4) / 4
+    for ratio in (0.3, 0.0, 1.0, 0.77):
+        _check_select_compact(g, w, pre, D, R.TOPK, ratio, 0.0)
+    _check_select_compact(g, w, pre, D, R.THRESHOLD, 0.5, 0.1)
 
 
 def test_compact_capacity_overflow_is_flagged_not_written():
