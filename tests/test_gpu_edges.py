@@ -99,6 +99,10 @@ def test_decode_launch_shapes_forced(waves, splits):
         test_decode_shapes_and_ragged_lengths(3, 5, 128)
         w = W.make("forced", "bf16", 256, 3, 128, 5, [70, 1, 16, 0, 33], 0, 0, 1.0, 6, project_qkv=True)
         _run(w, 6, 0.0, use_override=True)
+        if splits <= 2:   # long caches: every wave walks several pages with ragged ends, both head sizes
+            for Dh in (128, 64):
+                w = W.make("forcedlong", "bf16", 256, 2, Dh, 4, [700, 333, 64, 129], 0, 0, 1.0, 4, project_qkv=True)
+                _run(w, 4, 0.0, use_override=True)
     finally:
         P.dllava_set_launch_override(P.LAUNCH_DECODE_WAVES, 0)
         P.dllava_set_launch_override(P.LAUNCH_DECODE_SPLITS, 0)
