@@ -435,6 +435,8 @@ def pmc_probe(path, torch, L):
     dst.copy_(src)                                   # calibration dispatch: reads n bytes, writes n bytes
     torch.cuda.synchronize()
     path.score_vision(); path.select_compact()      # fills the first kept_len tokens of every sequence
+    path.qkv_project()                               # (projection of the kept rows: overwrites Q_out and the pages ...
+    path.select_compact()                            #  ... which this restores)
     path.prefill_attn()                              # (one dispatch each of the prefill kernels, for their counters)
     path.score_decode(0)
     path.pages.normal_()                             # slots beyond that: arbitrary finite data
@@ -483,6 +485,7 @@ def pmc_probe(path, torch, L):
                       "decode_algorithmic_bytes_per_launch": w.B * L * 2 * w.H * w.Dh * es,
                       "decode_step_algorithmic_bytes_per_launch": w.B * L * 2 * w.H * w.Dh * es + (w.d * w.dh + w.B * w.d) * es,
                       "score_vision_flops": 2.0 * path.M_vis * w.d * w.dh,
+                      "qkv_project_flops": 2.0 * rows * w.d * 3 * w.H * w.Dh,
                       "prefill_attn_flops": float(sum(4.0 * w.H * w.Dh * m * (m + 1) / 2 for m in n_kept)),
                       "compact_algorithmic_bytes": 2 * rows * (2 * w.d + 6 * w.H * w.Dh) * es // 2}))
 
