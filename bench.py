@@ -35,7 +35,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # HBM bytes moved per algorithmic byte by the decode kernel, from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE, each
 # scaled by its reading for a 256 MiB copy): profiles/decode_attn_c3_hbm_counters.txt
 DECODE_TRAFFIC_PER_ALGORITHMIC_BYTE = 1.027
-# the same for the one-launch step (K+V, W1 and the hidden rows): profiles/decode_step_c3_hbm_counters.txt
+# the same for the one-launch step (K+V, W1 and the hidden rows): profiles/decode_step_hbm_counters.txt
 STEP_TRAFFIC_PER_ALGORITHMIC_BYTE = 1.034
 
 
