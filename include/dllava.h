@@ -411,23 +411,44 @@ size_t dllava_predict_workspace(int64_t M, int32_t B, int32_t n_blocks);
 
 /*
  * The layers dllava_predict is made of, as calls of their own (Appendix A.4.1 names the layers; the formulas are
- * the ones stated above).  DLLAVA_BF16 only; float32 sums; each output element is rounded once.
- *
- * dllava_linear:        y = act(x W^T + bias) + residual      (act 0 = none, 1 = exact GELU), or
- *                       y = (x W^T + bias) * SiLU(residual)   (act 2: the gated unit of a SwiGLU feed-forward layer,
- *                                                              `residual` holding the gate x W_gate^T)
+ * the ones stated above), and the remaining layers of the LLaMA-family decoder the paper sparsifies.  DLLAVA_BF16
+ * only; float32 sums; each output element is rounded once.  Pointers are device pointers, 16-byte aligned.
+ */
+
+/*
+ * Linear layer:  y = act(x W^T + bias) + residual      (act 0 = none, 1 = exact GELU), or
+ *                y = (x W^T + bias) * SiLU(residual)   (act 2: the gated unit of a SwiGLU feed-forward layer,
+ *                                                       `residual` holding the gate x W_gate^T)
  *   x [M, K] row stride ldx;  W [N, K];  bias [N] float32 or NULL;
  *   residual [M, N] with y's row stride, or NULL (act 0, 1), may be y itself;  y [M, N] row stride ldy, out.
- *   Sizes: K % 64 == 0, N % 8 == 0, ldx % 8 == 0, ldy % 8 == 0; pointers 16-byte aligned.
- * dllava_layer_norm: y = (z - mean) / sqrt(var + 1e-6) * gamma + beta per row of 512 (biased variance);
- *   z, y [M, 512] contiguous;  gamma, beta [512] float32, 16-byte aligned, or NULL (1 and 0).
- * dllava_rms_norm:      y = x / sqrt(mean(x^2) + eps) * weight per row of d (the normalisation of the LLaMA-family
- *   decoder the paper sparsifies);  x [M, d] row stride ldx, y [M, d] row stride ldy;  weight [d] float32, 16-byte
- *   aligned, or NULL (= 1);  d % 8 == 0, d <= 8192.
- * dllava_span_attn:     O_i = softmax_j(scale * q_i . k_j) V over ALL rows j of the span of row i (no causal
- *   mask);  Q, K, V, O [rows, H, Dh] contiguous;  off [B+1] row offsets of the spans;  rows = host upper bound on
- *   off[B];  Dh in {64, 128}.
+ * Sizes: K % 64 == 0, N % 8 == 0, ldx % 8 == 0, ldy % 8 == 0.
  */
+int dllava_linear(const void* x, int64_t ldx, int64_t M, int64_t K, const void* W, const float* bias, int64_t N,
+                  int act, const void* residual, void* y, int64_t ldy, int dtype, void* stream);
+
+/*
+ * LayerNorm of 512-wide rows:  y = (z - mean) / sqrt(var + 1e-6) * gamma + beta per row (biased variance).
+ *   z, y [M, 512] contiguous;  gamma, beta [512] float32 or NULL (1 and 0).
+ */
+int dllava_layer_norm(const void* z, int64_t M, const float* gamma, const float* beta, void* y, int dtype,
+                         void* stream);
+
+/*
+ * RMSNorm:  y = x / sqrt(mean(x^2) + eps) * weight per row of d.
+ *   x [M, d] row stride ldx, y [M, d] row stride ldy;  weight [d] float32 or NULL (= 1);  d % 8 == 0, d <= 8192.
+ */
+int dllava_rms_norm(const void* x, int64_t ldx, int64_t M, int64_t d, const float* weight, float eps, void* y,
+                    int64_t ldy, int dtype, void* stream);
+
+/*
+ * Attention without a causal mask inside row spans (the attention of the image predictor's blocks):
+ *   O_i = softmax_j(scale * q_i . k_j) V over ALL rows j of the span of row i.
+ *   Q, K, V, O [rows, H, Dh] contiguous;  off [B+1] row offsets of the spans;  rows = host upper bound on off[B];
+ *   Dh in {64, 128}.
+ */
+int dllava_span_attn(const void* Q, const void* K, const void* V, int32_t B, const int32_t* off, int64_t rows,
+                     int32_t H, int32_t Dh, float scale, void* O, int dtype, void* stream);
+
 /*
  * Attention of the end-to-end sparsification training on the FULL token set (Sec. 3.3.3, Eq. 7): the keep mask acts
  * inside the softmax instead of removing tokens.  For sequence b, head h and row i:
@@ -447,45 +468,46 @@ int dllava_masked_attn(const void* Q, const void* K, const void* V, int32_t B, c
                        void* workspace, size_t workspace_bytes, void* stream);
 size_t dllava_masked_attn_workspace(int64_t rows, int32_t B);
 
-int dllava_linear(const void* x, int64_t ldx, int64_t M, int64_t K, const void* W, const float* bias, int64_t N,
-                  int act, const void* residual, void* y, int64_t ldy, int dtype, void* stream);
-int dllava_layer_norm(const void* z, int64_t M, const float* gamma, const float* beta, void* y, int dtype,
-                         void* stream);
 /*
- * The same linear layer for FEW rows (M <= 64: one row per sequence of a decode step), where the weight matrix is
- * the traffic: W is read once, spread over the chip (blocks of 32 output features x a part of K), in ONE launch: the
+ * dllava_linear for FEW rows (M <= 64: one row per sequence of a decode step), where the weight matrix is the
+ * traffic: W is read once, spread over the chip (blocks of 32 output features x a part of K), in ONE launch: the
  * blocks of one feature group hand their sums over through `workspace` and the last to arrive adds them in a fixed
- * order and applies bias, activation and residual.  workspace: dllava_linear_few_workspace(N, K) bytes, 256-byte
- * aligned, ZERO-FILLED once before its first use (its first 4096 bytes are counters that every call returns to
- * zero); one buffer of the largest size may serve all three few-rows entry points, calls ordered on one stream.
- * Arguments as dllava_linear; N % 32 == 0.
- * dllava_rope: rotary rotation IN PLACE of x [rows, H, Dh] at positions pos [rows] (int32), pairing and angles as in
- * dllava_qkv_project (feature i with i + Dh/2, angle pos * rope_base^(-2i/Dh)): q and k of the tokens of a decode step.
+ * order and applies bias, activation and residual.  Arguments as dllava_linear; N % 32 == 0.
+ *   workspace  dllava_linear_few_workspace(N, K) bytes, 256-byte aligned, ZERO-FILLED once before its first use (its
+ *              first 4096 bytes are counters that every call returns to zero); one buffer of the largest size may
+ *              serve all three few-rows entry points, calls ordered on one stream.
  */
 int dllava_linear_few(const void* x, int64_t ldx, int64_t M, int64_t K, const void* W, const float* bias, int64_t N,
                       int act, const void* residual, void* y, int64_t ldy, int dtype,
                       void* workspace, size_t workspace_bytes, void* stream);
 size_t dllava_linear_few_workspace(int64_t N, int64_t K);
-int dllava_rope(void* x, const int32_t* pos, int64_t rows, int32_t H, int32_t Dh, float rope_base, int dtype, void* stream);
+
 /*
- * Two fused forms of dllava_linear_few for a decode step through a decoder layer (M <= 64 rows):
- * dllava_qkv_few:   q, k, v [M, H, Dh] = x Wq^T, x Wk^T, x Wv^T with q and k rotated at pos[row] (as dllava_rope), the
- *                   three matrices [H*Dh, d] read once in one launch.
- * dllava_gated_few: y [M, F] = (x Wu^T) * SiLU(x Wg^T), the gate rounded to dtype before the SiLU (as if it had been
- *                   stored), Wg and Wu [F, d] read once in one launch.  F % 32 == 0.
- * workspace: dllava_decode_proj_workspace(N_total, d) bytes with N_total = 3*H*Dh resp. 2*F, as for dllava_linear_few.
- * Dh % 32 == 0 (a block rotates 16 features of the lower half of a head with their partners), F % 32 == 0.
+ * Rotary rotation IN PLACE of x [rows, H, Dh] at positions pos [rows] (int32), pairing and angles as in
+ * dllava_qkv_project (feature i with i + Dh/2, angle pos * rope_base^(-2i/Dh)): q and k of the tokens of a decode step.
+ */
+int dllava_rope(void* x, const int32_t* pos, int64_t rows, int32_t H, int32_t Dh, float rope_base, int dtype, void* stream);
+
+/*
+ * q, k, v [M, H, Dh] = x Wq^T, x Wk^T, x Wv^T for few rows (M <= 64) with q and k rotated at pos[row] (as dllava_rope),
+ * the three matrices [H*Dh, d] read once in one launch.  Dh % 32 == 0 (a block rotates 16 features of the lower half
+ * of a head with their partners).
+ *   workspace  dllava_decode_proj_workspace(3*H*Dh, d) bytes, as for dllava_linear_few.
  */
 int dllava_qkv_few(const void* x, int64_t ldx, int64_t M, int64_t d, const void* Wq, const void* Wk, const void* Wv,
                    int32_t H, int32_t Dh, const int32_t* pos, float rope_base, void* q, void* k, void* v, int dtype,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * y [M, F] = (x Wu^T) * SiLU(x Wg^T) for few rows (M <= 64), the gate rounded to dtype before the SiLU (as if it had
+ * been stored), Wg and Wu [F, d] read once in one launch.  F % 32 == 0.
+ *   workspace  dllava_decode_proj_workspace(2*F, d) bytes, as for dllava_linear_few.
+ */
 int dllava_gated_few(const void* x, int64_t ldx, int64_t M, int64_t d, const void* Wg, const void* Wu, int64_t F,
                      void* y, int64_t ldy, int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace bytes of dllava_qkv_few (N_total = 3*H*Dh) and dllava_gated_few (N_total = 2*F).  Host, pure. */
 size_t dllava_decode_proj_workspace(int64_t N_total, int64_t K);
-int dllava_rms_norm(const void* x, int64_t ldx, int64_t M, int64_t d, const float* weight, float eps, void* y,
-                    int64_t ldy, int dtype, void* stream);
-int dllava_span_attn(const void* Q, const void* K, const void* V, int32_t B, const int32_t* off, int64_t rows,
-                     int32_t H, int32_t Dh, float scale, void* O, int dtype, void* stream);
 
 #ifdef __cplusplus
 }
