@@ -184,7 +184,9 @@ size_t dllava_score_workspace(int64_t M, int64_t d, int64_t dh, int dtype);
  *              should produce: that row is then not written)
  *   workspace  device memory, 256-byte aligned, at least dllava_select_compact_workspace(B, sumN) bytes,
  *              zero-filled once by the caller before its first use: the library keeps hand-off words in it
- *              and leaves them zero at the end of every call.  Calls that share a workspace must not overlap.
+ *              (at fixed offsets from its start) and leaves them zero at the end of every call, so one buffer
+ *              sized for the largest (B, sumN) serves calls of smaller shapes too.  Calls that share a workspace
+ *              must not overlap.
  * Output buffers hidden_out / Q_out need capacity for sum N* rows (sumN always suffices).
  * Errors: keep_ratio outside [0,1] or NaN, NaN threshold, d*sizeof(dtype) % 16 != 0.
  */

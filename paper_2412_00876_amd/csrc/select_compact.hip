@@ -621,7 +621,7 @@ __device__ __forceinline__ RowPlace place_row(const Layout& L, int B, int r) {
 }
 
 constexpr int kHeadStart = 48;       // s_sleep units (64 clocks) the first copying blocks pause before their loads
-constexpr int kDoneGroup = 16;       // copying blocks that share a completion counter
+constexpr int kDoneStripes = 16;     // completion counters per sequence (the copy of kept row q bumps counter q % 16)
 constexpr int kPatience = 1 << 12;   // polls of a ready word (a few milliseconds) before a block looks for itself
 constexpr int kSpinLimit = 1 << 18;  // polls before it gives up (over a tenth of a second)
 
@@ -636,8 +636,11 @@ constexpr int kSpinLimit = 1 << 18;  // polls before it gives up (over a tenth o
 // block that is already running and that waits for nothing itself: the waits end under any dispatch order.
 // The words are cleared for the next call by the last block that needs them, found by counting -- in two levels,
 // because a hundred blocks bumping one word would queue up on it (measured: atomics on one address complete at
-// about 20 per microsecond): the copies of 16 consecutive kept rows share a counter, the last of each group and
-// the sequence's selection block bump done[b], and the last of those clears claim[b], ready[b] and done[b].
+// about 20 per microsecond): the copy of a sequence's q-th kept row bumps the sequence's counter q % 16 (how many
+// rows share it follows from k), the last block on each of those and the sequence's selection block bump done[b],
+// and the last of those clears claim[b], ready[b] and done[b].  All of these words sit at fixed offsets at the
+// start of the workspace, whatever the call's shape: a workspace serves calls of different shapes in turn, and a
+// word that one shape expects to be zero must never lie where another shape keeps data.
 __global__ __launch_bounds__(kThreads) void select_compact_topk_kernel(SelectArgs a, GatherArgs g, int rest_blocks) {
   union Shared {
     TopkShared sel;
@@ -650,7 +653,7 @@ __global__ __launch_bounds__(kThreads) void select_compact_topk_kernel(SelectArg
   int32_t* claim = a.ws_sync;
   int32_t* ready = claim + kLayoutSeqs;
   int32_t* done = ready + kLayoutSeqs;
-  int32_t* group_done = done + kLayoutSeqs;
+  int32_t* stripe_done = done + kLayoutSeqs;  // [kLayoutSeqs][kDoneStripes]
 
   int b, k;  // the sequence whose hand-off this block takes part in, and its number of kept vision rows
   RowPlace place{};
@@ -717,14 +720,13 @@ __global__ __launch_bounds__(kThreads) void select_compact_topk_kernel(SelectArg
   if (tid == 0) {
     bool last_of_group = true;
     if (copies) {
-      const int gq = place.q / kDoneGroup;
-      const int members = k - gq * kDoneGroup < kDoneGroup ? k - gq * kDoneGroup : kDoneGroup;
-      // groups of sequence b: from (rows of earlier sequences) / 16 + b on, which keeps the sequences' ranges apart
-      int32_t* cnt = &group_done[place.first / kDoneGroup + b + gq];
+      const int stripe = place.q % kDoneStripes;
+      const int members = (k - 1 - stripe) / kDoneStripes + 1;  // rows q < k with q % 16 == stripe (q itself is one)
+      int32_t* cnt = &stripe_done[b * kDoneStripes + stripe];
       last_of_group = add_agent(cnt, 1) == members - 1;
       if (last_of_group) zero_agent(cnt);
     }
-    const int groups = (k + kDoneGroup - 1) / kDoneGroup;
+    const int groups = k < kDoneStripes ? k : kDoneStripes;  // stripes that have rows
     if (last_of_group && add_agent(&done[b], 1) == groups) {
       zero_agent(&claim[b]);
       zero_agent(&ready[b]);
@@ -738,14 +740,16 @@ __global__ __launch_bounds__(kThreads) void select_compact_topk_kernel(SelectArg
 
 using namespace dllava;
 
-// hand-off words of the top-k arrangement: claim / ready / done per sequence, then one counter per group of kept rows
-static size_t sync_bytes(size_t sumN) {
-  return round_up((3 * kLayoutSeqs + sumN / kDoneGroup + kLayoutSeqs + 1) * sizeof(int32_t), 256);
-}
+// Workspace layout: [words that are zero between calls, at fixed offsets | per-sequence counts | kept positions].
+// The fixed part: the ticket of select_kernel (256 bytes of its own), then claim / ready / done per sequence and
+// the stripe counters of the one-launch arrangement.
+static constexpr size_t kTicketBytes = 256;
+static constexpr size_t kSyncWords = 3 * kLayoutSeqs + kLayoutSeqs * kDoneStripes;
+static constexpr size_t kFixedBytes = (kTicketBytes + kSyncWords * sizeof(int32_t) + 255) / 256 * 256;
 
 extern "C" size_t dllava_select_compact_workspace(int32_t B, int64_t sumN) {
   const size_t b = B > 0 ? B : 0, n = sumN > 0 ? sumN : 0;
-  return round_up(n * sizeof(int32_t), 256) + round_up(b * sizeof(int32_t), 256) + 256 + sync_bytes(n);
+  return kFixedBytes + round_up(b * sizeof(int32_t), 256) + round_up(n * sizeof(int32_t), 256);
 }
 
 extern "C" int dllava_select_compact(const float* logits, int32_t B, const int32_t* seq_off,
@@ -794,12 +798,11 @@ extern "C" int dllava_select_compact(const float* logits, int32_t B, const int32
                  "select_compact: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, workspace_bytes);
 
   hipStream_t st = static_cast<hipStream_t>(stream);
-  int32_t* ws_kept = static_cast<int32_t*>(workspace);
-  int32_t* ws_counts =
-      reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + round_up(static_cast<size_t>(sumN) * 4, 256));
-
-  int32_t* ws_ticket = ws_counts + round_up(static_cast<size_t>(B) * 4, 256) / 4;
-  int32_t* ws_sync = ws_ticket + 256 / 4;
+  char* ws = static_cast<char*>(workspace);
+  int32_t* ws_ticket = reinterpret_cast<int32_t*>(ws);
+  int32_t* ws_sync = reinterpret_cast<int32_t*>(ws + kTicketBytes);
+  int32_t* ws_counts = reinterpret_cast<int32_t*>(ws + kFixedBytes);
+  int32_t* ws_kept = reinterpret_cast<int32_t*>(ws + kFixedBytes + round_up(static_cast<size_t>(B) * 4, 256));
   const bool write_cache = K != nullptr;
   const int32_t cap = cache ? cache->max_pages_per_seq * cache->page_size : 0;
   SelectArgs sa{logits, seq_off, vis_start, vis_len, B, mode, keep_ratio, threshold, keep_mask, ws_kept, ws_counts,

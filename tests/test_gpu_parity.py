@@ -163,6 +163,43 @@ def test_select_compact_arrangements(launches):
         P.dllava_set_launch_override(P.LAUNCH_SELECT_LAUNCHES, 0)
 
 
+def test_select_compact_one_workspace_many_calls():
+    """Eighty calls in a row on ONE zero-filled workspace, the shape, the ratio and the mode changing from call to call
+    (three batches of different size; top-k in one launch, threshold in two): every call leaves the workspace's
+    hand-off words and counters at zero for the next, whatever ran before it.  Hidden rows only (the integers and one
+    copied tensor are what the hand-off can get wrong)."""
+    h = _H()
+    shapes = [
+        W.make("ws-a", "bf16", 64, 1, 64, 7, [3, 0, 1, 0, 2, 5, 0], [300, 40, 0, 1290, 17, 64, 2], [9, 2, 5, 0, 1, 0, 3], 0.2, 0),
+        W.make("ws-b", "bf16", 64, 1, 64, 2, [0, 1], [4200, 33], [1, 1], 0.2, 0),
+        W.make("ws-c", "bf16", 64, 1, 64, 40, 2, 70, 3, 0.2, 0),
+    ]
+    paths, scores = [], []
+    for i, w in enumerate(shapes):
+        pre = W.prefill_inputs(w)
+        paths.append((w, pre, h.GpuPath(w, pre, None, extra_tokens=max(w.seq_len))))
+        D = rng.normal(77 + i, "ws.D", (int(sum(w.n_vis)), 2)).astype(np.float32)
+        scores.append(np.round(D * 8) / 8)
+    ws = torch.zeros(max(P.dllava_select_compact_workspace(w.B, w.sumN) for w in shapes), dtype=torch.uint8, device=h.DEV)
+    rs = np.random.RandomState(5)
+    for call in range(80):
+        i = int(rs.randint(len(shapes)))
+        w, pre, g = paths[i]
+        g.ws_select = ws
+        mode = R.TOPK if rs.rand() < 0.75 else R.THRESHOLD
+        ratio = float(rs.choice([0.0, 0.05, 0.2, 0.5, 0.93, 1.0]))
+        theta = float(rs.choice([0.0, 0.3, -0.5]))
+        mask, idx, off = R.select(scores[i], w.seq_off, w.vis_start, w.vis_len, mode, ratio, theta)
+        out = g.select_compact(torch.from_numpy(scores[i]).to(h.DEV), mode, ratio, theta, with_q=False, with_kv=False)
+        total = int(off[-1])
+        assert np.array_equal(out["out_off"].cpu().numpy(), off), call
+        assert np.array_equal(out["keep_mask"].cpu().numpy(), mask), call
+        assert np.array_equal(out["kept_idx"].cpu().numpy()[:total], idx), call
+        src = np.concatenate([w.seq_off[b] + idx[off[b]:off[b + 1]] for b in range(w.B)]).astype(np.int64)
+        assert np.array_equal(h.bits(out["hidden_out"])[:total], pre["hidden"][src]), call
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("B", [255, 256, 257, 300])
 def test_select_compact_many_sequences(B):
     """Top-k over more and fewer sequences than the arrangement with analytic offsets takes (256): short ragged
