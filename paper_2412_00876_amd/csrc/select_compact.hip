@@ -716,7 +716,7 @@ __global__ __launch_bounds__(kThreads) void select_compact_topk_kernel(SelectArg
     if (tid == 0) g.kept_idx[place.j] = rel;
     copy_row(g, b, place.pos, static_cast<size_t>(place.s0) + rel, place.j);
   }
-  // (every thread's load of the kept position has returned: copy_row used it)
+  // (only this thread read the hand-off words, before the barrier above; the kept positions themselves stay)
   if (tid == 0) {
     bool last_of_group = true;
     if (copies) {
