@@ -106,7 +106,9 @@ const char* dllava_last_error(void);
  *                                compute unit; 4 .. 8 = 256 units x 32*value tokens, one block per compute unit
  *   DLLAVA_LAUNCH_QKV_TILE       the same for the projection kernel of dllava_qkv_project
  *   DLLAVA_LAUNCH_SELECT_LAUNCHES 1 = dllava_select_compact in top-k mode as one launch (selection and copies side by
- *                                side; what it picks for up to 256 sequences), 2 = selection, then the copies
+ *                                side; what it picks for up to 256 sequences), 2 = selection, then the copies,
+ *                                3 = one launch in which the selection blocks stand back, so that a copying block
+ *                                whose patience runs out (milliseconds) selects instead: the hand-off's fallback
  * The library reads no environment variables.
  */
 typedef enum {

@@ -73,6 +73,7 @@ struct SelectArgs {
   int32_t cap;         // tokens a sequence's pages can hold
   int32_t* err_flag;
   int32_t* ws_sync;    // top-k arrangement: [3][kLayoutSeqs] claim / ready / done words, zero between calls
+  int32_t stand_back;  // tests: the selection blocks of sequences with kept vision rows leave the selection to a copying block
 };
 
 constexpr int kKeyCache = 4096;  // scores of one vision span kept in LDS (16 KiB); longer spans re-read them
@@ -689,7 +690,10 @@ __global__ __launch_bounds__(kThreads) void select_compact_topk_kernel(SelectArg
   if (tid == 0) {
     int state = -1;
     if (!copies) {
-      state = __hip_atomic_exchange(&claim[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0 ? 1 : 0;
+      // (stand_back: as if this block had not been dispatched yet -- the path a copying block takes when its patience
+      // runs out is then the one that selects; a sequence without kept vision rows has no copying block to do it)
+      if (a.stand_back && k > 0) state = 0;
+      else state = __hip_atomic_exchange(&claim[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0 ? 1 : 0;
     } else {
       for (int spins = 0; state < 0; ++spins) {
         if (__hip_atomic_load(&ready[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) state = 0;
@@ -806,7 +810,8 @@ extern "C" int dllava_select_compact(const float* logits, int32_t B, const int32
   const bool write_cache = K != nullptr;
   const int32_t cap = cache ? cache->max_pages_per_seq * cache->page_size : 0;
   SelectArgs sa{logits, seq_off, vis_start, vis_len, B, mode, keep_ratio, threshold, keep_mask, ws_kept, ws_counts,
-                ws_ticket, out_off, write_cache ? cache->cache_len : nullptr, cap, err_flag, ws_sync};
+                ws_ticket, out_off, write_cache ? cache->cache_len : nullptr, cap, err_flag, ws_sync,
+                launch_override(DLLAVA_LAUNCH_SELECT_LAUNCHES) == 3};
   const bool analytic =
       mode == DLLAVA_MODE_TOPK && B <= kLayoutSeqs && sumN > 0 && launch_override(DLLAVA_LAUNCH_SELECT_LAUNCHES) != 2;
   if (!analytic) {

@@ -143,6 +143,25 @@ def test_select_large_and_degenerate_segments(n_vis, ratio):
     _check_select_compact(g, w, pre, D, R.THRESHOLD, ratio, 0.1)
 
 
+def test_select_compact_hand_off_fallback():
+    """The one-launch top-k arrangement when a sequence's selection block does not show up: its copying blocks poll,
+    lose patience after a few milliseconds, one of them claims the sequence and runs the selection itself, the others
+    go on polling until it is ready.  Forced from the host (the selection blocks stand back); results, and the
+    workspace left behind for an ordinary call, must be the same."""
+    h = _H()
+    w = W.make("fallback", "bf16", 128, 2, 64, 4, [3, 0, 1, 2], [300, 0, 45, 4200], [5, 2, 0, 9], 0.2, 0)
+    pre = W.prefill_inputs(w)
+    g = h.GpuPath(w, pre, None, extra_tokens=max(w.seq_len))
+    D = rng.normal(31, "fb.D", (int(sum(w.n_vis)), 2)).astype(np.float32)
+    for mode in (3, 0, 3):
+        P.dllava_set_launch_override(P.LAUNCH_SELECT_LAUNCHES, mode)
+        try:
+            for ratio in (0.2, 0.7, 0.0):
+                _check_select_compact(g, w, pre, D, R.TOPK, ratio, 0.0)
+        finally:
+            P.dllava_set_launch_override(P.LAUNCH_SELECT_LAUNCHES, 0)
+
+
 @pytest.mark.parametrize("launches", [1, 2])
 def test_select_compact_arrangements(launches):
     """Both arrangements of the top-k path forced on the same inputs (selection and copies in one launch, or one
