@@ -4,8 +4,8 @@ with the deferred append, the final commit), recorded once and replayed, against
 Integer work is compared in full at every step: the keep decision of every (step, sequence), the kept indices, the
 final cache lengths and every byte of the pages after the last step.  Floating outputs are compared where the oracle
 can follow: the decode logits of all sequences and the attention outputs of a few (sequence, head) pairs at the first
-64 steps, the last 64 and every 16th (every 32nd of 2048) in between (the oracle's cache is advanced at EVERY step, so a sampled step sees
-the cache exactly as long as the run made it).  Replays must agree with each other bit for bit."""
+64 steps, the last 64 and every 16th (every 32nd of 2048) in between (the oracle's cache is advanced at EVERY step, so
+a sampled step sees the cache exactly as long as the run made it).  Replays must agree with each other bit for bit."""
 import numpy as np
 import pytest
 import torch
